@@ -1,0 +1,159 @@
+"""Python face of the CPU oracle.  TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke
+check and by the benchmark's cpu_baseline leg, never by the product package.
+
+Linear layer (paper section 2.2, W4A16 with group size 128): thin ctypes wrappers around the C
+file next to this one, which carries the definition (unpack, exact fp32 dequantisation, fp32
+k-ascending sum with an fp64 shadow, round-to-nearest-even fp16).
+
+Tree-verify attention (paper section 2.1: the target model scores all n draft-tree tokens in one
+forward pass; a draft token may attend to the committed prefix, to itself and to its ancestors in
+the tree): plain numpy in fp64, written below.
+
+Pin status.  The paper prints no worked numerical example for either operation, so beyond the
+pins in tests/test_oracle_*.py (nibble-order fixtures, round trips, closed forms, exact rational
+brute force, numpy/torch library cross-checks, structural invariants) the numerics are unpinned
+by the paper and this oracle is the definition.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        L = ctypes.CDLL(path)
+        vp, i = ctypes.c_void_p, ctypes.c_int
+        L.orc_f16_to_f32.restype = ctypes.c_float
+        L.orc_f16_to_f32.argtypes = [ctypes.c_uint16]
+        L.orc_f32_to_f16.restype = ctypes.c_uint16
+        L.orc_f32_to_f16.argtypes = [ctypes.c_float]
+        L.orc_f16_to_f32_array.argtypes = [vp, vp, ctypes.c_size_t]
+        L.orc_f32_to_f16_array.argtypes = [vp, vp, ctypes.c_size_t]
+        L.orc_unpack_codes.argtypes = [vp, vp, i, i]
+        L.orc_unpack_zeros.argtypes = [vp, vp, i, i]
+        L.orc_dequant.argtypes = [vp, vp, vp, vp, i, i, i]
+        L.orc_matmul.argtypes = [vp, vp, vp, vp, vp, i, i, i]
+        L.orc_gemm.argtypes = [vp] * 8 + [i] * 4
+        L.orc_set_threads.restype = i
+        L.orc_set_threads.argtypes = [i]
+        for name in ("orc_f16_to_f32_array", "orc_f32_to_f16_array", "orc_unpack_codes",
+                     "orc_unpack_zeros", "orc_dequant", "orc_matmul", "orc_gemm"):
+            getattr(L, name).restype = None
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray) -> ctypes.c_void_p:
+    assert a.flags["C_CONTIGUOUS"]
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def set_threads(n: int) -> int:
+    """n > 0 sets the OpenMP thread count; returns the count in effect."""
+    return int(lib().orc_set_threads(int(n)))
+
+
+def f16_to_f32(h: np.ndarray) -> np.ndarray:
+    h = np.ascontiguousarray(h).view(np.uint16)
+    out = np.empty(h.shape, dtype=np.float32)
+    lib().orc_f16_to_f32_array(_p(h), _p(out), h.size)
+    return out
+
+
+def f32_to_f16(f: np.ndarray) -> np.ndarray:
+    f = np.ascontiguousarray(f, dtype=np.float32)
+    out = np.empty(f.shape, dtype=np.uint16)
+    lib().orc_f32_to_f16_array(_p(f), _p(out), f.size)
+    return out.view(np.float16)
+
+
+def unpack_codes(qweight: np.ndarray) -> np.ndarray:
+    """int32 [K/8, N] -> uint8 [K, N]"""
+    qweight = np.ascontiguousarray(qweight, dtype=np.int32)
+    K, N = qweight.shape[0] * 8, qweight.shape[1]
+    q = np.empty((K, N), dtype=np.uint8)
+    lib().orc_unpack_codes(_p(qweight), _p(q), K, N)
+    return q
+
+
+def unpack_zeros(qzeros: np.ndarray) -> np.ndarray:
+    """int32 [K/G, N/8] -> uint8 [K/G, N]"""
+    qzeros = np.ascontiguousarray(qzeros, dtype=np.int32)
+    R, N = qzeros.shape[0], qzeros.shape[1] * 8
+    z = np.empty((R, N), dtype=np.uint8)
+    lib().orc_unpack_zeros(_p(qzeros), _p(z), R, N)
+    return z
+
+
+def dequant(qweight: np.ndarray, scales: np.ndarray, qzeros: np.ndarray, G: int = 128) -> np.ndarray:
+    """-> fp32 [K, N], w = (q - z) * s, exact"""
+    qweight = np.ascontiguousarray(qweight, dtype=np.int32)
+    qzeros = np.ascontiguousarray(qzeros, dtype=np.int32)
+    scales = np.ascontiguousarray(scales, dtype=np.float16)
+    K, N = qweight.shape[0] * 8, qweight.shape[1]
+    assert scales.shape == (K // G, N) and qzeros.shape == (K // G, N // 8)
+    W = np.empty((K, N), dtype=np.float32)
+    lib().orc_dequant(_p(qweight), _p(scales.view(np.uint16)), _p(qzeros), _p(W), N, K, G)
+    return W
+
+
+def matmul(x: np.ndarray, W: np.ndarray, want64: bool = True):
+    """x fp16 [M, K], W fp32 [K, N] -> (y32, y64 or None, y16)"""
+    x = np.ascontiguousarray(x, dtype=np.float16)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    M, K = x.shape
+    N = W.shape[1]
+    assert W.shape[0] == K
+    y32 = np.empty((M, N), dtype=np.float32)
+    y64 = np.empty((M, N), dtype=np.float64) if want64 else None
+    y16 = np.empty((M, N), dtype=np.uint16)
+    lib().orc_matmul(_p(x.view(np.uint16)), _p(W), _p(y32), _p(y64) if want64 else None, _p(y16), M, N, K)
+    return y32, y64, y16.view(np.float16)
+
+
+def w4a16_gemm(x, qweight, scales, qzeros, G: int = 128, want64: bool = True):
+    """The whole layer: returns (y32, y64 or None, y16)."""
+    W = dequant(qweight, scales, qzeros, G)
+    return matmul(x, W, want64)
+
+
+# ---------------------------------------------------------------------------------------------
+# tree-verify attention, fp64
+
+
+def tree_verify_attn(q, k, v, mask, scale: float | None = None):
+    """q fp16 [M, Hq, D]; k, v fp16 [P+M, Hkv, D]; mask [M, M] (non-zero = visible).
+    Query row i of head h attends, through KV head h // (Hq/Hkv), to all P prefix keys and to the
+    draft keys j with mask[i, j] != 0.  Returns (out64 [M, Hq, D] fp64, out16 fp16)."""
+    q = np.asarray(q)
+    k = np.asarray(k)
+    v = np.asarray(v)
+    mask = np.asarray(mask)
+    M, Hq, D = q.shape
+    T, Hkv, _ = k.shape
+    P = T - M
+    assert P >= 0 and mask.shape == (M, M) and Hq % Hkv == 0
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    rep = Hq // Hkv
+    q64, k64, v64 = q.astype(np.float64), k.astype(np.float64), v.astype(np.float64)
+    out = np.zeros((M, Hq, D), dtype=np.float64)
+    for i in range(M):
+        visible = np.concatenate([np.ones(P, dtype=bool), mask[i] != 0])
+        for h in range(Hq):
+            kh = h // rep
+            logits = scale * (k64[visible, kh, :] @ q64[i, h, :])
+            logits -= logits.max()
+            p = np.exp(logits)
+            p /= p.sum()
+            out[i, h, :] = p @ v64[visible, kh, :]
+    return out, out.astype(np.float16)
