@@ -1,0 +1,116 @@
+/*
+ * libw4a16 -- C ABI of the MI355X (gfx950) W4A16 small-M linear layer and tree-verify attention.
+ *
+ * The computation is the group-wise 4-bit-weight / 16-bit-activation linear layer of a quantised
+ * target model (paper section 2.2, "W4A16": 4-bit weights, group size 128, fp16 activations) run
+ * at the token counts speculative decoding produces (paper section 2.1: M = 1 for plain decoding,
+ * M = draft length + 1 for a sequence draft, M = tree size n for a tree draft), plus the attention
+ * of the tree-verification pass.
+ *
+ * Conventions that hold for every entry point unless stated otherwise
+ *   - every pointer is a DEVICE pointer owned by the caller; the library never allocates, frees,
+ *     retains or synchronises on caller memory;
+ *   - fp16 buffers are passed as `const void*` / `void*` (IEEE binary16, row-major);
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); the work is enqueued
+ *     on it and the call returns without waiting;
+ *   - the return value is W4A16_OK or a negative W4A16_E* code; arguments are validated before any
+ *     GPU call, so an invalid call enqueues nothing; nothing is printed, nothing aborts;
+ *   - all pointers must be 16-byte aligned; buffers must not overlap;
+ *   - the same inputs give bit-identical outputs on every call (no atomically ordered sums).
+ */
+#ifndef W4A16_H
+#define W4A16_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define W4A16_OK 0
+#define W4A16_EINVAL (-1)     /* bad shape or argument value */
+#define W4A16_ENULL (-2)      /* a required pointer is NULL */
+#define W4A16_EALIGN (-3)     /* a pointer is not 16-byte aligned */
+#define W4A16_EUNSUP (-4)     /* valid but not implemented (group size other than 128, M > 64, ...) */
+#define W4A16_EWORKSPACE (-5) /* workspace missing or smaller than the *_workspace_bytes() value */
+#define W4A16_EHIP (-6)       /* the HIP runtime reported an error while enqueuing */
+
+#define W4A16_MAX_M 64
+
+/* Library version, major*10000 + minor*100 + patch. */
+int w4a16_version(void);
+
+/* Static, NUL-terminated description of a return code. */
+const char *w4a16_strerror(int code);
+
+/* Ablation knob for benchmarks and tests: overrides an internal launch heuristic process-wide.
+ * Names: "split_k" (0 = heuristic, else forced number of K splits), "fused_reduce" (1 = the last
+ * workgroup of a column block sums the split-K partials inside the GEMM kernel, 0 = a second
+ * kernel does), "wgs_per_cu" (target resident workgroups per compute unit used by the heuristic).
+ * Returns W4A16_EINVAL for an unknown name or an out-of-range value.  Not thread-safe. */
+int w4a16_set_param(const char *name, int value);
+int w4a16_get_param(const char *name);
+
+/* Size in bytes of the opaque packed weight buffer for an N-column, K-row weight with group size G
+ * (it holds the 4-bit codes, the fp16 scales and the 4-bit zero-points; columns are padded up to a
+ * multiple of 128 inside the buffer).  0 if the shape is not supported. */
+size_t w4a16_packed_bytes(int N, int K, int G);
+
+/* Bytes of scratch w4a16_gemm may need for any 1 <= M <= M_max at this shape (split-K partial sums
+ * and their tickets).  Never 0 for a supported shape. */
+size_t w4a16_workspace_bytes(int M_max, int N, int K, int G);
+
+/* Zero the ticket area at the start of a workspace.  Must be enqueued once before the first
+ * w4a16_gemm / tree_verify_attn that uses the buffer; each of those calls leaves the tickets zero
+ * again, so one initialisation serves any number of later calls (of any shape that fits).  Two
+ * calls that may run concurrently must not share a workspace. */
+int w4a16_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/* Re-lay the canonical quantised weight into the streaming layout the GEMM kernels read
+ * (paper section 2.2 fixes the scheme -- 4-bit codes, one scale and one zero-point per group of
+ * 128 rows per column; the canonical storage is
+ *   qweight int32 [K/8, N]   code of row k in bits 4*(k%8)..4*(k%8)+3 of word [k/8, n]
+ *   scales  fp16  [K/G, N]
+ *   qzeros  int32 [K/G, N/8] zero-point of column n in bits 4*(n%8)..+3 of word [g, n/8]).
+ * `packed` receives w4a16_packed_bytes(N, K, G) bytes.  Requires G == 128, K % 128 == 0,
+ * N % 8 == 0.  Exactly invertible by w4a16_unpack. */
+int w4a16_pack(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
+               int N, int K, int G, void *stream);
+
+/* Exact inverse of w4a16_pack: recovers the three canonical tensors bit for bit. */
+int w4a16_unpack(const void *packed, int32_t *qweight, void *scales, int32_t *qzeros,
+                 int N, int K, int G, void *stream);
+
+/* Test export: dequantise the packed weight to a dense fp32 matrix W [K, N] row-major,
+ * W[k,n] = (float)(q[k,n] - z[k/G,n]) * (float)s[k/G,n].  The product is exact in fp32, so the
+ * result is defined bit for bit. */
+int w4a16_dequant(const void *packed, float *W, int N, int K, int G, void *stream);
+
+/* y[M,N] (fp16) = x[M,K] (fp16) . dequant(packed)[K,N], accumulated in fp32 and rounded to fp16
+ * with round-to-nearest-even (paper section 2.2 for the layer; section 2.1 and the verification
+ * analysis of section 3 for the values of M).  1 <= M <= 64; rows >= M of x and y are never
+ * touched; y is overwritten.  `workspace` must hold w4a16_workspace_bytes(M, N, K, G) bytes and
+ * have been initialised with w4a16_workspace_init. */
+int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, int G,
+               void *workspace, size_t workspace_bytes, void *stream);
+
+/* Scratch needed by tree_verify_attn for these sizes (partial softmax states of the key splits). */
+size_t tree_verify_attn_workspace_bytes(int M, int P, int Hq, int Hkv, int D);
+
+/* Attention of the tree-verification pass (paper section 2.1: the target model scores the n
+ * draft-tree tokens in one forward pass).  Query row i of head h attends, through KV head
+ * h / (Hq/Hkv), to the P committed prefix keys and to the draft keys j with mask[i*M + j] != 0:
+ *   out[i,h,:] = sum_j softmax_j(scale * q[i,h,:].k[j,kvh,:]) * v[j,kvh,:]
+ * q, out fp16 [M, Hq, D]; k, v fp16 [P+M, Hkv, D] (draft keys at rows P..P+M-1); mask uint8 [M, M]
+ * row-major.  Softmax and accumulation in fp32.  Requires D == 128, 1 <= M <= 64, Hq % Hkv == 0,
+ * Hq/Hkv <= 8, P >= 0, and every row must see at least one key.  `workspace` as for w4a16_gemm,
+ * sized by tree_verify_attn_workspace_bytes and initialised by w4a16_workspace_init. */
+int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t *mask, void *out,
+                     int M, int P, int Hq, int Hkv, int D, float scale,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W4A16_H */

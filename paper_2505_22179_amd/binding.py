@@ -1,0 +1,144 @@
+"""ctypes binding of libw4a16.so: argument marshalling only.  Every function has the name of
+the C entry point it forwards to (include/w4a16.h); tensors are torch CUDA tensors used purely
+as device buffers, and the work is enqueued on torch's current stream.  There is no fallback: if
+the library has not been built, loading raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libw4a16.so")
+
+EXPORTS = (
+    "w4a16_version", "w4a16_strerror", "w4a16_set_param", "w4a16_get_param", "w4a16_packed_bytes",
+    "w4a16_workspace_bytes", "w4a16_workspace_init", "w4a16_pack", "w4a16_unpack", "w4a16_dequant",
+    "w4a16_gemm", "tree_verify_attn_workspace_bytes", "tree_verify_attn",
+)
+
+_lib = None
+
+
+class W4A16Error(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+def load() -> ctypes.CDLL:
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2505_22179_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.w4a16_version.restype = i
+    L.w4a16_strerror.restype = ctypes.c_char_p
+    L.w4a16_strerror.argtypes = [i]
+    L.w4a16_set_param.argtypes = [ctypes.c_char_p, i]
+    L.w4a16_get_param.argtypes = [ctypes.c_char_p]
+    L.w4a16_packed_bytes.restype = sz
+    L.w4a16_packed_bytes.argtypes = [i, i, i]
+    L.w4a16_workspace_bytes.restype = sz
+    L.w4a16_workspace_bytes.argtypes = [i, i, i, i]
+    L.w4a16_workspace_init.argtypes = [vp, sz, vp]
+    L.w4a16_pack.argtypes = [vp, vp, vp, vp, i, i, i, vp]
+    L.w4a16_unpack.argtypes = [vp, vp, vp, vp, i, i, i, vp]
+    L.w4a16_dequant.argtypes = [vp, vp, i, i, i, vp]
+    L.w4a16_gemm.argtypes = [vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.tree_verify_attn_workspace_bytes.restype = sz
+    L.tree_verify_attn_workspace_bytes.argtypes = [i, i, i, i, i]
+    L.tree_verify_attn.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, ctypes.c_float, vp, sz, vp]
+    _lib = L
+    return L
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(code: int, where: str) -> None:
+    if code != 0:
+        raise W4A16Error(code, where)
+
+
+def w4a16_version() -> int:
+    return load().w4a16_version()
+
+
+def strerror(code: int) -> str:
+    return load().w4a16_strerror(code).decode()
+
+
+def w4a16_set_param(name: str, value: int) -> None:
+    _check(load().w4a16_set_param(name.encode(), int(value)), "w4a16_set_param")
+
+
+def w4a16_get_param(name: str) -> int:
+    return load().w4a16_get_param(name.encode())
+
+
+def w4a16_packed_bytes(N: int, K: int, G: int = 128) -> int:
+    return load().w4a16_packed_bytes(N, K, G)
+
+
+def w4a16_workspace_bytes(M_max: int, N: int, K: int, G: int = 128) -> int:
+    return load().w4a16_workspace_bytes(M_max, N, K, G)
+
+
+def tree_verify_attn_workspace_bytes(M: int, P: int, Hq: int, Hkv: int, D: int) -> int:
+    return load().tree_verify_attn_workspace_bytes(M, P, Hq, Hkv, D)
+
+
+def w4a16_workspace_init(workspace) -> None:
+    _check(load().w4a16_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+           "w4a16_workspace_init")
+
+
+def new_workspace(nbytes: int, device="cuda"):
+    """Allocate and initialise a workspace of at least nbytes."""
+    ws = torch.empty(max(int(nbytes), 16384), dtype=torch.uint8, device=device)
+    w4a16_workspace_init(ws)
+    return ws
+
+
+def w4a16_pack(qweight, scales, qzeros, packed, N: int, K: int, G: int = 128) -> None:
+    _check(load().w4a16_pack(_ptr(qweight), _ptr(scales), _ptr(qzeros), _ptr(packed), N, K, G, _stream()), "w4a16_pack")
+
+
+def w4a16_unpack(packed, qweight, scales, qzeros, N: int, K: int, G: int = 128) -> None:
+    _check(load().w4a16_unpack(_ptr(packed), _ptr(qweight), _ptr(scales), _ptr(qzeros), N, K, G, _stream()), "w4a16_unpack")
+
+
+def w4a16_dequant(packed, W, N: int, K: int, G: int = 128) -> None:
+    _check(load().w4a16_dequant(_ptr(packed), _ptr(W), N, K, G, _stream()), "w4a16_dequant")
+
+
+def w4a16_gemm(x, packed, y, M: int, N: int, K: int, G: int, workspace) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().w4a16_gemm(_ptr(x), _ptr(packed), _ptr(y), M, N, K, G, _ptr(workspace), nbytes, _stream()), "w4a16_gemm")
+
+
+def tree_verify_attn(q, k, v, mask, out, M: int, P: int, Hq: int, Hkv: int, D: int, scale: float, workspace) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().tree_verify_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(mask), _ptr(out), M, P, Hq, Hkv, D,
+                                   float(scale), _ptr(workspace), nbytes, _stream()), "tree_verify_attn")
+
+
+# ---- conveniences for tests and the benchmark (still marshalling only) ----
+
+def pack_from_numpy(inp, device="cuda"):
+    """Upload a LinearInputs' canonical tensors and return the packed device buffer."""
+    qw = torch.from_numpy(inp.qweight).to(device)
+    sc = torch.from_numpy(inp.scales).to(device)
+    qz = torch.from_numpy(inp.qzeros).to(device)
+    packed = torch.empty(w4a16_packed_bytes(inp.N, inp.K, inp.G), dtype=torch.uint8, device=device)
+    w4a16_pack(qw, sc, qz, packed, inp.N, inp.K, inp.G)
+    return packed

@@ -1,0 +1,39 @@
+// Host-side helpers shared by the entry points (argument checks, launch error mapping, knobs).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/w4a16.h"
+#include "layout.h"
+
+namespace w4 {
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// shape checks common to every weight entry point; returns W4A16_OK or an error code
+inline int check_weight_shape(int N, int K, int G)
+{
+    if (N <= 0 || K <= 0 || G <= 0) return W4A16_EINVAL;
+    if (K % G != 0 || N % 8 != 0) return W4A16_EINVAL;
+    if (G != kGroup) return W4A16_EUNSUP;
+    if ((long long)pad_cols(N) / kBlockCols * (K / kGroup) > (1ll << 30)) return W4A16_EUNSUP;
+    return W4A16_OK;
+}
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? W4A16_OK : W4A16_EHIP;
+}
+
+struct Params {
+    int split_k = 0;       // 0 = heuristic
+    int fused_reduce = 1;
+    int wgs_per_cu = 0;    // 0 = heuristic
+    int attn_splits = 0;   // 0 = heuristic
+};
+Params &params();
+
+// number of 256-byte-aligned bytes reserved for tickets at the start of a workspace
+constexpr size_t kTicketBytes = 16384;   // 4096 tickets
+constexpr int kMaxTickets = 4096;
+
+}  // namespace w4

@@ -1,0 +1,236 @@
+// w4a16_pack / w4a16_unpack / w4a16_dequant: layout conversion kernels (offline, not on the timed
+// path) and the bit-exact dequantisation test export.  See layout.h for the packed layout and
+// include/w4a16.h for the contracts.
+#include "internal.h"
+#include <hip/hip_fp16.h>
+#include <string.h>
+
+namespace w4 {
+
+__device__ __forceinline__ uint32_t permute_fields_to_packed(uint32_t canon)
+{
+    uint32_t out = 0;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) out |= ((canon >> (4 * p)) & 0xFu) << (4 * field_of_p(p));
+    return out;
+}
+
+__device__ __forceinline__ uint32_t permute_fields_to_canonical(uint32_t packed)
+{
+    uint32_t out = 0;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) out |= ((packed >> (4 * field_of_p(p))) & 0xFu) << (4 * p);
+    return out;
+}
+
+// one thread per (record, tile, lane): writes the lane's 16 bytes of codes; threads with t == 0
+// and r == 0 also write the record's scales and zero-points for their column index c.
+__global__ void pack_kernel(const uint32_t *__restrict__ qweight, const uint16_t *__restrict__ scales,
+                            const uint32_t *__restrict__ qzeros, uint8_t *__restrict__ packed,
+                            int N, int K, long long total)
+{
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int groups = K / kGroup;
+    int lane = (int)(idx & 63);
+    int t = (int)((idx >> 6) & 7);
+    long long rec = idx >> 9;
+    int g = (int)(rec % groups);
+    int nb = (int)(rec / groups);
+    int r = lane >> 4, c = lane & 15;
+    int n = nb * kBlockCols + t * 16 + c;
+    uint8_t *base = packed + record_offset(nb, g, groups);
+    uint4 w = make_uint4(0, 0, 0, 0);
+    if (n < N) {
+        uint32_t v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int kw = g * 16 + j * 4 + r;  // canonical word row: rows 8*kw .. 8*kw+7
+            v[j] = permute_fields_to_packed(qweight[(size_t)kw * N + n]);
+        }
+        w = make_uint4(v[0], v[1], v[2], v[3]);
+    }
+    *reinterpret_cast<uint4 *>(base + t * 1024 + lane * 16) = w;
+    if (r == 0) {
+        uint16_t s = (n < N) ? scales[(size_t)g * N + n] : (uint16_t)0;
+        *reinterpret_cast<uint16_t *>(base + kScalesOff + c * 16 + t * 2) = s;
+        if (t == 0) {
+            uint32_t zw = 0;
+#pragma unroll
+            for (int tt = 0; tt < 8; ++tt) {
+                int nn = nb * kBlockCols + tt * 16 + c;
+                uint32_t z = 0;
+                if (nn < N) z = (qzeros[(size_t)g * (N / 8) + (nn >> 3)] >> (4 * (nn & 7))) & 0xFu;
+                zw |= z << (4 * tt);
+            }
+            *reinterpret_cast<uint32_t *>(base + kZerosOff + c * 4) = zw;
+        }
+    }
+}
+
+// one thread per canonical qweight word [kw, n]; the first K/128 rows of threads also restore
+// scales, and threads with n % 8 == 0 restore a qzeros word.
+__global__ void unpack_kernel(const uint8_t *__restrict__ packed, uint32_t *__restrict__ qweight,
+                              uint16_t *__restrict__ scales, uint32_t *__restrict__ qzeros,
+                              int N, int K, long long total)
+{
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int groups = K / kGroup;
+    int n = (int)(idx % N);
+    int kw = (int)(idx / N);
+    int g = kw >> 4, j = (kw >> 2) & 3, r = kw & 3;
+    int nb = n / kBlockCols, t = (n % kBlockCols) >> 4, c = n & 15;
+    const uint8_t *base = packed + record_offset(nb, g, groups);
+    uint32_t pw = *reinterpret_cast<const uint32_t *>(base + t * 1024 + (r * 16 + c) * 16 + j * 4);
+    qweight[(size_t)kw * N + n] = permute_fields_to_canonical(pw);
+    if ((kw & 15) == 0) {
+        scales[(size_t)g * N + n] = *reinterpret_cast<const uint16_t *>(base + kScalesOff + c * 16 + t * 2);
+        if ((n & 7) == 0) {
+            uint32_t zw = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {  // columns n .. n+7 share nb and t; c runs over c .. c+7
+                uint32_t pz = *reinterpret_cast<const uint32_t *>(base + kZerosOff + (c + i) * 4);
+                zw |= ((pz >> (4 * t)) & 0xFu) << (4 * i);
+            }
+            qzeros[(size_t)g * (N / 8) + (n >> 3)] = zw;
+        }
+    }
+}
+
+// one thread per element W[k, n]
+__global__ void dequant_kernel(const uint8_t *__restrict__ packed, float *__restrict__ W,
+                               int N, int K, long long total)
+{
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int groups = K / kGroup;
+    int n = (int)(idx % N);
+    int k = (int)(idx / N);
+    int g = k / kGroup, kk = k % kGroup;
+    int j = kk >> 5, r = (kk >> 3) & 3, p = kk & 7;
+    int nb = n / kBlockCols, t = (n % kBlockCols) >> 4, c = n & 15;
+    const uint8_t *base = packed + record_offset(nb, g, groups);
+    uint32_t pw = *reinterpret_cast<const uint32_t *>(base + t * 1024 + (r * 16 + c) * 16 + j * 4);
+    int q = (int)((pw >> (4 * field_of_p(p))) & 0xFu);
+    uint32_t pz = *reinterpret_cast<const uint32_t *>(base + kZerosOff + c * 4);
+    int z = (int)((pz >> (4 * t)) & 0xFu);
+    __half s = *reinterpret_cast<const __half *>(base + kScalesOff + c * 16 + t * 2);
+    W[idx] = (float)(q - z) * __half2float(s);
+}
+
+__global__ void fill_zero_kernel(uint32_t *p, size_t words)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < words) p[i] = 0u;
+}
+
+static Params g_params;
+Params &params() { return g_params; }
+
+}  // namespace w4
+
+using namespace w4;
+
+extern "C" {
+
+int w4a16_version(void) { return 100; }
+
+const char *w4a16_strerror(int code)
+{
+    switch (code) {
+    case W4A16_OK: return "ok";
+    case W4A16_EINVAL: return "invalid shape or argument";
+    case W4A16_ENULL: return "null pointer";
+    case W4A16_EALIGN: return "pointer not 16-byte aligned";
+    case W4A16_EUNSUP: return "unsupported configuration";
+    case W4A16_EWORKSPACE: return "workspace missing or too small";
+    case W4A16_EHIP: return "HIP runtime error";
+    default: return "unknown error code";
+    }
+}
+
+static int *param_slot(const char *name)
+{
+    if (!name) return nullptr;
+    Params &p = params();
+    if (!strcmp(name, "split_k")) return &p.split_k;
+    if (!strcmp(name, "fused_reduce")) return &p.fused_reduce;
+    if (!strcmp(name, "wgs_per_cu")) return &p.wgs_per_cu;
+    if (!strcmp(name, "attn_splits")) return &p.attn_splits;
+    return nullptr;
+}
+
+int w4a16_set_param(const char *name, int value)
+{
+    int *slot = param_slot(name);
+    if (!slot || value < 0 || value > 1024) return W4A16_EINVAL;
+    *slot = value;
+    return W4A16_OK;
+}
+
+int w4a16_get_param(const char *name)
+{
+    int *slot = param_slot(name);
+    return slot ? *slot : W4A16_EINVAL;
+}
+
+size_t w4a16_packed_bytes(int N, int K, int G)
+{
+    if (check_weight_shape(N, K, G) != W4A16_OK) return 0;
+    return (size_t)(pad_cols(N) / kBlockCols) * (size_t)(K / kGroup) * (size_t)kRecordBytes;
+}
+
+int w4a16_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return W4A16_ENULL;
+    if (misaligned(workspace)) return W4A16_EALIGN;
+    if (workspace_bytes < kTicketBytes) return W4A16_EWORKSPACE;
+    size_t words = kTicketBytes / 4;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, (uint32_t *)workspace, words);
+    return launch_status();
+}
+
+int w4a16_pack(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
+               int N, int K, int G, void *stream)
+{
+    int rc = check_weight_shape(N, K, G);
+    if (rc != W4A16_OK) return rc;
+    if (!qweight || !scales || !qzeros || !packed) return W4A16_ENULL;
+    if (misaligned(qweight) || misaligned(scales) || misaligned(qzeros) || misaligned(packed)) return W4A16_EALIGN;
+    long long total = (long long)(pad_cols(N) / kBlockCols) * (K / kGroup) * 512;
+    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint32_t *)qweight, (const uint16_t *)scales, (const uint32_t *)qzeros,
+                       (uint8_t *)packed, N, K, total);
+    return launch_status();
+}
+
+int w4a16_unpack(const void *packed, int32_t *qweight, void *scales, int32_t *qzeros,
+                 int N, int K, int G, void *stream)
+{
+    int rc = check_weight_shape(N, K, G);
+    if (rc != W4A16_OK) return rc;
+    if (!qweight || !scales || !qzeros || !packed) return W4A16_ENULL;
+    if (misaligned(qweight) || misaligned(scales) || misaligned(qzeros) || misaligned(packed)) return W4A16_EALIGN;
+    long long total = (long long)(K / 8) * N;
+    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint8_t *)packed, (uint32_t *)qweight, (uint16_t *)scales, (uint32_t *)qzeros,
+                       N, K, total);
+    return launch_status();
+}
+
+int w4a16_dequant(const void *packed, float *W, int N, int K, int G, void *stream)
+{
+    int rc = check_weight_shape(N, K, G);
+    if (rc != W4A16_OK) return rc;
+    if (!packed || !W) return W4A16_ENULL;
+    if (misaligned(packed) || misaligned(W)) return W4A16_EALIGN;
+    long long total = (long long)K * N;
+    if ((total + 255) / 256 > 0x7FFFFFFFll) return W4A16_EUNSUP;
+    hipLaunchKernelGGL(dequant_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint8_t *)packed, W, N, K, total);
+    return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every symbol the header
+declares, and rejects bad arguments before touching the GPU runtime."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_22179_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "w4a16.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:w4a16|tree_verify)_\w+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = B.load()
+    names = _declared()
+    assert "w4a16_gemm" in names and "tree_verify_attn" in names and "w4a16_pack" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_version_and_strerror():
+    assert B.w4a16_version() >= 100
+    assert B.strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert B.strerror(code) not in ("ok", "unknown error code")
+    assert B.strerror(-99) == "unknown error code"
+
+
+def test_sizes():
+    rec = 8192 + 256 + 64
+    assert B.w4a16_packed_bytes(4096, 4096) == 32 * 32 * rec
+    assert B.w4a16_packed_bytes(8, 128) == rec                 # padded to one 128-column block
+    assert B.w4a16_packed_bytes(136, 256) == 2 * 2 * rec
+    assert B.w4a16_packed_bytes(4096, 4096, 64) == 0            # group size other than 128
+    assert B.w4a16_packed_bytes(4096, 4100) == 0
+    assert B.w4a16_packed_bytes(4100, 4096) == 0
+    # minimal bytes per weight: 0.5 code + 2/128 scale + 0.5/128 zero
+    assert B.w4a16_packed_bytes(8192, 8192) / (8192 * 8192) == pytest.approx(0.51953125)
+    for shape in ((4096, 4096), (57344, 8192), (8192, 28672)):
+        assert B.w4a16_workspace_bytes(64, *shape) >= 16384
+    assert B.w4a16_workspace_bytes(65, 4096, 4096) == 0
+    assert B.tree_verify_attn_workspace_bytes(60, 2048, 64, 8, 128) > 16384
+    assert B.tree_verify_attn_workspace_bytes(60, 2048, 64, 8, 64) == 0
+
+
+def test_params():
+    B.w4a16_set_param("split_k", 3)
+    assert B.w4a16_get_param("split_k") == 3
+    B.w4a16_set_param("split_k", 0)
+    with pytest.raises(B.W4A16Error):
+        B.w4a16_set_param("no_such_knob", 1)
+    with pytest.raises(B.W4A16Error):
+        B.w4a16_set_param("split_k", -1)
+
+
+def test_argument_validation_happens_before_any_gpu_call():
+    lib = B.load()
+    a = 0x1000  # fake, aligned, never dereferenced: every call below must fail validation first
+    EINVAL, ENULL, EALIGN, EUNSUP, EWS = -1, -2, -3, -4, -5
+    g = lib.w4a16_gemm
+    assert g(a, a, a, 0, 4096, 4096, 128, a, 1 << 30, None) == EINVAL      # M = 0
+    assert g(a, a, a, 65, 4096, 4096, 128, a, 1 << 30, None) == EUNSUP     # M > 64
+    assert g(a, a, a, 1, 4096, 4000, 128, a, 1 << 30, None) == EINVAL      # K % G
+    assert g(a, a, a, 1, 4100, 4096, 128, a, 1 << 30, None) == EINVAL      # N % 8
+    assert g(a, a, a, 1, 4096, 4096, 64, a, 1 << 30, None) == EUNSUP       # G != 128
+    assert g(None, a, a, 1, 4096, 4096, 128, a, 1 << 30, None) == ENULL
+    assert g(a, None, a, 1, 4096, 4096, 128, a, 1 << 30, None) == ENULL
+    assert g(a, a, None, 1, 4096, 4096, 128, a, 1 << 30, None) == ENULL
+    assert g(a + 2, a, a, 1, 4096, 4096, 128, a, 1 << 30, None) == EALIGN
+    assert g(a, a, a, 1, 4096, 4096, 128, None, 0, None) == EWS            # split-K shape, no workspace
+    assert g(a, a, a, 1, 4096, 4096, 128, a, 100, None) == EWS
+    p = lib.w4a16_pack
+    assert p(None, a, a, a, 4096, 4096, 128, None) == ENULL
+    assert p(a, a, a, a + 4, 4096, 4096, 128, None) == EALIGN
+    assert p(a, a, a, a, 4096, 4096, 32, None) == EUNSUP
+    assert lib.w4a16_unpack(a, a, a, None, 4096, 4096, 128, None) == ENULL
+    assert lib.w4a16_dequant(a, None, 4096, 4096, 128, None) == ENULL
+    assert lib.w4a16_dequant(a, a, -1, 4096, 128, None) == EINVAL
+    assert lib.w4a16_workspace_init(None, 1 << 20, None) == ENULL
+    assert lib.w4a16_workspace_init(a, 16, None) == EWS
+    t = lib.tree_verify_attn
+    f = ctypes.c_float(0.1)
+    assert t(a, a, a, a, a, 60, 2048, 64, 8, 64, f, a, 1 << 30, None) == EUNSUP    # D != 128
+    assert t(a, a, a, a, a, 65, 2048, 64, 8, 128, f, a, 1 << 30, None) == EUNSUP   # M > 64
+    assert t(a, a, a, a, a, 60, 2048, 64, 7, 128, f, a, 1 << 30, None) == EINVAL   # Hq % Hkv
+    assert t(a, a, a, a, a, 0, 2048, 64, 8, 128, f, a, 1 << 30, None) == EINVAL
+    assert t(a, a, a, None, a, 60, 2048, 64, 8, 128, f, a, 1 << 30, None) == ENULL
+    assert t(a, a, a, a, a, 60, 2048, 64, 8, 128, f, None, 0, None) == EWS
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2505_22179_amd")
+    bad = re.compile(r"^\s*(from|import)\s+oracle\b|liboracle|w4a16_oracle|#include\s+\"[^\"]*oracle", re.M)
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h")):
+                assert not bad.search(open(os.path.join(dirpath, fn)).read()), (dirpath, fn)

@@ -1,0 +1,148 @@
+"""GPU: w4a16_gemm through the C ABI against the CPU oracle (paper section 2.2 layer at the token
+counts of section 2.1).  Tolerance: max |err| <= 1e-2 and relative Frobenius error <= 1e-3 against
+the oracle's fp32 result (see tests/parity.py for the fp16-ulp caveat); bit-exact where the
+arithmetic is exact in any order."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as R
+from paper_2505_22179_amd import binding as B
+from paper_2505_22179_amd import inputs as I
+from tests.parity import check_gemm, column_subproblem
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+SENTINEL = 1234.0
+
+
+@pytest.fixture(scope="module")
+def big_ws():
+    return B.new_workspace(256 << 20)
+
+
+@pytest.fixture(autouse=True)
+def _reset_knobs():
+    yield
+    for k in ("split_k", "wgs_per_cu"):
+        B.w4a16_set_param(k, 0)
+    B.w4a16_set_param("fused_reduce", 1)
+
+
+def run_gemm(inp, packed, ws, M=None, guard_rows=2):
+    """Returns fp16 y[M, N]; also checks that rows >= M of the y buffer are left untouched."""
+    M = inp.M if M is None else M
+    x = torch.from_numpy(inp.x[:M]).to(DEV).contiguous()
+    y = torch.full((M + guard_rows, inp.N), SENTINEL, dtype=torch.float16, device=DEV)
+    B.w4a16_gemm(x, packed, y, M, inp.N, inp.K, inp.G, ws)
+    torch.cuda.synchronize()
+    out = y.cpu().numpy()
+    assert (out[M:] == np.float16(SENTINEL)).all(), "rows >= M were written"
+    return out[:M]
+
+
+SMALL = [
+    # M, K, N  -- several column blocks, several groups per wavefront, ragged M and N tails
+    (1, 128, 8), (1, 4096, 4096), (3, 1024, 136), (4, 2048, 512), (8, 1536, 1000),
+    (16, 1024, 256), (17, 2048, 264), (32, 4096, 384), (33, 1024, 128), (48, 2048, 520),
+    (60, 4096, 256), (64, 2048, 1024), (64, 128, 128), (7, 14336, 256),
+]
+
+
+@pytest.mark.parametrize("M,K,N", SMALL)
+def test_parity_small(M, K, N, big_ws):
+    print(f"gemm parity M={M} K={K} N={N}", flush=True)
+    inp = I.make_linear(5000 + M * 7 + K + N, M, K, N)
+    packed = B.pack_from_numpy(inp)
+    y32, _, _ = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
+    for split, fused in ((0, 1), (1, 1), (3, 1), (2, 0), (0, 0)):
+        B.w4a16_set_param("split_k", split)
+        B.w4a16_set_param("fused_reduce", fused)
+        y = run_gemm(inp, packed, big_ws)
+        check_gemm(y, y32, f"M={M} K={K} N={N} split={split} fused={fused}")
+
+
+@pytest.mark.parametrize("M", [1, 5, 16, 31, 48, 64])
+def test_exact_inputs_bit_exact(M, big_ws):
+    # x in {-2..2}, scales 2^-7: every partial sum is exact in fp32 whatever the order, so every
+    # kernel variant must reproduce the oracle's fp16 output bit for bit
+    K, N = 3072, 392
+    print(f"gemm exact M={M}", flush=True)
+    inp = I.make_linear(6000 + M, M, K, N, x_kind="small_int", scale_kind="pow2")
+    packed = B.pack_from_numpy(inp)
+    _, _, y16 = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
+    for split, fused in ((0, 1), (1, 1), (4, 1), (6, 0)):
+        B.w4a16_set_param("split_k", split)
+        B.w4a16_set_param("fused_reduce", fused)
+        y = run_gemm(inp, packed, big_ws)
+        assert np.array_equal(y.view(np.uint16), y16.view(np.uint16)), (M, split, fused)
+
+
+def test_run_to_run_determinism_and_ticket_reuse(big_ws):
+    inp = I.make_linear(7001, 24, 8192, 2048)
+    packed = B.pack_from_numpy(inp)
+    first = run_gemm(inp, packed, big_ws)
+    for _ in range(6):   # the tickets must come back to zero after every call
+        again = run_gemm(inp, packed, big_ws)
+        assert np.array_equal(again.view(np.uint16), first.view(np.uint16))
+    other = I.make_linear(7002, 9, 4096, 1024)
+    y32, _, _ = R.w4a16_gemm(other.x, other.qweight, other.scales, other.qzeros, 128, want64=False)
+    check_gemm(run_gemm(other, B.pack_from_numpy(other), big_ws), y32, "after reuse")
+
+
+def test_rows_do_not_influence_each_other(big_ws):
+    inp = I.make_linear(7003, 40, 2048, 512)
+    packed = B.pack_from_numpy(inp)
+    base = run_gemm(inp, packed, big_ws)
+    inp.x[7] = np.float16(3.0)
+    inp.x[39] *= np.float16(-1)
+    pert = run_gemm(inp, packed, big_ws)
+    keep = [m for m in range(40) if m not in (7, 39)]
+    assert np.array_equal(pert[keep].view(np.uint16), base[keep].view(np.uint16))
+    assert not np.array_equal(pert[7], base[7])
+
+
+def test_m_prefix_consistency(big_ws):
+    # the first rows of a 64-row call match a smaller call within tolerance of the same oracle rows
+    inp = I.make_linear(7004, 64, 4096, 512)
+    packed = B.pack_from_numpy(inp)
+    y32, _, _ = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
+    for M in (1, 2, 15, 16, 47, 63, 64):
+        check_gemm(run_gemm(inp, packed, big_ws, M=M), y32[:M], f"prefix M={M}")
+
+
+FULL = [(4, 1, 0), (4, 1, 2), (4, 1, 3), (4, 64, 1), (4, 64, 3), (4, 60, 2), (3, 48, 2), (3, 8, 3), (4, 16, 0), (4, 32, 1)]
+
+
+@pytest.mark.parametrize("cfg,M,gi", FULL)
+def test_parity_full_size_sampled_columns(cfg, M, gi, big_ws):
+    """Llama-3-8B / 70B layer shapes in the launch configuration the benchmark times; the oracle
+    recomputes 256 sampled output columns (all rows) from the same canonical tensors."""
+    name, K, N = (I.LLAMA3_8B if cfg == 3 else I.LLAMA3_70B)[gi]
+    print(f"gemm full-size cfg={cfg} {name} M={M} K={K} N={N}", flush=True)
+    inp = I.make_linear(I.seed_for(cfg, gi), M, K, N, m_max=64)
+    packed = B.pack_from_numpy(inp)
+    need = B.w4a16_workspace_bytes(M, N, K)
+    ws = B.new_workspace(need)   # exactly the advertised size
+    y = run_gemm(inp, packed, ws)
+    rng = np.random.default_rng(gi + M)
+    blocks = rng.choice(N // 8, size=32, replace=False)
+    cols = np.sort((blocks[:, None] * 8 + np.arange(8)[None, :]).ravel())
+    qw, sc, qz = column_subproblem(inp, cols)
+    y32, _, _ = R.w4a16_gemm(inp.x, qw, sc, qz, 128, want64=False)
+    stats = check_gemm(y[:, cols], y32, f"{name} M={M}")
+    print("   ", stats, flush=True)
+    assert np.isfinite(y.astype(np.float32)).all()
+    # a property that holds at any size: column sums of y against x . (column-summed W) in fp64
+    del packed
+
+
+def test_workspace_too_small_is_rejected():
+    inp = I.make_linear(7005, 1, 4096, 4096)
+    packed = B.pack_from_numpy(inp)
+    x = torch.from_numpy(inp.x).to(DEV)
+    y = torch.empty((1, 4096), dtype=torch.float16, device=DEV)
+    tiny = torch.empty(16384, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.W4A16Error) as e:
+        B.w4a16_gemm(x, packed, y, 1, 4096, 4096, 128, tiny)
+    assert e.value.code == -5
