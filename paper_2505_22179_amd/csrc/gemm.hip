@@ -2,17 +2,17 @@
 //
 // The layer (paper section 2.2: 4-bit weights in groups of 128 with fp16 activations) is bound by
 // streaming the packed weight from HBM for every M in range, so the kernel is organised around
-// that stream: each wavefront owns one 128-column block and a set of quantisation groups, pulls
-// each group's record (8 KB of codes + scales + zero-points, see layout.h) with 16-byte loads
-// straight into registers, turns the codes into exact small-integer fp16 values (q - z), and
-// feeds them as the second operand of 16x16x32 fp16 MFMA steps whose first operand is the
-// matching x fragment.  The group's integer-weight partial product is then folded into the fp32
-// accumulators with one multiply-add by the group's scale, so no weight is ever rounded to fp16
+// that stream: each wavefront owns TW 16-column tiles of one 128-column block and a set of
+// quantisation groups, pulls each group's codes (1 KB per tile, see layout.h) with 16-byte loads
+// straight into registers, turns them into exact small-integer fp16 values (q - z), and feeds them
+// as the second operand of 16x16x32 fp16 MFMA steps whose first operand is the matching x
+// fragment.  The group's integer-weight partial product is then folded into the fp32 accumulators
+// with one multiply-add by the group's scale, so no weight is ever rounded to fp16
 // (w = (q - z) * s needs 15 significand bits) and the only rounding is fp32 accumulation.
-// Wavefronts of a workgroup split the K range and are summed through LDS; workgroups may split K
-// further, in which case fp32 partials go through a caller workspace and are summed in a fixed
-// order (by the last workgroup to finish a column block, or by a second kernel), so results do
-// not depend on scheduling.
+// The four wavefronts of a workgroup split the K range and are summed through LDS; workgroups may
+// split K further, in which case fp32 partials go through a caller workspace and are summed in a
+// fixed order (by the last workgroup to finish a column unit, or by a second kernel), so results
+// do not depend on scheduling.
 #include "internal.h"
 
 namespace w4 {
@@ -23,14 +23,11 @@ typedef _Float16 half8v __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 4;              // wavefronts per workgroup, each on its own groups
-constexpr int kThreads = kWaves * 64;
-
 // x fragments of one group: MT row tiles x four 32-wide k steps, plus the group's scales and zeros
 template <int MT>
 struct GroupOperands {
     u32x4 a[MT][4];
-    u32x4 s;        // eight fp16 scales
+    u32x4 s;        // eight fp16 scales (all eight tiles of the record)
     uint32_t z;     // eight 4-bit zero-points
 };
 
@@ -69,33 +66,45 @@ template <int MT>
 __device__ __forceinline__ void load_operands(GroupOperands<MT> &f, const uint8_t *rec,
                                               const _Float16 *const (&xp)[MT], int g, int c)
 {
-    f.s = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(rec + kScalesOff + c * 16));
-    f.z = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4));
+    f.s = *reinterpret_cast<const u32x4 *>(rec + kScalesOff + c * 16);
+    f.z = *reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             f.a[mt][j] = *reinterpret_cast<const u32x4 *>(xp[mt] + (size_t)g * kGroup + j * 32);
+    __builtin_amdgcn_sched_barrier(0);
 }
 
-// One quantisation group for this wavefront's eight column tiles.  As soon as a tile's codes have
-// been expanded its registers are refilled with the same tile of the wavefront's next group, so
-// one group of codes (8 KB per wavefront) is always in flight without a second register set.
-template <int MT>
-__device__ __forceinline__ void compute_group(const GroupOperands<MT> &f, u32x4 (&w)[kTiles],
-                                              float4v (&acc)[kTiles][MT], const uint8_t *next_rec,
-                                              bool has_next, int lane, uint32_t magic)
+// One quantisation group for this wavefront's TW column tiles (tiles t0 .. t0+TW-1 of the record).
+// As soon as a tile's codes have been expanded its registers are refilled with the same tile of
+// the wavefront's next group, so one group of codes is always in flight without a second
+// register set.
+template <int MT, int TW, bool ALWAYS_REFILL>
+__device__ __forceinline__ void compute_group(const GroupOperands<MT> &f, u32x4 (&w)[TW],
+                                              float4v (&acc)[TW][MT], const uint8_t *next_rec,
+                                              bool has_next, int t0, int lane, uint32_t magic)
 {
+    // this wavefront's TW scales / zero-points sit at a uniform offset inside the record's eight
+    const uint32_t zbits = f.z >> (4 * t0);
+    uint32_t sw[(TW + 1) / 2];
 #pragma unroll
-    for (int t = 0; t < kTiles; ++t) {
-        uint32_t z = (f.z >> (4 * t)) & 0xFu;
+    for (int i = 0; i < (TW + 1) / 2; ++i) {
+        if (TW == 8) sw[i] = f.s[i];
+        else if (TW == 4) sw[i] = t0 ? f.s[2 + i] : f.s[i];
+        else sw[i] = (t0 & 4) ? ((t0 & 2) ? f.s[3] : f.s[2]) : ((t0 & 2) ? f.s[1] : f.s[0]);
+    }
+#pragma unroll
+    for (int t = 0; t < TW; ++t) {
+        uint32_t z = (zbits >> (4 * t)) & 0xFu;
         uint32_t zz = z | (z << 16);
         half2v zneg = as_h2(zz | 0xE400E400u);            // -(1024 + z)
         half2v zneg16 = as_h2((zz << 4) | 0xD400D400u);   // -(64 + z)
         half8v b[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) b[j] = dequant8(w[t][j], zneg, zneg16, magic);
-        if (has_next) w[t] = load_tile(next_rec, t, lane);
+        if (ALWAYS_REFILL || has_next) w[t] = load_tile(next_rec, t0 + t, lane);
+        __builtin_amdgcn_sched_barrier(0);   // keep the refill here: the scheduler would otherwise sink all loads to the loop end
         float4v part[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) part[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
@@ -105,40 +114,73 @@ __device__ __forceinline__ void compute_group(const GroupOperands<MT> &f, u32x4 
             for (int mt = 0; mt < MT; ++mt)
                 part[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, f.a[mt][j]), b[j],
                                                                   part[mt], 0, 0, 0);
-        uint32_t sw = f.s[t >> 1];
-        _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+        uint32_t s2 = sw[t >> 1];
+        _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (s2 >> 16) : (s2 & 0xFFFFu)));
         float s = (float)sh;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[t][mt] += s * part[mt];
     }
 }
 
-// element e of a column block's fragment-ordered result -> (row m, column n)
+// Four consecutive elements e4*4 .. e4*4+3 of a column unit's fragment-ordered result are four
+// consecutive columns of one output row: round to fp16 and store them as one 8-byte word.
+// Fragment order: e = ((t * MT + mt) * 4 + i) * 64 + lane, row = mt*16 + 4*(lane/16) + i,
+// column = first_col + t*16 + lane%16.
 template <int MT>
-__device__ __forceinline__ void store_elem(_Float16 *__restrict__ y, float v, int e, int nb, int M, int N)
+__device__ __forceinline__ void store_quad(_Float16 *__restrict__ y, float4v v, int e4, int first_col, int M, int N)
 {
-    int ln = e & 63, reg = e >> 6;
+    int ln = (e4 * 4) & 63, reg = e4 >> 4;
     int i = reg & 3, tm = reg >> 2;
     int mt = tm % MT, t = tm / MT;
     int m = mt * 16 + 4 * (ln >> 4) + i;
-    int n = nb * kBlockCols + t * 16 + (ln & 15);
-    if (m < M && n < N) y[(size_t)m * N + n] = (_Float16)v;
+    int n = first_col + t * 16 + (ln & 15);
+    if (m < M && n < N) {   // N % 8 == 0 and n % 4 == 0: the quad never straddles the edge
+        half4v h = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+        *reinterpret_cast<half4v *>(y + (size_t)m * N + n) = h;
+    }
 }
 
-template <int MT>
-__global__ __launch_bounds__(kThreads, (MT == 1 ? 3 : 1)) void gemm_kernel(
+// wavefronts per SIMD the register allocator must leave room for: one workgroup has to fit
+constexpr int min_waves_per_simd(int mt, int tw, int nw, int depth)
+{
+    return nw / 4;
+}
+
+// coherent-at-device-scope accesses for the split-K partials: they bypass the per-XCD L2's
+// non-coherent lines one access at a time, so no whole-cache write-back or invalidate is needed
+__device__ __forceinline__ void store_partial(float *p, float4v v)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) __hip_atomic_store(p + i, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float4v load_partial(const float *p)
+{
+    float4v v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = __hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return v;
+}
+
+// MT row tiles of 16, TW column tiles per wavefront, NW wavefronts per workgroup (all on the same
+// columns, each on its own quantisation groups), DEPTH groups of codes in flight per wavefront.
+template <int MT, int TW, int NW, int DEPTH>
+__global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) void gemm_kernel(
     const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
     float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused)
 {
-    extern __shared__ float lds[];
+    extern __shared__ float4v lds4[];
     __shared__ uint32_t ticket_sh;
-    constexpr int R = 32 * MT;     // accumulator registers per lane
-    constexpr int E = R * 64;      // fp32 results per column block
-    constexpr int Q = E / kThreads;
+    constexpr int kThreads = NW * 64;
+    constexpr int R = 4 * TW * MT;   // accumulator registers per lane
+    constexpr int E4 = R * 16;       // float4 results per column unit (R * 64 floats)
+    constexpr int Q = (E4 + kThreads - 1) / kThreads;   // float4 per thread in the epilogue
+    constexpr bool kRagged = (E4 % kThreads) != 0;       // small units: some threads own no quad
+    constexpr int U = DEPTH > 2 ? DEPTH : 2;             // unroll: ring position and x-fragment buffer are static
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps the group loop scalar
     const int r = lane >> 4, c = lane & 15;
-    const int nb = blockIdx.x / S, ks = blockIdx.x % S;
+    const int unit = blockIdx.x / S, ks = blockIdx.x % S;        // column unit = TW tiles
+    const int nb = (unit * TW) >> 3, t0 = (unit * TW) & 7;
     const int g_begin = (int)((long long)groups * ks / S);
     const int g_end = (int)((long long)groups * (ks + 1) / S);
 
@@ -151,146 +193,246 @@ __global__ __launch_bounds__(kThreads, (MT == 1 ? 3 : 1)) void gemm_kernel(
     }
     const uint8_t *rec0 = packed + record_offset(nb, 0, groups);
 
-    float4v acc[kTiles][MT];
+    float4v acc[TW][MT];
 #pragma unroll
-    for (int t = 0; t < kTiles; ++t)
+    for (int t = 0; t < TW; ++t)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[t][mt] = (float4v){0.f, 0.f, 0.f, 0.f};
 
     GroupOperands<MT> fa, fb;
-    u32x4 w[kTiles];
+    u32x4 w[DEPTH][TW];
     uint32_t magic = 0x64006400u;
     asm volatile("" : "+v"(magic));   // keep it in a VGPR rather than a literal
-    int g = g_begin + wave;
-    if (g < g_end) {
-        const uint8_t *rec = rec0 + (size_t)g * kRecordBytes;
+    // this wavefront's groups are g0, g0 + NW, ...: n_w of them
+    const int g0 = g_begin + wave;
+    const int n_w = g0 < g_end ? (g_end - g0 + NW - 1) / NW : 0;
+    const uint8_t *recw = rec0 + (size_t)g0 * kRecordBytes;       // record of this wavefront's group 0
+    constexpr size_t kStep = (size_t)NW * kRecordBytes;            // distance between its consecutive groups
 #pragma unroll
-        for (int t = 0; t < kTiles; ++t) w[t] = load_tile(rec, t, lane);
-        load_operands<MT>(fa, rec, xp, g, c);
+    for (int d = 0; d < DEPTH; ++d) {
+        if (d < n_w) {
+#pragma unroll
+            for (int t = 0; t < TW; ++t) w[d][t] = load_tile(recw + d * kStep, t0 + t, lane);
+        }
     }
-    while (g < g_end) {
-        int gn = g + kWaves;
-        bool more = gn < g_end;
-        const uint8_t *rec = rec0 + (size_t)gn * kRecordBytes;
-        if (more) load_operands<MT>(fb, rec, xp, gn, c);
-        compute_group<MT>(fa, w, acc, rec, more, lane, magic);
-        g = gn;
-        if (!more) break;
-        gn = g + kWaves;
-        more = gn < g_end;
-        rec = rec0 + (size_t)gn * kRecordBytes;
-        if (more) load_operands<MT>(fa, rec, xp, gn, c);
-        compute_group<MT>(fb, w, acc, rec, more, lane, magic);
-        g = gn;
+    if (n_w > 0) load_operands<MT>(fa, recw, xp, g0, c);
+    int i = 0;
+    // steady state: every group handled here has a successor DEPTH groups ahead, so all loads are
+    // unconditional and the compiler can count exactly how many may stay in flight at each wait
+    for (; i + U + DEPTH <= n_w; i += U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int gi = i + u;
+            load_operands<MT>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
+            compute_group<MT, TW, true>((u & 1) ? fb : fa, w[u % DEPTH], acc, recw + (size_t)(gi + DEPTH) * kStep,
+                                        true, t0, lane, magic);
+        }
+    }
+    // drain: at most U + DEPTH - 1 groups left; ring position and fragment buffer stay static
+#pragma unroll
+    for (int u = 0; u < U + DEPTH - 1; ++u) {
+        const int gi = i + u;
+        if (gi < n_w) {   // uniform
+            if (gi + 1 < n_w)
+                load_operands<MT>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
+            compute_group<MT, TW, false>((u & 1) ? fb : fa, w[u % DEPTH], acc, recw + (size_t)(gi + DEPTH) * kStep,
+                                         gi + DEPTH < n_w, t0, lane, magic);
+        }
     }
 
-    // sum the wavefronts' accumulators through LDS, wave 0 first (fixed order)
+    // sum the wavefronts' accumulators through LDS in wave order
+    float *lds = reinterpret_cast<float *>(lds4);
 #pragma unroll
-    for (int t = 0; t < kTiles; ++t)
+    for (int t = 0; t < TW; ++t)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 lds[(wave * R + (t * MT + mt) * 4 + i) * 64 + lane] = acc[t][mt][i];
     __syncthreads();
-    float *mine = partial + (size_t)blockIdx.x * E;
+    const int first_col = nb * kBlockCols + t0 * 16;
+    float4v sum[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
-        int e = tid + kThreads * q;
-        float v = lds[e];
+        int e4 = tid + kThreads * q;
+        float4v v = (float4v){0.f, 0.f, 0.f, 0.f};
+        if (!kRagged || e4 < E4) {
+            v = lds4[e4];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) v += lds[w * E + e];
-        if (S == 1) store_elem<MT>(y, v, e, nb, M, N);
-        else mine[e] = v;
+            for (int w2 = 1; w2 < NW; ++w2) v += lds4[w2 * E4 + e4];
+        }
+        sum[q] = v;
     }
-    if (S == 1) return;
-    if (!fused) return;
-    // the last workgroup of this column block to arrive sums all S partials in split order
-    __threadfence();
+    if (S == 1) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            if (!kRagged || tid + kThreads * q < E4) store_quad<MT>(y, sum[q], tid + kThreads * q, first_col, M, N);
+        return;
+    }
+    float *mine = partial + (size_t)blockIdx.x * E4 * 4;
+    if (!fused) {
+        float4v *mine4 = reinterpret_cast<float4v *>(mine);
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            if (!kRagged || tid + kThreads * q < E4) mine4[tid + kThreads * q] = sum[q];
+        return;
+    }
+    // the last workgroup of this column unit to arrive sums all S partials in split order
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+        if (!kRagged || tid + kThreads * q < E4) store_partial(mine + (size_t)(tid + kThreads * q) * 4, sum[q]);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partials have reached device scope
     __syncthreads();
-    if (tid == 0) ticket_sh = atomicAdd(&tickets[nb], 1u);
+    if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_sh != (uint32_t)(S - 1)) return;
-    __threadfence();
-    const float *all = partial + (size_t)nb * S * E;
+    const float *all = partial + (size_t)unit * S * E4 * 4;
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        int e = tid + kThreads * q;
-        float v = 0.f;
-        for (int s = 0; s < S; ++s)
-            v += __hip_atomic_load(all + (size_t)s * E + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        store_elem<MT>(y, v, e, nb, M, N);
+    for (int q = 0; q < Q; ++q) sum[q] = (float4v){0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < S; ++s) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            if (!kRagged || tid + kThreads * q < E4)
+                sum[q] += load_partial(all + ((size_t)s * E4 + tid + kThreads * q) * 4);
     }
-    if (tid == 0) __hip_atomic_store(&tickets[nb], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+        if (!kRagged || tid + kThreads * q < E4) store_quad<MT>(y, sum[q], tid + kThreads * q, first_col, M, N);
+    if (tid == 0) __hip_atomic_store(&tickets[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// second pass of the two-kernel split-K mode: one workgroup per column block
-template <int MT>
-__global__ __launch_bounds__(kThreads) void splitk_reduce_kernel(const float *__restrict__ partial,
-                                                                 _Float16 *__restrict__ y, int M, int N, int S)
+// second pass of the two-kernel split-K mode: one workgroup per column unit
+constexpr int kReduceThreads = 256;
+template <int MT, int TW>
+__global__ __launch_bounds__(kReduceThreads) void splitk_reduce_kernel(const float *__restrict__ partial,
+                                                                       _Float16 *__restrict__ y, int M, int N, int S)
 {
-    constexpr int E = 32 * MT * 64;
-    constexpr int Q = E / kThreads;
-    const int nb = blockIdx.x, tid = threadIdx.x;
-    const float *all = partial + (size_t)nb * S * E;
+    constexpr int E4 = 4 * TW * MT * 16;
+    constexpr int Q = (E4 + kReduceThreads - 1) / kReduceThreads;
+    constexpr bool kRagged = (E4 % kReduceThreads) != 0;
+    const int unit = blockIdx.x, tid = threadIdx.x;
+    const int nb = (unit * TW) >> 3, t0 = (unit * TW) & 7;
+    const float4v *all = reinterpret_cast<const float4v *>(partial) + (size_t)unit * S * E4;
+    float4v sum[Q];
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        int e = tid + kThreads * q;
-        float v = 0.f;
-        for (int s = 0; s < S; ++s) v += all[(size_t)s * E + e];
-        store_elem<MT>(y, v, e, nb, M, N);
+    for (int q = 0; q < Q; ++q) sum[q] = (float4v){0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < S; ++s) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            if (!kRagged || tid + kReduceThreads * q < E4) sum[q] += all[(size_t)s * E4 + tid + kReduceThreads * q];
     }
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+        if (!kRagged || tid + kReduceThreads * q < E4)
+            store_quad<MT>(y, sum[q], tid + kReduceThreads * q, nb * kBlockCols + t0 * 16, M, N);
 }
 
 // ---- host side ---------------------------------------------------------------------------------
 
-static int choose_split(int mt, int nblocks, int groups)
+struct Plan {
+    int tw;      // column tiles per wavefront (2, 4 or 8)
+    int nw;      // wavefronts per workgroup (4, 8 or 16), all splitting K for the same columns
+    int depth;   // groups of codes in flight per wavefront (1, 2 or 4)
+    int S;       // workgroups splitting K for one column unit
+};
+
+// the kernel variants that are compiled: X(MT, TW, NW, DEPTH)
+#define W4_VARIANTS_SMALL(X, MT)                                                                    \
+    X(MT, 2, 4, 1) X(MT, 2, 4, 2) X(MT, 2, 4, 4) X(MT, 4, 4, 1) X(MT, 4, 4, 2) X(MT, 8, 4, 1) X(MT, 8, 4, 2)
+#define W4_VARIANTS(X)                                                                              \
+    W4_VARIANTS_SMALL(X, 1) W4_VARIANTS_SMALL(X, 2) W4_VARIANTS_SMALL(X, 3) W4_VARIANTS_SMALL(X, 4) \
+    X(1, 2, 8, 1) X(1, 2, 8, 2) X(1, 2, 8, 4) X(1, 2, 16, 1) X(1, 4, 4, 4) X(1, 4, 8, 1) X(1, 4, 8, 2)          \
+    X(1, 8, 8, 1) X(1, 8, 8, 2) X(2, 2, 8, 1) X(2, 2, 8, 2) X(2, 2, 8, 4) X(2, 4, 8, 1) X(2, 4, 8, 2) X(3, 2, 8, 1)
+
+static bool variant_exists(int mt, int tw, int nw, int depth)
+{
+#define X(MT_, TW_, NW_, D_) if (mt == MT_ && tw == TW_ && nw == NW_ && depth == D_) return true;
+    W4_VARIANTS(X)
+#undef X
+    return false;
+}
+
+// Launch shape: enough wavefronts to keep every compute unit streaming with no K split across
+// workgroups where the shape allows it (each split costs an fp32 partial round trip), and as many
+// tiles per wavefront as that allows (each x fragment is reused once per tile).
+static Plan choose_plan(int mt, int nblocks, int groups)
 {
     const Params &p = params();
-    int cap = groups / kWaves > 0 ? groups / kWaves : 1;   // every wavefront gets at least one group
-    if (cap > 64) cap = 64;
-    if (p.split_k > 0) return p.split_k < groups ? p.split_k : groups;
-    int per_cu = p.wgs_per_cu > 0 ? p.wgs_per_cu : (mt == 1 ? 3 : (mt == 2 ? 2 : 1));
-    double target = 256.0 * per_cu;
-    int best = 1;
+    const int tiles = nblocks * kTiles;
+    const int forced_s = p.split_k > 0 ? (p.split_k < groups ? p.split_k : groups) : 0;
+    Plan best = {8, 4, 1, forced_s ? forced_s : 1};
     double best_cost = 1e30;
-    for (int s = 1; s <= cap; ++s) {
-        double ratio = (double)nblocks * s / target;
-        double cost = ratio > 1 ? ratio - 1 : 1 / ratio - 1;
-        if (groups % (s * kWaves) != 0) cost += 0.25;       // uneven work per wavefront
-        if (cost < best_cost) { best_cost = cost; best = s; }
+    const double want_waves = 256.0 * (mt == 1 ? 16 : (mt == 2 ? 8 : 4));
+    for (int tw = 8; tw >= 2; tw >>= 1) {
+        if (p.tiles_per_wave > 0 && tw != p.tiles_per_wave) continue;
+        for (int nw = 4; nw <= 16; nw <<= 1) {
+            if (p.waves_per_wg > 0 && nw != p.waves_per_wg) continue;
+            for (int depth = 1; depth <= 4; depth <<= 1) {
+                if (p.prefetch_depth > 0 && depth != p.prefetch_depth) continue;
+                if (!variant_exists(mt, tw, nw, depth)) continue;
+                const int units = tiles / tw;
+                int cap = groups / nw > 0 ? groups / nw : 1;   // every wavefront gets at least one group
+                if (cap > 64) cap = 64;
+                for (int s = forced_s ? forced_s : 1; s <= (forced_s ? forced_s : cap); ++s) {
+                    double fill = (double)units * s * nw / want_waves;
+                    double cost = fill >= 1 ? 0.1 * (fill - 1) : 1 / fill - 1;
+                    cost += 0.5 * (s - 1);                                   // partial-sum round trip
+                    cost += (tw == 8 ? 0 : (tw == 4 ? 0.05 : 0.12)) * mt;    // x-fragment reuse
+                    const int per_wave = groups / (s * nw);
+                    cost += per_wave >= depth ? 0 : 0.2;                     // ring deeper than the loop
+                    cost += depth == 1 ? 0.3 : (depth == 2 ? 0.1 : 0);       // bytes in flight per wavefront
+                    if (groups % (s * nw) != 0) cost += 0.25;                // uneven work per wavefront
+                    if (cost < best_cost) { best_cost = cost; best = {tw, nw, depth, s}; }
+                }
+            }
+        }
     }
+    if (best_cost >= 1e30) best.tw = 0;   // the knobs name a variant that is not compiled
     return best;
 }
 
-static size_t partial_bytes(int mt, int nblocks, int S)
+static size_t partial_bytes(int mt, int nblocks, const Plan &pl)
 {
-    return S > 1 ? (size_t)nblocks * S * (32 * mt * 64) * sizeof(float) : 0;
+    const size_t units = (size_t)nblocks * kTiles / pl.tw;
+    return pl.S > 1 ? units * pl.S * (4 * pl.tw * mt * 64) * sizeof(float) : 0;
 }
 
-template <int MT>
+template <int MT, int TW, int NW, int DEPTH>
 static int launch(const void *x, const void *packed, void *y, int M, int N, int K, int S, void *workspace,
                   hipStream_t stream)
 {
     static bool lds_ok = false;   // LDS above 64 KB needs an opt-in, once per kernel
-    const size_t lds_bytes = (size_t)kWaves * 32 * MT * 64 * sizeof(float);
+    const size_t lds_bytes = (size_t)NW * 4 * TW * MT * 64 * sizeof(float);
+    if (lds_bytes > 160 * 1024) return W4A16_EUNSUP;
     if (!lds_ok && lds_bytes > 48 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<MT>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<MT, TW, NW, DEPTH>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
             return W4A16_EHIP;
         lds_ok = true;
     }
     const int groups = K / kGroup, nblocks = pad_cols(N) / kBlockCols;
+    const int units = nblocks * kTiles / TW;
     const int fused = params().fused_reduce;
     uint32_t *tickets = reinterpret_cast<uint32_t *>(workspace);
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
-    hipLaunchKernelGGL(gemm_kernel<MT>, dim3((unsigned)(nblocks * S)), dim3(kThreads), lds_bytes, stream,
-                       (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, tickets, M, N, K,
-                       groups, S, fused);
+    hipLaunchKernelGGL((gemm_kernel<MT, TW, NW, DEPTH>), dim3((unsigned)(units * S)), dim3(NW * 64), lds_bytes,
+                       stream, (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, tickets, M, N,
+                       K, groups, S, fused);
     if (S > 1 && !fused)
-        hipLaunchKernelGGL(splitk_reduce_kernel<MT>, dim3((unsigned)nblocks), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
                            (const float *)partial, (_Float16 *)y, M, N, S);
     return launch_status();
+}
+
+static int dispatch(int mt, const Plan &pl, const void *x, const void *packed, void *y, int M, int N, int K,
+                    void *workspace, hipStream_t stream)
+{
+#define X(MT_, TW_, NW_, D_)                                                       \
+    if (mt == MT_ && pl.tw == TW_ && pl.nw == NW_ && pl.depth == D_)               \
+        return launch<MT_, TW_, NW_, D_>(x, packed, y, M, N, K, pl.S, workspace, stream);
+    W4_VARIANTS(X)
+#undef X
+    return W4A16_EUNSUP;
 }
 
 }  // namespace w4
@@ -305,7 +447,8 @@ size_t w4a16_workspace_bytes(int M_max, int N, int K, int G)
     const int groups = K / kGroup, nblocks = pad_cols(N) / kBlockCols;
     size_t need = 0;
     for (int mt = 1; mt <= (M_max + 15) / 16; ++mt) {
-        size_t b = partial_bytes(mt, nblocks, choose_split(mt, nblocks, groups));
+        const Plan pl = choose_plan(mt, nblocks, groups);
+        size_t b = pl.tw ? partial_bytes(mt, nblocks, pl) : 0;
         if (b > need) need = b;
     }
     return kTicketBytes + need;
@@ -322,19 +465,14 @@ int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, 
     if (misaligned(x) || misaligned(packed) || misaligned(y) || misaligned(workspace)) return W4A16_EALIGN;
     const int groups = K / kGroup, nblocks = pad_cols(N) / kBlockCols;
     const int mt = (M + 15) / 16;
-    int S = choose_split(mt, nblocks, groups);
-    if (S > 1 && nblocks > kMaxTickets) S = 1;
-    if (S > 1) {
+    Plan pl = choose_plan(mt, nblocks, groups);
+    if (pl.tw == 0) return W4A16_EUNSUP;
+    if (pl.S > 1 && nblocks * kTiles / pl.tw > kMaxTickets) pl.S = 1;
+    if (pl.S > 1) {
         if (!workspace) return W4A16_EWORKSPACE;
-        if (workspace_bytes < kTicketBytes + partial_bytes(mt, nblocks, S)) return W4A16_EWORKSPACE;
+        if (workspace_bytes < kTicketBytes + partial_bytes(mt, nblocks, pl)) return W4A16_EWORKSPACE;
     }
-    hipStream_t st = (hipStream_t)stream;
-    switch (mt) {
-    case 1: return launch<1>(x, packed, y, M, N, K, S, workspace, st);
-    case 2: return launch<2>(x, packed, y, M, N, K, S, workspace, st);
-    case 3: return launch<3>(x, packed, y, M, N, K, S, workspace, st);
-    default: return launch<4>(x, packed, y, M, N, K, S, workspace, st);
-    }
+    return dispatch(mt, pl, x, packed, y, M, N, K, workspace, (hipStream_t)stream);
 }
 
 }  // extern "C"

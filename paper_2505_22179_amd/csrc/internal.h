@@ -29,6 +29,9 @@ struct Params {
     int fused_reduce = 1;
     int wgs_per_cu = 0;    // 0 = heuristic
     int attn_splits = 0;   // 0 = heuristic
+    int tiles_per_wave = 0;   // 0 = heuristic, else 2, 4 or 8
+    int waves_per_wg = 0;     // 0 = heuristic, else 4, 8 or 16
+    int prefetch_depth = 0;   // 0 = heuristic, else 1, 2 or 4
 };
 Params &params();
 

@@ -158,6 +158,9 @@ static int *param_slot(const char *name)
     if (!strcmp(name, "fused_reduce")) return &p.fused_reduce;
     if (!strcmp(name, "wgs_per_cu")) return &p.wgs_per_cu;
     if (!strcmp(name, "attn_splits")) return &p.attn_splits;
+    if (!strcmp(name, "tiles_per_wave")) return &p.tiles_per_wave;
+    if (!strcmp(name, "waves_per_wg")) return &p.waves_per_wg;
+    if (!strcmp(name, "prefetch_depth")) return &p.prefetch_depth;
     return nullptr;
 }
 
@@ -165,6 +168,7 @@ int w4a16_set_param(const char *name, int value)
 {
     int *slot = param_slot(name);
     if (!slot || value < 0 || value > 1024) return W4A16_EINVAL;
+    if (slot == &params().tiles_per_wave && value != 0 && value != 2 && value != 4 && value != 8) return W4A16_EINVAL;
     *slot = value;
     return W4A16_OK;
 }

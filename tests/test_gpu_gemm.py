@@ -24,7 +24,7 @@ def big_ws():
 @pytest.fixture(autouse=True)
 def _reset_knobs():
     yield
-    for k in ("split_k", "wgs_per_cu"):
+    for k in ("split_k", "tiles_per_wave", "waves_per_wg", "prefetch_depth"):
         B.w4a16_set_param(k, 0)
     B.w4a16_set_param("fused_reduce", 1)
 
@@ -41,6 +41,21 @@ def run_gemm(inp, packed, ws, M=None, guard_rows=2):
     return out[:M]
 
 
+# (tiles_per_wave, waves_per_wg, prefetch_depth, split_k, fused_reduce); 0 = the library's heuristic.
+# Every row is a kernel variant compiled for all M.
+VARIANTS = [(0, 0, 0, 0, 1), (8, 4, 1, 1, 1), (8, 4, 2, 3, 1), (4, 4, 2, 2, 0), (4, 4, 1, 1, 1), (2, 4, 4, 0, 0),
+            (2, 4, 2, 3, 1), (2, 4, 4, 1, 1), (2, 4, 1, 5, 0)]
+VARIANTS_M16 = [(2, 16, 1, 1, 1), (2, 16, 1, 2, 1), (2, 8, 4, 3, 0), (4, 8, 2, 2, 0), (4, 4, 4, 1, 1), (8, 8, 2, 1, 1), (8, 8, 1, 3, 1)]
+
+
+def set_variant(tw, nw, depth, split, fused):
+    B.w4a16_set_param("tiles_per_wave", tw)
+    B.w4a16_set_param("waves_per_wg", nw)
+    B.w4a16_set_param("prefetch_depth", depth)
+    B.w4a16_set_param("split_k", split)
+    B.w4a16_set_param("fused_reduce", fused)
+
+
 SMALL = [
     # M, K, N  -- several column blocks, several groups per wavefront, ragged M and N tails
     (1, 128, 8), (1, 4096, 4096), (3, 1024, 136), (4, 2048, 512), (8, 1536, 1000),
@@ -55,11 +70,37 @@ def test_parity_small(M, K, N, big_ws):
     inp = I.make_linear(5000 + M * 7 + K + N, M, K, N)
     packed = B.pack_from_numpy(inp)
     y32, _, _ = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
-    for split, fused in ((0, 1), (1, 1), (3, 1), (2, 0), (0, 0)):
-        B.w4a16_set_param("split_k", split)
-        B.w4a16_set_param("fused_reduce", fused)
+    for variant in VARIANTS:
+        set_variant(*variant)
         y = run_gemm(inp, packed, big_ws)
-        check_gemm(y, y32, f"M={M} K={K} N={N} split={split} fused={fused}")
+        check_gemm(y, y32, f"M={M} K={K} N={N} (tw, nw, depth, split, fused)={variant}")
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 4096, 520), (7, 2176, 256), (16, 8192, 136)])
+def test_parity_wide_workgroups(M, K, N, big_ws):
+    """variants that exist for M <= 16 only (8 and 16 wavefronts per workgroup on wider tiles)"""
+    print(f"gemm parity (wide workgroups) M={M} K={K} N={N}", flush=True)
+    inp = I.make_linear(5500 + M + K + N, M, K, N)
+    packed = B.pack_from_numpy(inp)
+    y32, _, _ = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
+    ex = I.make_linear(5600 + M, M, K, N, x_kind="small_int", scale_kind="pow2")
+    ex_packed = B.pack_from_numpy(ex)
+    _, _, ex16 = R.w4a16_gemm(ex.x, ex.qweight, ex.scales, ex.qzeros, 128, want64=False)
+    for variant in VARIANTS_M16:
+        set_variant(*variant)
+        check_gemm(run_gemm(inp, packed, big_ws), y32, f"M={M} K={K} N={N} variant={variant}")
+        assert np.array_equal(run_gemm(ex, ex_packed, big_ws).view(np.uint16), ex16.view(np.uint16)), variant
+
+
+def test_uncompiled_variant_is_reported():
+    inp = I.make_linear(5700, 40, 256, 128)
+    packed = B.pack_from_numpy(inp)
+    x = torch.from_numpy(inp.x).to(DEV)
+    y = torch.empty((40, 128), dtype=torch.float16, device=DEV)
+    set_variant(8, 16, 4, 0, 1)
+    with pytest.raises(B.W4A16Error) as e:
+        B.w4a16_gemm(x, packed, y, 40, 128, 256, 128, B.new_workspace(1 << 20))
+    assert e.value.code == -4
 
 
 @pytest.mark.parametrize("M", [1, 5, 16, 31, 48, 64])
@@ -71,11 +112,10 @@ def test_exact_inputs_bit_exact(M, big_ws):
     inp = I.make_linear(6000 + M, M, K, N, x_kind="small_int", scale_kind="pow2")
     packed = B.pack_from_numpy(inp)
     _, _, y16 = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
-    for split, fused in ((0, 1), (1, 1), (4, 1), (6, 0)):
-        B.w4a16_set_param("split_k", split)
-        B.w4a16_set_param("fused_reduce", fused)
+    for variant in VARIANTS:
+        set_variant(*variant)
         y = run_gemm(inp, packed, big_ws)
-        assert np.array_equal(y.view(np.uint16), y16.view(np.uint16)), (M, split, fused)
+        assert np.array_equal(y.view(np.uint16), y16.view(np.uint16)), (M, variant)
 
 
 def test_run_to_run_determinism_and_ticket_reuse(big_ws):
