@@ -46,8 +46,8 @@ const char *w4a16_strerror(int code);
 
 /* Ablation knob for benchmarks and tests: overrides an internal launch heuristic process-wide.
  * Names: "split_k" (0 = heuristic, else forced number of K splits), "fused_reduce" (1 = the last
- * workgroup of a column block sums the split-K partials inside the GEMM kernel, 0 = a second
- * kernel does), "wgs_per_cu" (target resident workgroups per compute unit used by the heuristic),
+ * workgroup of a column unit sums the split-K partials inside the GEMM kernel, 0 = a second
+ * kernel does, 2 = per-shape choice, the default),
  * "tiles_per_wave" (0 = heuristic, else 2, 4 or 8 sixteen-column tiles per wavefront),
  * "waves_per_wg" (0 = heuristic, else 4, 8 or 16 wavefronts per workgroup), "prefetch_depth" (0 =
  * heuristic, else 1, 2 or 4 groups of codes in flight per wavefront); a combination that is not

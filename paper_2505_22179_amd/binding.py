@@ -10,7 +10,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "lib", "libw4a16.so")
+LIB_PATH = os.environ.get("W4A16_LIB") or os.path.join(_HERE, "lib", "libw4a16.so")   # W4A16_LIB: load another build of the same ABI
 
 EXPORTS = (
     "w4a16_version", "w4a16_strerror", "w4a16_set_param", "w4a16_get_param", "w4a16_packed_bytes",

@@ -23,6 +23,7 @@ constexpr int kKeyBlock = 32;
 constexpr int kVStride = 132;   // halves per LDS row of V (264 B): the four 16-lane groups hit disjoint banks
 constexpr int kAttnThreads = 256;
 constexpr int kRowsPad = 64;
+constexpr int kMaxSplits = 16;   // key ranges per head (the merge keeps one value per range in registers)
 
 __device__ __forceinline__ float xor_max(float v, int lane_mask)
 {
@@ -156,43 +157,71 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
         }
         return;
     }
+    // partial state of this key range: unnormalised output rows plus (running max, running sum).
+    // Stored with device-scope accesses so that the workgroup that merges the ranges, possibly on
+    // another XCD, reads them without any whole-cache write-back or invalidate.
     float *po = part_o + (size_t)blockIdx.x * kRowsPad * kHeadDim;
     float *pml = part_ml + (size_t)blockIdx.x * kRowsPad * 2;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int row = row0 + 4 * r + i;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) po[row * kHeadDim + dt * 16 + c] = o[dt][i];
+        for (int dt = 0; dt < 8; ++dt)
+            __hip_atomic_store(po + row * kHeadDim + dt * 16 + c, o[dt][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (c == 0) {
-            pml[row * 2] = m_row[i];
-            pml[row * 2 + 1] = l_row[i];
+            __hip_atomic_store(pml + row * 2, m_row[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(pml + row * 2 + 1, l_row[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    __threadfence();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (tid == 0) ticket_sh = atomicAdd(&tickets[h], 1u);
+    if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[h], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_sh != (uint32_t)(nsplit - 1)) return;
-    __threadfence();
-    // last workgroup of this head: merge the splits in order
-    const float *ho = part_o + (size_t)h * nsplit * kRowsPad * kHeadDim;
+    // last workgroup of this head: merge the ranges in order.  Weights first (through LDS), then rows.
+    float *wgt = reinterpret_cast<float *>(&vs[0][0][0]);   // [nsplit][64] merge weights, reuses the V tiles
     const float *hml = part_ml + (size_t)h * nsplit * kRowsPad * 2;
+    const float *ho = part_o + (size_t)h * nsplit * kRowsPad * kHeadDim;
+    if (tid < kRowsPad) {
+        float ms[kMaxSplits], ls[kMaxSplits];
+#pragma unroll
+        for (int s2 = 0; s2 < kMaxSplits; ++s2) {
+            ms[s2] = NEG_INF;
+            ls[s2] = 0.f;
+            if (s2 < nsplit) {
+                ms[s2] = __hip_atomic_load(hml + ((size_t)s2 * kRowsPad + tid) * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ls[s2] = __hip_atomic_load(hml + ((size_t)s2 * kRowsPad + tid) * 2 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        float m_all = NEG_INF;
+#pragma unroll
+        for (int s2 = 0; s2 < kMaxSplits; ++s2) m_all = fmaxf(m_all, ms[s2]);
+        float den = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < kMaxSplits; ++s2) {
+            ms[s2] = (ms[s2] == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms[s2] - m_all);
+            den += ms[s2] * ls[s2];
+        }
+        float inv = 1.f / den;
+#pragma unroll
+        for (int s2 = 0; s2 < kMaxSplits; ++s2)
+            if (s2 < nsplit) wgt[s2 * kRowsPad + tid] = ms[s2] * inv;
+    }
+    __syncthreads();
     for (int e = tid; e < M * kHeadDim; e += kAttnThreads) {
         int row = e / kHeadDim, d = e % kHeadDim;
-        float m_all = NEG_INF;
-        for (int s2 = 0; s2 < nsplit; ++s2)
-            m_all = fmaxf(m_all, __hip_atomic_load(hml + ((size_t)s2 * kRowsPad + row) * 2, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT));
-        float num = 0.f, den = 0.f;
-        for (int s2 = 0; s2 < nsplit; ++s2) {
-            float ms = __hip_atomic_load(hml + ((size_t)s2 * kRowsPad + row) * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            float ls = __hip_atomic_load(hml + ((size_t)s2 * kRowsPad + row) * 2 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            float os = __hip_atomic_load(ho + ((size_t)s2 * kRowsPad + row) * kHeadDim + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            float wgt = (ms == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms - m_all);
-            num += wgt * os;
-            den += wgt * ls;
+        float part[kMaxSplits];
+#pragma unroll
+        for (int s2 = 0; s2 < kMaxSplits; ++s2) {
+            part[s2] = 0.f;
+            if (s2 < nsplit)
+                part[s2] = __hip_atomic_load(ho + ((size_t)s2 * kRowsPad + row) * kHeadDim + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        out[((size_t)row * Hq + h) * kHeadDim + d] = (_Float16)(num / den);
+        float num = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < kMaxSplits; ++s2)
+            if (s2 < nsplit) num += wgt[s2 * kRowsPad + row] * part[s2];
+        out[((size_t)row * Hq + h) * kHeadDim + d] = (_Float16)num;
     }
     if (tid == 0) __hip_atomic_store(&tickets[h], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -202,7 +231,7 @@ static int attn_splits(int M, int P, int Hq)
     int nblk = (P + M + kKeyBlock - 1) / kKeyBlock;
     int want = params().attn_splits > 0 ? params().attn_splits : (512 + Hq - 1) / Hq;
     if (want > nblk) want = nblk;
-    if (want > 64) want = 64;
+    if (want > kMaxSplits) want = kMaxSplits;
     return want < 1 ? 1 : want;
 }
 
@@ -224,7 +253,7 @@ size_t tree_verify_attn_workspace_bytes(int M, int P, int Hq, int Hkv, int D)
 {
     if (check_attn(M, P, Hq, Hkv, D) != W4A16_OK) return 0;
     const int nblk = (P + M + kKeyBlock - 1) / kKeyBlock;
-    const int ns = nblk < 64 ? nblk : 64;   // the most splits any setting of the knobs can ask for
+    const int ns = nblk < kMaxSplits ? nblk : kMaxSplits;   // the most splits any setting of the knobs can ask for
     return kTicketBytes + (size_t)Hq * ns * kRowsPad * (kHeadDim + 2) * sizeof(float);
 }
 

@@ -330,10 +330,16 @@ __global__ __launch_bounds__(kReduceThreads) void splitk_reduce_kernel(const flo
 // ---- host side ---------------------------------------------------------------------------------
 
 struct Plan {
-    int tw;      // column tiles per wavefront (2, 4 or 8)
+    int tw;      // column tiles per wavefront (2, 4 or 8); 0 = no compiled variant matches the knobs
     int nw;      // wavefronts per workgroup (4, 8 or 16), all splitting K for the same columns
     int depth;   // groups of codes in flight per wavefront (1, 2 or 4)
     int S;       // workgroups splitting K for one column unit
+    int fused;   // S > 1: 1 = last workgroup of a unit sums the partials, 0 = a second kernel does
+};
+
+struct TunedRow { int N, K, mt, tw, nw, depth, S, fused; };
+static const TunedRow kTuned[] = {
+#include "tuned_plans.inc"
 };
 
 // the kernel variants that are compiled: X(MT, TW, NW, DEPTH)
@@ -352,43 +358,51 @@ static bool variant_exists(int mt, int tw, int nw, int depth)
     return false;
 }
 
-// Launch shape: enough wavefronts to keep every compute unit streaming with no K split across
-// workgroups where the shape allows it (each split costs an fp32 partial round trip), and as many
-// tiles per wavefront as that allows (each x fragment is reused once per tile).
-static Plan choose_plan(int mt, int nblocks, int groups)
+// Launch shape.  Measured winners for the shapes in tuned_plans.inc; otherwise a rule distilled from
+// those measurements: about one workgroup per compute unit (more when the tile is small), as few
+// K splits across workgroups as that allows (each costs an fp32 partial round trip that grows
+// with M), and as many tiles per wavefront as that allows (each x fragment is reused per tile).
+// Any knob set through w4a16_set_param overrides the corresponding field.
+static Plan choose_plan(int mt, int N, int K)
 {
     const Params &p = params();
-    const int tiles = nblocks * kTiles;
-    const int forced_s = p.split_k > 0 ? (p.split_k < groups ? p.split_k : groups) : 0;
-    Plan best = {8, 4, 1, forced_s ? forced_s : 1};
-    double best_cost = 1e30;
-    const double want_waves = 256.0 * (mt == 1 ? 16 : (mt == 2 ? 8 : 4));
-    for (int tw = 8; tw >= 2; tw >>= 1) {
-        if (p.tiles_per_wave > 0 && tw != p.tiles_per_wave) continue;
-        for (int nw = 4; nw <= 16; nw <<= 1) {
-            if (p.waves_per_wg > 0 && nw != p.waves_per_wg) continue;
-            for (int depth = 1; depth <= 4; depth <<= 1) {
-                if (p.prefetch_depth > 0 && depth != p.prefetch_depth) continue;
-                if (!variant_exists(mt, tw, nw, depth)) continue;
-                const int units = tiles / tw;
-                int cap = groups / nw > 0 ? groups / nw : 1;   // every wavefront gets at least one group
-                if (cap > 64) cap = 64;
-                for (int s = forced_s ? forced_s : 1; s <= (forced_s ? forced_s : cap); ++s) {
-                    double fill = (double)units * s * nw / want_waves;
-                    double cost = fill >= 1 ? 0.1 * (fill - 1) : 1 / fill - 1;
-                    cost += 0.5 * (s - 1);                                   // partial-sum round trip
-                    cost += (tw == 8 ? 0 : (tw == 4 ? 0.05 : 0.12)) * mt;    // x-fragment reuse
-                    const int per_wave = groups / (s * nw);
-                    cost += per_wave >= depth ? 0 : 0.2;                     // ring deeper than the loop
-                    cost += depth == 1 ? 0.3 : (depth == 2 ? 0.1 : 0);       // bytes in flight per wavefront
-                    if (groups % (s * nw) != 0) cost += 0.25;                // uneven work per wavefront
-                    if (cost < best_cost) { best_cost = cost; best = {tw, nw, depth, s}; }
+    const int groups = K / kGroup, tiles = pad_cols(N) / 16;
+    Plan best = {0, 0, 0, 0, 1};
+    const bool free_choice = !p.tiles_per_wave && !p.waves_per_wg && !p.prefetch_depth && !p.split_k;
+    if (free_choice) {
+        for (const TunedRow &r : kTuned)
+            if (r.N == N && r.K == K && r.mt == mt && variant_exists(mt, r.tw, r.nw, r.depth))
+                best = {r.tw, r.nw, r.depth, r.S, r.fused};
+    }
+    if (best.tw == 0) {
+        const int forced_s = p.split_k > 0 ? (p.split_k < groups ? p.split_k : groups) : 0;
+        double best_cost = 1e30;
+        for (int tw = 8; tw >= 2; tw >>= 1) {
+            if (p.tiles_per_wave > 0 && tw != p.tiles_per_wave) continue;
+            for (int nw = 4; nw <= 16; nw <<= 1) {
+                if (p.waves_per_wg > 0 ? nw != p.waves_per_wg : nw == 16) continue;
+                for (int depth = 1; depth <= 4; depth <<= 1) {
+                    if (p.prefetch_depth > 0 ? depth != p.prefetch_depth : depth != 1) continue;
+                    if (!variant_exists(mt, tw, nw, depth)) continue;
+                    const int units = tiles / tw;
+                    int cap = groups / (2 * nw) > 0 ? groups / (2 * nw) : 1;   // two groups per wavefront at least
+                    if (cap > 16) cap = 16;
+                    for (int s = forced_s ? forced_s : 1; s <= (forced_s ? forced_s : cap); ++s) {
+                        const double fill = (double)units * s / 256.0;         // workgroups per compute unit
+                        double cost = fill >= 1 ? 0.25 * (fill - 1) : 1.5 * (1 / fill - 1);
+                        cost += 0.06 * mt * (s - 1);                            // partial-sum round trip
+                        cost += 0.05 * mt * (8 / tw - 1);                       // x-fragment reuse
+                        cost += (mt > 1 && nw > 4) ? 0.3 : 0.0;                 // registers: big tiles want 4 wavefronts
+                        cost += (mt == 1 && nw == 4 && units * s < 384) ? 0.3 : 0.0;
+                        if (groups % (s * nw) != 0) cost += 0.2;               // uneven work per wavefront
+                        if (cost < best_cost) { best_cost = cost; best = {tw, nw, depth, s, mt == 1}; }
+                    }
                 }
             }
         }
     }
-    if (best_cost >= 1e30) best.tw = 0;   // the knobs name a variant that is not compiled
-    return best;
+    if (p.fused_reduce != 2) best.fused = p.fused_reduce;
+    return best;   // tw == 0: the knobs name a variant that is not compiled
 }
 
 static size_t partial_bytes(int mt, int nblocks, const Plan &pl)
@@ -398,8 +412,8 @@ static size_t partial_bytes(int mt, int nblocks, const Plan &pl)
 }
 
 template <int MT, int TW, int NW, int DEPTH>
-static int launch(const void *x, const void *packed, void *y, int M, int N, int K, int S, void *workspace,
-                  hipStream_t stream)
+static int launch(const void *x, const void *packed, void *y, int M, int N, int K, int S, int fused,
+                  void *workspace, hipStream_t stream)
 {
     static bool lds_ok = false;   // LDS above 64 KB needs an opt-in, once per kernel
     const size_t lds_bytes = (size_t)NW * 4 * TW * MT * 64 * sizeof(float);
@@ -412,7 +426,6 @@ static int launch(const void *x, const void *packed, void *y, int M, int N, int 
     }
     const int groups = K / kGroup, nblocks = pad_cols(N) / kBlockCols;
     const int units = nblocks * kTiles / TW;
-    const int fused = params().fused_reduce;
     uint32_t *tickets = reinterpret_cast<uint32_t *>(workspace);
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
     hipLaunchKernelGGL((gemm_kernel<MT, TW, NW, DEPTH>), dim3((unsigned)(units * S)), dim3(NW * 64), lds_bytes,
@@ -429,7 +442,7 @@ static int dispatch(int mt, const Plan &pl, const void *x, const void *packed, v
 {
 #define X(MT_, TW_, NW_, D_)                                                       \
     if (mt == MT_ && pl.tw == TW_ && pl.nw == NW_ && pl.depth == D_)               \
-        return launch<MT_, TW_, NW_, D_>(x, packed, y, M, N, K, pl.S, workspace, stream);
+        return launch<MT_, TW_, NW_, D_>(x, packed, y, M, N, K, pl.S, pl.fused, workspace, stream);
     W4_VARIANTS(X)
 #undef X
     return W4A16_EUNSUP;
@@ -444,10 +457,10 @@ extern "C" {
 size_t w4a16_workspace_bytes(int M_max, int N, int K, int G)
 {
     if (check_weight_shape(N, K, G) != W4A16_OK || M_max < 1 || M_max > W4A16_MAX_M) return 0;
-    const int groups = K / kGroup, nblocks = pad_cols(N) / kBlockCols;
+    const int nblocks = pad_cols(N) / kBlockCols;
     size_t need = 0;
     for (int mt = 1; mt <= (M_max + 15) / 16; ++mt) {
-        const Plan pl = choose_plan(mt, nblocks, groups);
+        const Plan pl = choose_plan(mt, N, K);
         size_t b = pl.tw ? partial_bytes(mt, nblocks, pl) : 0;
         if (b > need) need = b;
     }
@@ -463,9 +476,9 @@ int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, 
     if (M > W4A16_MAX_M) return W4A16_EUNSUP;
     if (!x || !packed || !y) return W4A16_ENULL;
     if (misaligned(x) || misaligned(packed) || misaligned(y) || misaligned(workspace)) return W4A16_EALIGN;
-    const int groups = K / kGroup, nblocks = pad_cols(N) / kBlockCols;
+    const int nblocks = pad_cols(N) / kBlockCols;
     const int mt = (M + 15) / 16;
-    Plan pl = choose_plan(mt, nblocks, groups);
+    Plan pl = choose_plan(mt, N, K);
     if (pl.tw == 0) return W4A16_EUNSUP;
     if (pl.S > 1 && nblocks * kTiles / pl.tw > kMaxTickets) pl.S = 1;
     if (pl.S > 1) {

@@ -26,8 +26,7 @@ inline int launch_status()
 
 struct Params {
     int split_k = 0;       // 0 = heuristic
-    int fused_reduce = 1;
-    int wgs_per_cu = 0;    // 0 = heuristic
+    int fused_reduce = 2;  // 0 = second kernel, 1 = last workgroup, 2 = per-shape choice
     int attn_splits = 0;   // 0 = heuristic
     int tiles_per_wave = 0;   // 0 = heuristic, else 2, 4 or 8
     int waves_per_wg = 0;     // 0 = heuristic, else 4, 8 or 16

@@ -156,7 +156,6 @@ static int *param_slot(const char *name)
     Params &p = params();
     if (!strcmp(name, "split_k")) return &p.split_k;
     if (!strcmp(name, "fused_reduce")) return &p.fused_reduce;
-    if (!strcmp(name, "wgs_per_cu")) return &p.wgs_per_cu;
     if (!strcmp(name, "attn_splits")) return &p.attn_splits;
     if (!strcmp(name, "tiles_per_wave")) return &p.tiles_per_wave;
     if (!strcmp(name, "waves_per_wg")) return &p.waves_per_wg;

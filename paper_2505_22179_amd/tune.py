@@ -1,0 +1,149 @@
+"""Launch-shape tuner for w4a16_gemm (needs a GPU).
+
+For every (layer shape, M bucket of 16 rows) it times each compiled kernel variant -- tiles per
+wavefront, wavefronts per workgroup, prefetch depth, K splits, fused or two-kernel reduction --
+through the library's ablation knobs, on weights rotated through more than 512 MB so the
+last-level cache never serves them, and writes the winners as rows of csrc/tuned_plans.inc.  The
+library falls back to a generic rule for shapes that have no row.
+
+    python -m paper_2505_22179_amd.tune --out gpurun_out/tuned_plans.inc [--shapes 70b,8b]
+
+Rebuild the library after copying the output over csrc/tuned_plans.inc.
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import sys
+
+import torch
+
+from . import binding as B
+from . import inputs as I
+
+G = 128
+KNOBS = ("tiles_per_wave", "waves_per_wg", "prefetch_depth", "split_k", "fused_reduce")
+
+
+def weight_bytes(K: int, N: int) -> int:
+    return K * N // 2 + (K // G) * N * 5 // 2
+
+
+def make_packed(K: int, N: int, copies: int, seed: int = 1):
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (K // 8, N), dtype=torch.int32, device="cuda", generator=gen)
+    sc = (torch.rand((K // G, N), device="cuda", generator=gen) * 9e-3 + 1e-3).to(torch.float16)
+    qz = torch.randint(-2 ** 31, 2 ** 31 - 1, (K // G, N // 8), dtype=torch.int32, device="cuda", generator=gen)
+    p = torch.empty(B.w4a16_packed_bytes(N, K, G), dtype=torch.uint8, device="cuda")
+    B.w4a16_pack(qw, sc, qz, p, N, K, G)
+    return [p] + [p.clone() for _ in range(copies - 1)]
+
+
+def time_graph(fn, copies: int, min_us: float = 1500.0) -> float:
+    """Microseconds per launch: a HIP graph of `copies` launches (one per weight copy), replayed
+    back to back for at least min_us after an equally long warm-up so that clocks stay up."""
+    for c in range(copies):
+        fn(c)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for c in range(copies):
+            fn(c)
+    for _ in range(3):
+        g.replay()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    g.replay()
+    b.record()
+    torch.cuda.synchronize()
+    n = max(4, int(min_us / max(a.elapsed_time(b) * 1e3, 1.0)) + 1)
+    best = 1e9
+    for _ in range(2):
+        for _ in range(n):
+            g.replay()
+        a.record()
+        for _ in range(n):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        best = min(best, a.elapsed_time(b) / (n * copies))
+    return best * 1e3
+
+
+def set_knobs(values) -> None:
+    for k, v in zip(KNOBS, values):
+        B.w4a16_set_param(k, v)
+
+
+def candidates(N: int, K: int):
+    for tw in (8, 4, 2):
+        for nw in (4, 8, 16):
+            for depth in (1, 2, 4):
+                for S, fused in ((1, 1), (2, 1), (2, 0), (3, 0), (4, 1), (4, 0), (6, 0), (8, 0)):
+                    units = (N // 16) // tw
+                    if units * S * nw < 1024 or units * S * nw > 16384 or S * nw > K // G:
+                        continue
+                    yield (tw, nw, depth, S, fused)
+
+
+def tune_shape(name: str, K: int, N: int, Ms, ws, log):
+    wb = weight_bytes(K, N)
+    copies = max(3, int(700e6 // wb) + 1)
+    packs = make_packed(K, N, copies)
+    per_bucket = collections.defaultdict(list)   # mt -> list of {plan: us}
+    for M in Ms:
+        x = torch.randn((M, K), device="cuda").to(torch.float16)
+        y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+        res = {}
+        for plan in candidates(N, K):
+            set_knobs(plan)
+            try:
+                res[plan] = time_graph(lambda c: B.w4a16_gemm(x, packs[c], y, M, N, K, G, ws), copies)
+            except B.W4A16Error:
+                continue   # variant not compiled for this M
+        best = min(res.values())
+        top = sorted(res.items(), key=lambda kv: kv[1])[:4]
+        log(f"{name} K={K} N={N} M={M}: ideal {wb / 8e6:.1f} us | " +
+            " ".join(f"[tw{p[0]} nw{p[1]} d{p[2]} S{p[3]}{'f' if p[4] else 'k'} {us:.1f}us]" for p, us in top))
+        per_bucket[(M + 15) // 16].append({p: us / best for p, us in res.items()})
+    set_knobs((0, 0, 0, 0, 2))
+    rows = []
+    for mt, runs in sorted(per_bucket.items()):
+        common = set(runs[0])
+        for r in runs[1:]:
+            common &= set(r)
+        plan = min(common, key=lambda p: sum(r[p] for r in runs))
+        rows.append((N, K, mt) + plan)
+    del packs
+    torch.cuda.empty_cache()
+    return rows
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", required=True)
+    ap.add_argument("--shapes", default="70b,8b")
+    ap.add_argument("--M", default="1,4,8,16,32,48,64")
+    args = ap.parse_args()
+    Ms = [int(m) for m in args.M.split(",")]
+    ws = B.new_workspace(1 << 30)
+
+    def log(s):
+        print(s, file=sys.stderr, flush=True)
+
+    rows = []
+    for which in args.shapes.split(","):
+        for name, K, N in (I.LLAMA3_70B if which == "70b" else I.LLAMA3_8B):
+            rows += tune_shape(f"{which}.{name}", K, N, Ms, ws, log)
+    with open(args.out, "w") as f:
+        f.write("// Tuned launch shapes, written by `python -m paper_2505_22179_amd.tune` on an MI355X.\n")
+        f.write("// {N, K, row tiles, tiles per wavefront, wavefronts per workgroup, prefetch depth, K splits, fused reduce}\n")
+        for r in rows:
+            f.write("{" + ", ".join(str(v) for v in r) + "},\n")
+    log(f"wrote {len(rows)} rows to {args.out}")
+
+
+if __name__ == "__main__":
+    main()

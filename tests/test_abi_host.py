@@ -75,8 +75,8 @@ def test_argument_validation_happens_before_any_gpu_call():
     assert g(a, None, a, 1, 4096, 4096, 128, a, 1 << 30, None) == ENULL
     assert g(a, a, None, 1, 4096, 4096, 128, a, 1 << 30, None) == ENULL
     assert g(a + 2, a, a, 1, 4096, 4096, 128, a, 1 << 30, None) == EALIGN
-    assert g(a, a, a, 1, 4096, 4096, 128, None, 0, None) == EWS            # split-K shape, no workspace
-    assert g(a, a, a, 1, 4096, 4096, 128, a, 100, None) == EWS
+    assert g(a, a, a, 1, 8192, 28672, 128, None, 0, None) == EWS           # a shape that splits K, no workspace
+    assert g(a, a, a, 1, 8192, 28672, 128, a, 100, None) == EWS
     p = lib.w4a16_pack
     assert p(None, a, a, a, 4096, 4096, 128, None) == ENULL
     assert p(a, a, a, a + 4, 4096, 4096, 128, None) == EALIGN

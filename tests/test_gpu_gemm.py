@@ -26,7 +26,7 @@ def _reset_knobs():
     yield
     for k in ("split_k", "tiles_per_wave", "waves_per_wg", "prefetch_depth"):
         B.w4a16_set_param(k, 0)
-    B.w4a16_set_param("fused_reduce", 1)
+    B.w4a16_set_param("fused_reduce", 2)
 
 
 def run_gemm(inp, packed, ws, M=None, guard_rows=2):
@@ -183,6 +183,7 @@ def test_workspace_too_small_is_rejected():
     x = torch.from_numpy(inp.x).to(DEV)
     y = torch.empty((1, 4096), dtype=torch.float16, device=DEV)
     tiny = torch.empty(16384, dtype=torch.uint8, device=DEV)
+    B.w4a16_set_param("split_k", 2)
     with pytest.raises(B.W4A16Error) as e:
         B.w4a16_gemm(x, packed, y, 1, 4096, 4096, 128, tiny)
     assert e.value.code == -5
