@@ -6,9 +6,9 @@
 // ends up with eight scores of ONE query row (keys 4r..4r+3 of two 16-key tiles): exactly the
 // first-operand fragment the P.V product needs, with no shuffle in between.  The tree mask is
 // applied to the draft keys, softmax runs online in fp32 (base-2 exponentials), and V reaches the
-// second MFMA operand through a small LDS tile because the contraction there runs over keys while
-// V is stored with the head dimension contiguous.  Key ranges are combined by the last workgroup
-// of a head to finish, in split order, so the result does not depend on scheduling.
+// second MFMA operand through a double-buffered LDS tile shared by the four wavefronts, because
+// the contraction there runs over keys while V is stored with the head dimension contiguous.  Key ranges are combined by a second small
+// kernel, in range order, so the result does not depend on scheduling.
 #include "internal.h"
 
 namespace w4 {
@@ -33,11 +33,10 @@ __device__ __forceinline__ float xor_max(float v, int lane_mask)
 __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ k, const _Float16 *__restrict__ v,
     const uint8_t *__restrict__ mask, _Float16 *__restrict__ out, float *__restrict__ part_o,
-    float *__restrict__ part_ml, uint32_t *__restrict__ tickets, int M, int P, int Hq, int Hkv,
+    float *__restrict__ part_ml, int M, int P, int Hq, int Hkv,
     float scale_log2e, int nsplit)
 {
-    __shared__ _Float16 vs[4][kKeyBlock][kVStride];
-    __shared__ uint32_t ticket_sh;
+    __shared__ _Float16 vs[2][kKeyBlock][kVStride];   // V tile of the current and of the next key block
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane >> 4, c = lane & 15;
@@ -62,30 +61,55 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) o[dt] = (float4v){0.f, 0.f, 0.f, 0.f};
 
-    for (int blk = b0; blk < b1; ++blk) {
+    // the workgroup stages each 32-key V block once (32 B per thread) and all four wavefronts read it
+    const int st_key = tid >> 3, st_chunk = (tid & 7) * 2;
+    auto load_v = [&](int blk, u32x4 (&reg)[2]) {
+        int src = min(blk * kKeyBlock + st_key, T - 1);
+        const _Float16 *p = v + (size_t)src * kv_stride + kvh * kHeadDim + st_chunk * 8;
+        reg[0] = *reinterpret_cast<const u32x4 *>(p);
+        reg[1] = *reinterpret_cast<const u32x4 *>(p + 8);
+    };
+    auto store_v = [&](int buf, const u32x4 (&reg)[2]) {
+        u32x2 *dst = reinterpret_cast<u32x2 *>(&vs[buf][st_key][st_chunk * 8]);
+        dst[0] = (u32x2){reg[0][0], reg[0][1]};
+        dst[1] = (u32x2){reg[0][2], reg[0][3]};
+        dst[2] = (u32x2){reg[1][0], reg[1][1]};
+        dst[3] = (u32x2){reg[1][2], reg[1][3]};
+    };
+    // K fragments (first operand of S^T): tile a = keys key0 + 0..15, tile b = key0 + 16..31
+    auto load_k = [&](int blk, half8v (&fa)[4], half8v (&fb)[4]) {
         const int key0 = blk * kKeyBlock;
-        // stage this block's V rows (32 keys x 256 B) into the wavefront's LDS tile
-        __syncthreads();   // previous block's readers are done
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            int idx = u * 64 + lane;
-            int key = idx >> 4, chunk = idx & 15;
-            int src = min(key0 + key, T - 1);
-            u32x4 d = *reinterpret_cast<const u32x4 *>(v + (size_t)src * kv_stride + kvh * kHeadDim + chunk * 8);
-            u32x2 *dst = reinterpret_cast<u32x2 *>(&vs[wave][key][chunk * 8]);
-            dst[0] = (u32x2){d[0], d[1]};
-            dst[1] = (u32x2){d[2], d[3]};
-        }
-        // S^T tiles: first operand = K rows (tile a: keys key0 + 0..15, tile b: key0 + 16..31)
-        float4v sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
         const _Float16 *ka = k + (size_t)min(key0 + c, T - 1) * kv_stride + kvh * kHeadDim + 8 * r;
         const _Float16 *kb = k + (size_t)min(key0 + 16 + c, T - 1) * kv_stride + kvh * kHeadDim + 8 * r;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            half8v fa = *reinterpret_cast<const half8v *>(ka + 32 * j);
-            half8v fb = *reinterpret_cast<const half8v *>(kb + 32 * j);
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa, qf[j], sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb, qf[j], sb, 0, 0, 0);
+            fa[j] = *reinterpret_cast<const half8v *>(ka + 32 * j);
+            fb[j] = *reinterpret_cast<const half8v *>(kb + 32 * j);
+        }
+    };
+    u32x4 vreg[2];
+    half8v kfa[4], kfb[4];
+    if (b0 < b1) {
+        load_v(b0, vreg);
+        load_k(b0, kfa, kfb);
+        store_v(0, vreg);
+    }
+    int cur = 0;
+    for (int blk = b0; blk < b1; ++blk) {
+        const int key0 = blk * kKeyBlock;
+        __syncthreads();   // tile `cur` is complete; nobody still reads the other tile
+        // prefetch the next block's V rows and K fragments (the last block re-reads itself: the
+        // loads stay unconditional so that their completion can be counted exactly)
+        const int nxt = blk + 1 < b1 ? blk + 1 : blk;
+        half8v nfa[4], nfb[4];
+        load_v(nxt, vreg);
+        load_k(nxt, nfa, nfb);
+        __builtin_amdgcn_sched_barrier(0);
+        float4v sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfa[j], qf[j], sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfb[j], qf[j], sb, 0, 0, 0);
         }
         // lane (r, c): sa[i] = score of key key0 + 4r + i, sb[i] = key0 + 16 + 4r + i, query row my_row
         float s[8];
@@ -121,19 +145,25 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
         float a_row[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) a_row[i] = __shfl(alpha, 4 * r + i, 64);
-        __syncthreads();   // V tile written
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
             half8v vb;   // second operand: V[key slot][dt*16 + c], slots = keys 4r+p and 16+4r+p
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                vb[p] = vs[wave][4 * r + p][dt * 16 + c];
-                vb[4 + p] = vs[wave][16 + 4 * r + p][dt * 16 + c];
+                vb[p] = vs[cur][4 * r + p][dt * 16 + c];
+                vb[4 + p] = vs[cur][16 + 4 * r + p][dt * 16 + c];
             }
             float4v acc = o[dt];
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[i] *= a_row[i];
             o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, vb, acc, 0, 0, 0);
+        }
+        store_v(cur ^ 1, vreg);
+        cur ^= 1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            kfa[j] = nfa[j];
+            kfb[j] = nfb[j];
         }
     }
 
@@ -157,73 +187,61 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
         }
         return;
     }
-    // partial state of this key range: unnormalised output rows plus (running max, running sum).
-    // Stored with device-scope accesses so that the workgroup that merges the ranges, possibly on
-    // another XCD, reads them without any whole-cache write-back or invalidate.
+    // partial state of this key range: unnormalised output rows plus (running max, running sum);
+    // a second kernel merges the ranges (the kernel boundary makes them visible, at no fence cost)
     float *po = part_o + (size_t)blockIdx.x * kRowsPad * kHeadDim;
     float *pml = part_ml + (size_t)blockIdx.x * kRowsPad * 2;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int row = row0 + 4 * r + i;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-            __hip_atomic_store(po + row * kHeadDim + dt * 16 + c, o[dt][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int dt = 0; dt < 8; ++dt) po[row * kHeadDim + dt * 16 + c] = o[dt][i];
         if (c == 0) {
-            __hip_atomic_store(pml + row * 2, m_row[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(pml + row * 2 + 1, l_row[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            pml[row * 2] = m_row[i];
+            pml[row * 2 + 1] = l_row[i];
         }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[h], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    if (ticket_sh != (uint32_t)(nsplit - 1)) return;
-    // last workgroup of this head: merge the ranges in order.  Weights first (through LDS), then rows.
-    float *wgt = reinterpret_cast<float *>(&vs[0][0][0]);   // [nsplit][64] merge weights, reuses the V tiles
+}
+
+// merge of the key ranges: one thread per four consecutive output elements, ranges in order
+__global__ __launch_bounds__(256) void tree_attn_merge_kernel(const float *__restrict__ part_o,
+                                                              const float *__restrict__ part_ml,
+                                                              _Float16 *__restrict__ out, int M, int Hq, int nsplit)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;   // over M * Hq * 32 quads
+    if (idx >= M * Hq * (kHeadDim / 4)) return;
+    const int d4 = idx % (kHeadDim / 4), h = (idx / (kHeadDim / 4)) % Hq, row = idx / (kHeadDim / 4) / Hq;
+    const float NEG_INF = -__builtin_inff();
     const float *hml = part_ml + (size_t)h * nsplit * kRowsPad * 2;
-    const float *ho = part_o + (size_t)h * nsplit * kRowsPad * kHeadDim;
-    if (tid < kRowsPad) {
-        float ms[kMaxSplits], ls[kMaxSplits];
+    const float4v *ho = reinterpret_cast<const float4v *>(part_o + (size_t)h * nsplit * kRowsPad * kHeadDim);
+    float ms[kMaxSplits], ls[kMaxSplits];
+    float4v os[kMaxSplits];
 #pragma unroll
-        for (int s2 = 0; s2 < kMaxSplits; ++s2) {
-            ms[s2] = NEG_INF;
-            ls[s2] = 0.f;
-            if (s2 < nsplit) {
-                ms[s2] = __hip_atomic_load(hml + ((size_t)s2 * kRowsPad + tid) * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ls[s2] = __hip_atomic_load(hml + ((size_t)s2 * kRowsPad + tid) * 2 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+    for (int s = 0; s < kMaxSplits; ++s) {
+        ms[s] = NEG_INF;
+        ls[s] = 0.f;
+        os[s] = (float4v){0.f, 0.f, 0.f, 0.f};
+        if (s < nsplit) {
+            ms[s] = hml[((size_t)s * kRowsPad + row) * 2];
+            ls[s] = hml[((size_t)s * kRowsPad + row) * 2 + 1];
+            os[s] = ho[((size_t)s * kRowsPad + row) * (kHeadDim / 4) + d4];
         }
-        float m_all = NEG_INF;
-#pragma unroll
-        for (int s2 = 0; s2 < kMaxSplits; ++s2) m_all = fmaxf(m_all, ms[s2]);
-        float den = 0.f;
-#pragma unroll
-        for (int s2 = 0; s2 < kMaxSplits; ++s2) {
-            ms[s2] = (ms[s2] == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms[s2] - m_all);
-            den += ms[s2] * ls[s2];
-        }
-        float inv = 1.f / den;
-#pragma unroll
-        for (int s2 = 0; s2 < kMaxSplits; ++s2)
-            if (s2 < nsplit) wgt[s2 * kRowsPad + tid] = ms[s2] * inv;
     }
-    __syncthreads();
-    for (int e = tid; e < M * kHeadDim; e += kAttnThreads) {
-        int row = e / kHeadDim, d = e % kHeadDim;
-        float part[kMaxSplits];
+    float m_all = NEG_INF;
 #pragma unroll
-        for (int s2 = 0; s2 < kMaxSplits; ++s2) {
-            part[s2] = 0.f;
-            if (s2 < nsplit)
-                part[s2] = __hip_atomic_load(ho + ((size_t)s2 * kRowsPad + row) * kHeadDim + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        float num = 0.f;
+    for (int s = 0; s < kMaxSplits; ++s) m_all = fmaxf(m_all, ms[s]);
+    float den = 0.f;
+    float4v num = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s2 = 0; s2 < kMaxSplits; ++s2)
-            if (s2 < nsplit) num += wgt[s2 * kRowsPad + row] * part[s2];
-        out[((size_t)row * Hq + h) * kHeadDim + d] = (_Float16)num;
+    for (int s = 0; s < kMaxSplits; ++s) {
+        float wgt = (ms[s] == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms[s] - m_all);
+        den += wgt * ls[s];
+        num += wgt * os[s];
     }
-    if (tid == 0) __hip_atomic_store(&tickets[h], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const float inv = 1.f / den;
+    typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+    half4v hv = {(_Float16)(num[0] * inv), (_Float16)(num[1] * inv), (_Float16)(num[2] * inv), (_Float16)(num[3] * inv)};
+    *reinterpret_cast<half4v *>(out + ((size_t)row * Hq + h) * kHeadDim + d4 * 4) = hv;
 }
 
 static int attn_splits(int M, int P, int Hq)
@@ -268,13 +286,17 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
     const int ns = attn_splits(M, P, Hq);
     const size_t need = kTicketBytes + (size_t)Hq * ns * kRowsPad * (kHeadDim + 2) * sizeof(float);
     if (ns > 1 && (!workspace || workspace_bytes < need)) return W4A16_EWORKSPACE;
-    uint32_t *tickets = reinterpret_cast<uint32_t *>(workspace);
     float *part_o = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
     float *part_ml = part_o + (size_t)Hq * ns * kRowsPad * kHeadDim;
     const float scale_log2e = scale * 1.4426950408889634f;
     hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)(Hq * ns)), dim3(kAttnThreads), 0, (hipStream_t)stream,
                        (const _Float16 *)q, (const _Float16 *)k, (const _Float16 *)v, mask, (_Float16 *)out,
-                       part_o, part_ml, tickets, M, P, Hq, Hkv, scale_log2e, ns);
+                       part_o, part_ml, M, P, Hq, Hkv, scale_log2e, ns);
+    if (ns > 1) {
+        const int quads = M * Hq * (kHeadDim / 4);
+        hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0,
+                           (hipStream_t)stream, (const float *)part_o, (const float *)part_ml, (_Float16 *)out, M, Hq, ns);
+    }
     return launch_status();
 }
 
