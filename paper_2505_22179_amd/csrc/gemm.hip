@@ -33,25 +33,34 @@ struct GroupOperands {
 
 __device__ __forceinline__ half2v as_h2(uint32_t u) { return __builtin_bit_cast(half2v, u); }
 
-// (w & mask) | magic in one VALU instruction (the mask rides in an SGPR, the magic in a VGPR:
-// VOP3 encodings take no literal on this ISA, which is why the compiler splits it in two)
-__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t magic)
+// Constants of the code expansion, kept in registers: (w & mask) | magic then selects to the single
+// three-operand v_and_or_b32, which takes no literal on this ISA (with literal operands the
+// compiler has to split it into an AND and an OR).
+struct DequantConsts {
+    uint32_t magic;     // 0x6400 in both halves: fp16 1024
+    uint32_t mask_lo;   // 0x000F000F
+    uint32_t mask_hi;   // 0x00F000F0
+};
+
+__device__ __forceinline__ DequantConsts dequant_consts()
 {
-    uint32_t out;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(out) : "v"(w), "s"(mask), "v"(magic));
-    return out;
+    DequantConsts k = {0x64006400u, 0x000F000Fu, 0x00F000F0u};
+    asm volatile("" : "+v"(k.magic));    // opaque to constant propagation: stays in a VGPR
+    asm volatile("" : "+s"(k.mask_lo));  // stay in SGPRs
+    asm volatile("" : "+s"(k.mask_hi));
+    return k;
 }
 
 // eight codes of one packed word -> eight fp16 values (q - z), exactly.
 // 0x6400 | q is the fp16 number 1024 + q; 0x6400 | (q << 4) is 1024 + 16 q.
-__device__ __forceinline__ half8v dequant8(uint32_t w, half2v zneg, half2v zneg16, uint32_t magic)
+__device__ __forceinline__ half8v dequant8(uint32_t w, half2v zneg, half2v zneg16, const DequantConsts &k)
 {
     const half2v sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
     uint32_t w2 = w >> 8;
-    half2v b0 = as_h2(and_or(w, 0x000F000Fu, magic)) + zneg;                    // p0 p1
-    half2v b1 = as_h2(and_or(w, 0x00F000F0u, magic)) * sixteenth + zneg16;      // p2 p3
-    half2v b2 = as_h2(and_or(w2, 0x000F000Fu, magic)) + zneg;                   // p4 p5
-    half2v b3 = as_h2(and_or(w2, 0x00F000F0u, magic)) * sixteenth + zneg16;     // p6 p7
+    half2v b0 = as_h2((w & k.mask_lo) | k.magic) + zneg;                    // p0 p1
+    half2v b1 = as_h2((w & k.mask_hi) | k.magic) * sixteenth + zneg16;      // p2 p3
+    half2v b2 = as_h2((w2 & k.mask_lo) | k.magic) + zneg;                   // p4 p5
+    half2v b3 = as_h2((w2 & k.mask_hi) | k.magic) * sixteenth + zneg16;     // p6 p7
     half4v lo = __builtin_shufflevector(b0, b1, 0, 1, 2, 3);
     half4v hi = __builtin_shufflevector(b2, b3, 0, 1, 2, 3);
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -76,35 +85,66 @@ __device__ __forceinline__ void load_operands(GroupOperands<MT> &f, const uint8_
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// One quantisation group for this wavefront's TW column tiles (tiles t0 .. t0+TW-1 of the record).
-// As soon as a tile's codes have been expanded its registers are refilled with the same tile of
-// the wavefront's next group, so one group of codes is always in flight without a second
-// register set.
-template <int MT, int TW, bool ALWAYS_REFILL>
-__device__ __forceinline__ void compute_group(const GroupOperands<MT> &f, u32x4 (&w)[TW],
-                                              float4v (&acc)[TW][MT], const uint8_t *next_rec,
-                                              bool has_next, int t0, int lane, uint32_t magic)
+// scale / zero-point words of this wavefront's TW tiles (tiles t0 .. t0+TW-1 of the record's eight)
+template <int TW>
+struct TileQuant {
+    uint32_t zbits;                 // 4-bit zero-points, tile t in bits 4t..4t+3
+    uint32_t sw[(TW + 1) / 2];      // fp16 scales, two per word
+};
+
+template <int MT, int TW>
+__device__ __forceinline__ TileQuant<TW> tile_quant(const GroupOperands<MT> &f, int t0)
 {
-    // this wavefront's TW scales / zero-points sit at a uniform offset inside the record's eight
-    const uint32_t zbits = f.z >> (4 * t0);
-    uint32_t sw[(TW + 1) / 2];
-#pragma unroll
-    for (int i = 0; i < (TW + 1) / 2; ++i) {
-        if (TW == 8) sw[i] = f.s[i];
-        else if (TW == 4) sw[i] = t0 ? f.s[2 + i] : f.s[i];
-        else sw[i] = (t0 & 4) ? ((t0 & 2) ? f.s[3] : f.s[2]) : ((t0 & 2) ? f.s[1] : f.s[0]);
+    TileQuant<TW> q;
+    q.zbits = f.z >> (4 * t0);
+    const uint32_t s0 = f.s[0], s1 = f.s[1], s2 = f.s[2], s3 = f.s[3];
+    if constexpr (TW == 8) {
+        q.sw[0] = s0; q.sw[1] = s1; q.sw[2] = s2; q.sw[3] = s3;
+    } else if constexpr (TW == 4) {
+        q.sw[0] = t0 ? s2 : s0;
+        q.sw[1] = t0 ? s3 : s1;
+    } else {
+        q.sw[0] = (t0 & 4) ? ((t0 & 2) ? s3 : s2) : ((t0 & 2) ? s1 : s0);
     }
+    return q;
+}
+
+// the four second operands (k steps) of one tile: exact fp16 (q - z)
+template <int TW>
+__device__ __forceinline__ void dequant_tile(half8v (&b)[4], const u32x4 &w, const TileQuant<TW> &q, int t,
+                                             const DequantConsts &magic)
+{
+    uint32_t z = (q.zbits >> (4 * t)) & 0xFu;
+    uint32_t zz = z | (z << 16);
+    half2v zneg = as_h2(zz | 0xE400E400u);            // -(1024 + z)
+    half2v zneg16 = as_h2((zz << 4) | 0xD400D400u);   // -(64 + z)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) b[j] = dequant8(w[j], zneg, zneg16, magic);
+}
+
+// One quantisation group for this wavefront's TW column tiles, software-pipelined over tiles:
+// while the matrix pipe works on tile t (its operand `bc` was expanded one stage earlier), the
+// vector ALU expands tile t+1 -- or tile 0 of the wavefront's next group at the last stage -- and
+// the registers of every expanded tile are refilled at once with the same tile DEPTH groups ahead,
+// so the code stream never stalls on its own arithmetic.
+//   f, w      operands and codes of this group;  fn, wn  those of the next group (ring neighbour)
+//   bc        in: expanded tile 0 of this group; out: expanded tile 0 of the next group
+template <int MT, int TW, bool ALWAYS_REFILL>
+__device__ __forceinline__ void compute_group(const GroupOperands<MT> &f, const GroupOperands<MT> &fn,
+                                              u32x4 (&w)[TW], u32x4 (&wn)[TW], half8v (&bc)[4],
+                                              float4v (&acc)[TW][MT], const uint8_t *refill_rec, bool refill,
+                                              bool next_group, int t0, int lane, const DequantConsts &magic)
+{
+    const TileQuant<TW> q = tile_quant<MT, TW>(f, t0);
+    const TileQuant<TW> qn = tile_quant<MT, TW>(fn, t0);
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
-        uint32_t z = (zbits >> (4 * t)) & 0xFu;
-        uint32_t zz = z | (z << 16);
-        half2v zneg = as_h2(zz | 0xE400E400u);            // -(1024 + z)
-        half2v zneg16 = as_h2((zz << 4) | 0xD400D400u);   // -(64 + z)
-        half8v b[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) b[j] = dequant8(w[t][j], zneg, zneg16, magic);
-        if (ALWAYS_REFILL || has_next) w[t] = load_tile(next_rec, t0 + t, lane);
-        __builtin_amdgcn_sched_barrier(0);   // keep the refill here: the scheduler would otherwise sink all loads to the loop end
+        // tile t was expanded during the previous stage: its code registers are free again
+        if (ALWAYS_REFILL || refill) w[t] = load_tile(refill_rec, t0 + t, lane);
+        __builtin_amdgcn_sched_barrier(0);   // loads stay where they are written
+        half8v bn[4];
+        if (t + 1 < TW) dequant_tile<TW>(bn, w[t + 1 < TW ? t + 1 : 0], q, t + 1, magic);
+        else if (ALWAYS_REFILL || next_group) dequant_tile<TW>(bn, wn[0], qn, 0, magic);
         float4v part[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) part[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
@@ -112,13 +152,22 @@ __device__ __forceinline__ void compute_group(const GroupOperands<MT> &f, u32x4 
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                part[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, f.a[mt][j]), b[j],
+                part[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, f.a[mt][j]), bc[j],
                                                                   part[mt], 0, 0, 0);
-        uint32_t s2 = sw[t >> 1];
+        uint32_t s2 = q.sw[t >> 1];
         _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (s2 >> 16) : (s2 & 0xFFFFu)));
         float s = (float)sh;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[t][mt] += s * part[mt];
+        // interleave: one matrix instruction, then a share of the next tile's expansion
+#pragma unroll
+        for (int i = 0; i < 4 * MT; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, (40 + 4 * MT - 1) / (4 * MT), 0);   // VALU
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bc[j] = bn[j];
     }
 }
 
@@ -201,8 +250,7 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
 
     GroupOperands<MT> fa, fb;
     u32x4 w[DEPTH][TW];
-    uint32_t magic = 0x64006400u;
-    asm volatile("" : "+v"(magic));   // keep it in a VGPR rather than a literal
+    const DequantConsts magic = dequant_consts();
     // this wavefront's groups are g0, g0 + NW, ...: n_w of them
     const int g0 = g_begin + wave;
     const int n_w = g0 < g_end ? (g_end - g0 + NW - 1) / NW : 0;
@@ -215,7 +263,11 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
             for (int t = 0; t < TW; ++t) w[d][t] = load_tile(recw + d * kStep, t0 + t, lane);
         }
     }
-    if (n_w > 0) load_operands<MT>(fa, recw, xp, g0, c);
+    half8v bc[4];
+    if (n_w > 0) {
+        load_operands<MT>(fa, recw, xp, g0, c);
+        dequant_tile<TW>(bc, w[0][0], tile_quant<MT, TW>(fa, t0), 0, magic);
+    }
     int i = 0;
     // steady state: every group handled here has a successor DEPTH groups ahead, so all loads are
     // unconditional and the compiler can count exactly how many may stay in flight at each wait
@@ -224,8 +276,8 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
         for (int u = 0; u < U; ++u) {
             const int gi = i + u;
             load_operands<MT>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
-            compute_group<MT, TW, true>((u & 1) ? fb : fa, w[u % DEPTH], acc, recw + (size_t)(gi + DEPTH) * kStep,
-                                        true, t0, lane, magic);
+            compute_group<MT, TW, true>((u & 1) ? fb : fa, (u & 1) ? fa : fb, w[u % DEPTH], w[(u + 1) % DEPTH], bc, acc,
+                                        recw + (size_t)(gi + DEPTH) * kStep, true, true, t0, lane, magic);
         }
     }
     // drain: at most U + DEPTH - 1 groups left; ring position and fragment buffer stay static
@@ -235,8 +287,9 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
         if (gi < n_w) {   // uniform
             if (gi + 1 < n_w)
                 load_operands<MT>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
-            compute_group<MT, TW, false>((u & 1) ? fb : fa, w[u % DEPTH], acc, recw + (size_t)(gi + DEPTH) * kStep,
-                                         gi + DEPTH < n_w, t0, lane, magic);
+            compute_group<MT, TW, false>((u & 1) ? fb : fa, (u & 1) ? fa : fb, w[u % DEPTH], w[(u + 1) % DEPTH], bc, acc,
+                                         recw + (size_t)(gi + DEPTH) * kStep, gi + DEPTH < n_w, gi + 1 < n_w, t0, lane,
+                                         magic);
         }
     }
 
@@ -347,8 +400,8 @@ static const TunedRow kTuned[] = {
     X(MT, 2, 4, 1) X(MT, 2, 4, 2) X(MT, 2, 4, 4) X(MT, 4, 4, 1) X(MT, 4, 4, 2) X(MT, 8, 4, 1) X(MT, 8, 4, 2)
 #define W4_VARIANTS(X)                                                                              \
     W4_VARIANTS_SMALL(X, 1) W4_VARIANTS_SMALL(X, 2) W4_VARIANTS_SMALL(X, 3) W4_VARIANTS_SMALL(X, 4) \
-    X(1, 2, 8, 1) X(1, 2, 8, 2) X(1, 2, 8, 4) X(1, 2, 16, 1) X(1, 4, 4, 4) X(1, 4, 8, 1) X(1, 4, 8, 2)          \
-    X(1, 8, 8, 1) X(1, 8, 8, 2) X(2, 2, 8, 1) X(2, 2, 8, 2) X(2, 2, 8, 4) X(2, 4, 8, 1) X(2, 4, 8, 2) X(3, 2, 8, 1)
+    X(1, 2, 8, 1) X(1, 2, 8, 2) X(1, 2, 8, 4) X(1, 4, 4, 4) X(1, 4, 8, 1) X(1, 4, 8, 2)                         \
+    X(1, 8, 8, 1) X(1, 8, 8, 2) X(2, 2, 8, 1) X(2, 2, 8, 2) X(2, 4, 8, 1)
 
 static bool variant_exists(int mt, int tw, int nw, int depth)
 {

@@ -45,7 +45,7 @@ def run_gemm(inp, packed, ws, M=None, guard_rows=2):
 # Every row is a kernel variant compiled for all M.
 VARIANTS = [(0, 0, 0, 0, 1), (8, 4, 1, 1, 1), (8, 4, 2, 3, 1), (4, 4, 2, 2, 0), (4, 4, 1, 1, 1), (2, 4, 4, 0, 0),
             (2, 4, 2, 3, 1), (2, 4, 4, 1, 1), (2, 4, 1, 5, 0)]
-VARIANTS_M16 = [(2, 16, 1, 1, 1), (2, 16, 1, 2, 1), (2, 8, 4, 3, 0), (4, 8, 2, 2, 0), (4, 4, 4, 1, 1), (8, 8, 2, 1, 1), (8, 8, 1, 3, 1)]
+VARIANTS_M16 = [(2, 8, 1, 1, 1), (2, 8, 2, 2, 1), (2, 8, 4, 3, 0), (4, 8, 2, 2, 0), (4, 4, 4, 1, 1), (8, 8, 2, 1, 1), (8, 8, 1, 3, 1)]
 
 
 def set_variant(tw, nw, depth, split, fused):
@@ -97,7 +97,7 @@ def test_uncompiled_variant_is_reported():
     packed = B.pack_from_numpy(inp)
     x = torch.from_numpy(inp.x).to(DEV)
     y = torch.empty((40, 128), dtype=torch.float16, device=DEV)
-    set_variant(8, 16, 4, 0, 1)
+    set_variant(8, 16, 4, 0, 2)
     with pytest.raises(B.W4A16Error) as e:
         B.w4a16_gemm(x, packed, y, 40, 128, 256, 128, B.new_workspace(1 << 20))
     assert e.value.code == -4
