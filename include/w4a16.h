@@ -49,7 +49,8 @@ const char *w4a16_strerror(int code);
  * workgroup of a column unit sums the split-K partials inside the GEMM kernel, 0 = a second
  * kernel does, 2 = per-shape choice, the default),
  * "tiles_per_wave" (0 = heuristic, else 2, 4 or 8 sixteen-column tiles per wavefront),
- * "waves_per_wg" (0 = heuristic, else 4, 8 or 16 wavefronts per workgroup), "prefetch_depth" (0 =
+ * "waves_per_wg" (0 = heuristic; 4, 8 or 16 wavefronts per workgroup that split K; 1 selects the
+ * variant whose four wavefronts split the columns and share x through LDS), "prefetch_depth" (0 =
  * heuristic, else 1, 2 or 4 groups of codes in flight per wavefront); a combination that is not
  * compiled makes w4a16_gemm return W4A16_EUNSUP,
  * "attn_splits" (0 = heuristic, else the number of key ranges per head in tree_verify_attn).

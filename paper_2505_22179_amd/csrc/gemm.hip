@@ -23,12 +23,17 @@ typedef _Float16 half8v __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// scales and zero-points of one record, as a lane needs them (column = lane % 16 of every tile)
+struct QuantWords {
+    u32x4 s;        // eight fp16 scales (all eight tiles of the record)
+    uint32_t z;     // eight 4-bit zero-points
+};
+
 // x fragments of one group: MT row tiles x four 32-wide k steps, plus the group's scales and zeros
 template <int MT>
 struct GroupOperands {
     u32x4 a[MT][4];
-    u32x4 s;        // eight fp16 scales (all eight tiles of the record)
-    uint32_t z;     // eight 4-bit zero-points
+    QuantWords q;
 };
 
 __device__ __forceinline__ half2v as_h2(uint32_t u) { return __builtin_bit_cast(half2v, u); }
@@ -75,8 +80,8 @@ template <int MT>
 __device__ __forceinline__ void load_operands(GroupOperands<MT> &f, const uint8_t *rec,
                                               const _Float16 *const (&xp)[MT], int g, int c)
 {
-    f.s = *reinterpret_cast<const u32x4 *>(rec + kScalesOff + c * 16);
-    f.z = *reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4);
+    f.q.s = *reinterpret_cast<const u32x4 *>(rec + kScalesOff + c * 16);
+    f.q.z = *reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -92,8 +97,8 @@ struct TileQuant {
     uint32_t sw[(TW + 1) / 2];      // fp16 scales, two per word
 };
 
-template <int MT, int TW>
-__device__ __forceinline__ TileQuant<TW> tile_quant(const GroupOperands<MT> &f, int t0)
+template <int TW>
+__device__ __forceinline__ TileQuant<TW> tile_quant(const QuantWords &f, int t0)
 {
     TileQuant<TW> q;
     q.zbits = f.z >> (4 * t0);
@@ -130,13 +135,13 @@ __device__ __forceinline__ void dequant_tile(half8v (&b)[4], const u32x4 &w, con
 //   f, w      operands and codes of this group;  fn, wn  those of the next group (ring neighbour)
 //   bc        in: expanded tile 0 of this group; out: expanded tile 0 of the next group
 template <int MT, int TW, bool ALWAYS_REFILL>
-__device__ __forceinline__ void compute_group(const GroupOperands<MT> &f, const GroupOperands<MT> &fn,
+__device__ __forceinline__ void compute_group(const u32x4 (&a)[MT][4], const QuantWords &f, const QuantWords &fn,
                                               u32x4 (&w)[TW], u32x4 (&wn)[TW], half8v (&bc)[4],
                                               float4v (&acc)[TW][MT], const uint8_t *refill_rec, bool refill,
                                               bool next_group, int t0, int lane, const DequantConsts &magic)
 {
-    const TileQuant<TW> q = tile_quant<MT, TW>(f, t0);
-    const TileQuant<TW> qn = tile_quant<MT, TW>(fn, t0);
+    const TileQuant<TW> q = tile_quant<TW>(f, t0);
+    const TileQuant<TW> qn = tile_quant<TW>(fn, t0);
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
         // tile t was expanded during the previous stage: its code registers are free again
@@ -152,7 +157,7 @@ __device__ __forceinline__ void compute_group(const GroupOperands<MT> &f, const 
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                part[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, f.a[mt][j]), bc[j],
+                part[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a[mt][j]), bc[j],
                                                                   part[mt], 0, 0, 0);
         uint32_t s2 = q.sw[t >> 1];
         _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (s2 >> 16) : (s2 & 0xFFFFu)));
@@ -266,7 +271,7 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
     half8v bc[4];
     if (n_w > 0) {
         load_operands<MT>(fa, recw, xp, g0, c);
-        dequant_tile<TW>(bc, w[0][0], tile_quant<MT, TW>(fa, t0), 0, magic);
+        dequant_tile<TW>(bc, w[0][0], tile_quant<TW>(fa.q, t0), 0, magic);
     }
     int i = 0;
     // steady state: every group handled here has a successor DEPTH groups ahead, so all loads are
@@ -276,7 +281,8 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
         for (int u = 0; u < U; ++u) {
             const int gi = i + u;
             load_operands<MT>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
-            compute_group<MT, TW, true>((u & 1) ? fb : fa, (u & 1) ? fa : fb, w[u % DEPTH], w[(u + 1) % DEPTH], bc, acc,
+            compute_group<MT, TW, true>(((u & 1) ? fb : fa).a, ((u & 1) ? fb : fa).q, ((u & 1) ? fa : fb).q, w[u % DEPTH],
+                                        w[(u + 1) % DEPTH], bc, acc,
                                         recw + (size_t)(gi + DEPTH) * kStep, true, true, t0, lane, magic);
         }
     }
@@ -287,7 +293,8 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
         if (gi < n_w) {   // uniform
             if (gi + 1 < n_w)
                 load_operands<MT>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
-            compute_group<MT, TW, false>((u & 1) ? fb : fa, (u & 1) ? fa : fb, w[u % DEPTH], w[(u + 1) % DEPTH], bc, acc,
+            compute_group<MT, TW, false>(((u & 1) ? fb : fa).a, ((u & 1) ? fb : fa).q, ((u & 1) ? fa : fb).q, w[u % DEPTH],
+                                         w[(u + 1) % DEPTH], bc, acc,
                                          recw + (size_t)(gi + DEPTH) * kStep, gi + DEPTH < n_w, gi + 1 < n_w, t0, lane,
                                          magic);
         }
@@ -354,6 +361,148 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
     if (tid == 0) __hip_atomic_store(&tickets[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Variant for larger M, where re-reading x dominates the on-chip traffic: the four wavefronts of a
+// workgroup walk the SAME quantisation groups, each on its own TW column tiles (a column unit of
+// 4*TW tiles per workgroup), and the group's x fragments are fetched from L2 once per workgroup
+// -- each wavefront fetches the k step equal to its index for all row tiles -- and parked in LDS
+// in operand order, double-buffered, so one barrier per group suffices and every wavefront reads
+// its first MFMA operands with conflict-free 16-byte LDS loads.  Each wavefront owns its output
+// columns outright (no cross-wavefront sum); K may still be split across workgroups, in which
+// case the fp32 partials go to the workspace and splitk_reduce_kernel finishes the job.
+template <int MT, int TW, int DEPTH>
+__global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW == 4 && DEPTH == 2))) ? 2 : 1)) void gemm_ns_kernel(
+    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
+    float *__restrict__ partial, int M, int N, int K, int groups, int S)
+{
+    extern __shared__ float4v lds4[];
+    constexpr int R = 4 * TW * MT;            // accumulator registers per lane
+    constexpr int E4 = R * 16;                // float4 results per wavefront
+    constexpr int U = DEPTH > 2 ? DEPTH : 2;  // unroll: ring position, x buffer and scale buffer are static
+    constexpr int kFragQuads = MT * 4 * 64;   // 16-byte fragments of one group's x tile
+    u32x4 *xa = reinterpret_cast<u32x4 *>(lds4);                  // [2][MT*4][64]
+    float4v *out4 = lds4;                                         // [4 wavefronts][E4], reuses the x tiles after the loop
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane >> 4, c = lane & 15;
+    const int wg_unit = blockIdx.x / S, ks = blockIdx.x % S;
+    const int unit = wg_unit * 4 + wave;                          // this wavefront's column unit
+    const int tiles_total = pad_cols(N) / 16;
+    const bool active = unit * TW < tiles_total;                  // a ragged last workgroup has idle wavefronts
+    const int tile_first = active ? unit * TW : 0;
+    const int nb = tile_first >> 3, t0 = tile_first & 7;
+    const int g_begin = (int)((long long)groups * ks / S);
+    const int g_end = (int)((long long)groups * (ks + 1) / S);
+    const int n = g_end - g_begin;
+
+    // x fragment this lane fetches for the workgroup: k step = wave, row tile mt
+    const _Float16 *xs[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        int row = mt * 16 + c;
+        row = row < M ? row : M - 1;   // rows >= M are never read; their products are never stored
+        xs[mt] = x + (size_t)row * K + wave * 32 + r * 8;
+    }
+    const uint8_t *recw = packed + record_offset(nb, g_begin, groups);   // record of group 0 of the range
+
+    float4v acc[TW][MT];
+#pragma unroll
+    for (int t = 0; t < TW; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[t][mt] = (float4v){0.f, 0.f, 0.f, 0.f};
+
+    u32x4 w[DEPTH][TW];
+    QuantWords qa, qb;
+    u32x4 xreg[MT];
+    u32x4 a[MT][4];
+    const DequantConsts magic = dequant_consts();
+    auto load_quant = [&](QuantWords &q, int gi) {
+        const uint8_t *rec = recw + (size_t)gi * kRecordBytes;
+        q.s = *reinterpret_cast<const u32x4 *>(rec + kScalesOff + c * 16);
+        q.z = *reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4);
+    };
+    auto load_x = [&](int gi) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            xreg[mt] = *reinterpret_cast<const u32x4 *>(xs[mt] + (size_t)(g_begin + gi) * kGroup);
+    };
+    auto park_x = [&](int buf) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) xa[buf * kFragQuads + (mt * 4 + wave) * 64 + lane] = xreg[mt];
+    };
+    auto fetch_a = [&](int buf) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[mt][j] = xa[buf * kFragQuads + (mt * 4 + j) * 64 + lane];
+    };
+
+    half8v bc[4];
+    if (n > 0) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (d < n)
+#pragma unroll
+                for (int t = 0; t < TW; ++t) w[d][t] = load_tile(recw + (size_t)d * kRecordBytes, t0 + t, lane);
+        load_x(0);
+        load_quant(qa, 0);
+        park_x(0);
+        dequant_tile<TW>(bc, w[0][0], tile_quant<TW>(qa, t0), 0, magic);
+    }
+    int i = 0;
+    // steady state: every group here has successors, all loads are unconditional
+    for (; i + U + DEPTH <= n; i += U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int gi = i + u;
+            __syncthreads();   // x tile (u & 1) is parked; nobody still reads the other one
+            load_x(gi + 1);
+            load_quant((u & 1) ? qa : qb, gi + 1);
+            fetch_a(u & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_group<MT, TW, true>(a, (u & 1) ? qb : qa, (u & 1) ? qa : qb, w[u % DEPTH], w[(u + 1) % DEPTH], bc, acc,
+                                        recw + (size_t)(gi + DEPTH) * kRecordBytes, true, true, t0, lane, magic);
+            park_x((u & 1) ^ 1);
+        }
+    }
+    // drain
+#pragma unroll
+    for (int u = 0; u < U + DEPTH - 1; ++u) {
+        const int gi = i + u;
+        if (gi < n) {   // uniform over the workgroup
+            __syncthreads();
+            const bool more = gi + 1 < n;
+            if (more) {
+                load_x(gi + 1);
+                load_quant((u & 1) ? qa : qb, gi + 1);
+            }
+            fetch_a(u & 1);
+            compute_group<MT, TW, false>(a, (u & 1) ? qb : qa, (u & 1) ? qa : qb, w[u % DEPTH], w[(u + 1) % DEPTH], bc, acc,
+                                         recw + (size_t)(gi + DEPTH) * kRecordBytes, gi + DEPTH < n, more, t0, lane, magic);
+            if (more) park_x((u & 1) ^ 1);
+        }
+    }
+
+    // each wavefront turns its accumulators into row-contiguous quads through its own LDS region
+    __syncthreads();   // the x tiles are dead: every wavefront has left the group loop
+    float *mine_lds = reinterpret_cast<float *>(out4 + wave * E4);
+#pragma unroll
+    for (int t = 0; t < TW; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int k4 = 0; k4 < 4; ++k4) mine_lds[((t * MT + mt) * 4 + k4) * 64 + lane] = acc[t][mt][k4];
+    if (!active) return;
+    const int first_col = nb * kBlockCols + t0 * 16;
+    float4v *part4 = reinterpret_cast<float4v *>(partial) + ((size_t)unit * S + ks) * E4;
+#pragma unroll
+    for (int q = 0; q < E4 / 64; ++q) {
+        const int e4 = lane + 64 * q;
+        const float4v v = out4[wave * E4 + e4];
+        if (S == 1) store_quad<MT>(y, v, e4, first_col, M, N);
+        else part4[e4] = v;
+    }
+}
+
 // second pass of the two-kernel split-K mode: one workgroup per column unit
 constexpr int kReduceThreads = 256;
 template <int MT, int TW>
@@ -384,7 +533,8 @@ __global__ __launch_bounds__(kReduceThreads) void splitk_reduce_kernel(const flo
 
 struct Plan {
     int tw;      // column tiles per wavefront (2, 4 or 8); 0 = no compiled variant matches the knobs
-    int nw;      // wavefronts per workgroup (4, 8 or 16), all splitting K for the same columns
+    int nw;      // wavefronts per workgroup: 4, 8 or 16 that split K for the same columns, or 1 for the
+                 // variant whose four wavefronts split the columns and share x fragments through LDS
     int depth;   // groups of codes in flight per wavefront (1, 2 or 4)
     int S;       // workgroups splitting K for one column unit
     int fused;   // S > 1: 1 = last workgroup of a unit sums the partials, 0 = a second kernel does
@@ -403,8 +553,15 @@ static const TunedRow kTuned[] = {
     X(1, 2, 8, 1) X(1, 2, 8, 2) X(1, 2, 8, 4) X(1, 4, 4, 4) X(1, 4, 8, 1) X(1, 4, 8, 2)                         \
     X(1, 8, 8, 1) X(1, 8, 8, 2) X(2, 2, 8, 1) X(2, 2, 8, 2) X(2, 4, 8, 1)
 
+// column-split variant (nw == 0): Y(MT, TW, DEPTH)
+#define W4_NS_VARIANTS(Y)                                                                           \
+    Y(2, 4, 1) Y(2, 4, 2) Y(2, 8, 1) Y(3, 4, 1) Y(3, 4, 2) Y(3, 8, 1) Y(4, 4, 1) Y(4, 4, 2) Y(4, 8, 1) Y(1, 8, 1) Y(1, 8, 2)
+
 static bool variant_exists(int mt, int tw, int nw, int depth)
 {
+#define Y(MT_, TW_, D_) if (nw == 1 && mt == MT_ && tw == TW_ && depth == D_) return true;
+    W4_NS_VARIANTS(Y)
+#undef Y
 #define X(MT_, TW_, NW_, D_) if (mt == MT_ && tw == TW_ && nw == NW_ && depth == D_) return true;
     W4_VARIANTS(X)
 #undef X
@@ -432,13 +589,14 @@ static Plan choose_plan(int mt, int N, int K)
         double best_cost = 1e30;
         for (int tw = 8; tw >= 2; tw >>= 1) {
             if (p.tiles_per_wave > 0 && tw != p.tiles_per_wave) continue;
-            for (int nw = 4; nw <= 16; nw <<= 1) {
-                if (p.waves_per_wg > 0 ? nw != p.waves_per_wg : nw == 16) continue;
+            for (int nw = 1; nw <= 16; nw = (nw == 1 ? 4 : nw << 1)) {
+                if (p.waves_per_wg > 0 ? nw != p.waves_per_wg : (nw == 16 || nw == 1)) continue;
                 for (int depth = 1; depth <= 4; depth <<= 1) {
                     if (p.prefetch_depth > 0 ? depth != p.prefetch_depth : depth != 1) continue;
                     if (!variant_exists(mt, tw, nw, depth)) continue;
-                    const int units = tiles / tw;
-                    int cap = groups / (2 * nw) > 0 ? groups / (2 * nw) : 1;   // two groups per wavefront at least
+                    const int units = nw == 1 ? (tiles / tw + 3) / 4 : tiles / tw;   // workgroups per K split
+                    const int kways = nw == 1 ? 1 : nw;                        // wavefronts sharing a K range
+                    int cap = groups / (2 * kways) > 0 ? groups / (2 * kways) : 1;   // two groups per wavefront at least
                     if (cap > 16) cap = 16;
                     for (int s = forced_s ? forced_s : 1; s <= (forced_s ? forced_s : cap); ++s) {
                         const double fill = (double)units * s / 256.0;         // workgroups per compute unit
@@ -447,7 +605,7 @@ static Plan choose_plan(int mt, int N, int K)
                         cost += 0.05 * mt * (8 / tw - 1);                       // x-fragment reuse
                         cost += (mt > 1 && nw > 4) ? 0.3 : 0.0;                 // registers: big tiles want 4 wavefronts
                         cost += (mt == 1 && nw == 4 && units * s < 384) ? 0.3 : 0.0;
-                        if (groups % (s * nw) != 0) cost += 0.2;               // uneven work per wavefront
+                        if (groups % (s * kways) != 0) cost += 0.2;            // uneven work per wavefront
                         if (cost < best_cost) { best_cost = cost; best = {tw, nw, depth, s, mt == 1}; }
                     }
                 }
@@ -490,6 +648,28 @@ static int launch(const void *x, const void *packed, void *y, int M, int N, int 
     return launch_status();
 }
 
+template <int MT, int TW, int DEPTH>
+static int launch_ns(const void *x, const void *packed, void *y, int M, int N, int K, int S, void *workspace,
+                     hipStream_t stream)
+{
+    static bool lds_ok = false;
+    const size_t lds_bytes = (size_t)TW * MT * 4096;   // four wavefronts' results; the x tiles (MT * 8 KB) fit inside
+    if (!lds_ok && lds_bytes > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ns_kernel<MT, TW, DEPTH>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+            return W4A16_EHIP;
+        lds_ok = true;
+    }
+    const int groups = K / kGroup, units = pad_cols(N) / 16 / TW;
+    float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
+    hipLaunchKernelGGL((gemm_ns_kernel<MT, TW, DEPTH>), dim3((unsigned)((units + 3) / 4 * S)), dim3(256), lds_bytes, stream,
+                       (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, M, N, K, groups, S);
+    if (S > 1)
+        hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
+                           (const float *)partial, (_Float16 *)y, M, N, S);
+    return launch_status();
+}
+
 static int dispatch(int mt, const Plan &pl, const void *x, const void *packed, void *y, int M, int N, int K,
                     void *workspace, hipStream_t stream)
 {
@@ -498,6 +678,11 @@ static int dispatch(int mt, const Plan &pl, const void *x, const void *packed, v
         return launch<MT_, TW_, NW_, D_>(x, packed, y, M, N, K, pl.S, pl.fused, workspace, stream);
     W4_VARIANTS(X)
 #undef X
+#define Y(MT_, TW_, D_)                                                            \
+    if (mt == MT_ && pl.nw == 1 && pl.tw == TW_ && pl.depth == D_)                 \
+        return launch_ns<MT_, TW_, D_>(x, packed, y, M, N, K, pl.S, workspace, stream);
+    W4_NS_VARIANTS(Y)
+#undef Y
     return W4A16_EUNSUP;
 }
 

@@ -79,11 +79,12 @@ def set_knobs(values) -> None:
 
 def candidates(N: int, K: int):
     for tw in (8, 4, 2):
-        for nw in (4, 8, 16):
+        for nw in (1, 4, 8, 16):   # 1 = column-split workgroup sharing x through LDS
             for depth in (1, 2, 4):
                 for S, fused in ((1, 1), (2, 1), (2, 0), (3, 0), (4, 1), (4, 0), (6, 0), (8, 0)):
                     units = (N // 16) // tw
-                    if units * S * nw < 1024 or units * S * nw > 16384 or S * nw > K // G:
+                    waves = units * S * (nw if nw > 1 else 1)
+                    if waves < 768 or waves > 16384 or S * max(nw, 2) > K // G or (nw == 1 and fused == 1 and S > 1):
                         continue
                     yield (tw, nw, depth, S, fused)
 

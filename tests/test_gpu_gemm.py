@@ -43,8 +43,10 @@ def run_gemm(inp, packed, ws, M=None, guard_rows=2):
 
 # (tiles_per_wave, waves_per_wg, prefetch_depth, split_k, fused_reduce); 0 = the library's heuristic.
 # Every row is a kernel variant compiled for all M.
-VARIANTS = [(0, 0, 0, 0, 1), (8, 4, 1, 1, 1), (8, 4, 2, 3, 1), (4, 4, 2, 2, 0), (4, 4, 1, 1, 1), (2, 4, 4, 0, 0),
+VARIANTS = [(0, 0, 0, 0, 2), (8, 4, 1, 1, 1), (8, 4, 2, 3, 1), (4, 4, 2, 2, 0), (4, 4, 1, 1, 1), (2, 4, 4, 0, 0),
             (2, 4, 2, 3, 1), (2, 4, 4, 1, 1), (2, 4, 1, 5, 0)]
+# column-split workgroups (waves_per_wg = 1): compiled for M > 16 (and tw 8 at any M)
+VARIANTS_NS = [(4, 1, 1, 1, 2), (4, 1, 1, 3, 2), (8, 1, 1, 1, 2), (8, 1, 1, 2, 2)]
 VARIANTS_M16 = [(2, 8, 1, 1, 1), (2, 8, 2, 2, 1), (2, 8, 4, 3, 0), (4, 8, 2, 2, 0), (4, 4, 4, 1, 1), (8, 8, 2, 1, 1), (8, 8, 1, 3, 1)]
 
 
@@ -70,7 +72,7 @@ def test_parity_small(M, K, N, big_ws):
     inp = I.make_linear(5000 + M * 7 + K + N, M, K, N)
     packed = B.pack_from_numpy(inp)
     y32, _, _ = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
-    for variant in VARIANTS:
+    for variant in VARIANTS + (VARIANTS_NS if M > 16 else VARIANTS_NS[2:]):
         set_variant(*variant)
         y = run_gemm(inp, packed, big_ws)
         check_gemm(y, y32, f"M={M} K={K} N={N} (tw, nw, depth, split, fused)={variant}")
@@ -112,7 +114,7 @@ def test_exact_inputs_bit_exact(M, big_ws):
     inp = I.make_linear(6000 + M, M, K, N, x_kind="small_int", scale_kind="pow2")
     packed = B.pack_from_numpy(inp)
     _, _, y16 = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
-    for variant in VARIANTS:
+    for variant in VARIANTS + (VARIANTS_NS if M > 16 else VARIANTS_NS[2:]):
         set_variant(*variant)
         y = run_gemm(inp, packed, big_ws)
         assert np.array_equal(y.view(np.uint16), y16.view(np.uint16)), (M, variant)
