@@ -139,6 +139,17 @@ def time_steps(fn, steps: int, warmup: int, use_graph: bool, copies: int):
     return start.elapsed_time(stop) / steps
 
 
+def measured_traffic():
+    """HBM bytes per gate_up launch from the committed rocprofv3 PMC summary (FETCH_SIZE and
+    WRITE_SIZE runs, calibrated against a copy kernel of known size); None if it is not there."""
+    path = os.path.join(ROOT, "profiles", "w4a16_gemm_llama70b_m1_hbm_traffic.txt")
+    try:
+        vals = dict(ln.strip().split("=") for ln in open(path) if "_BYTES_PER_LAUNCH_GATE_UP_M1=" in ln)
+        return int(vals["FETCH_BYTES_PER_LAUNCH_GATE_UP_M1"]) + int(vals["WRITE_BYTES_PER_LAUNCH_GATE_UP_M1"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def cpu_baseline(shapes, label: str):
     """The CPU oracle, as it stands, on the same layer at M = 1: every GEMM once with all host
     threads, and the two small GEMMs once more on a single thread (to bound the run)."""
