@@ -180,6 +180,14 @@ __device__ __forceinline__ void compute_group(const u32x4 (&a)[MT][4], const Qua
 // consecutive columns of one output row: round to fp16 and store them as one 8-byte word.
 // Fragment order: e = ((t * MT + mt) * 4 + i) * 64 + lane, row = mt*16 + 4*(lane/16) + i,
 // column = first_col + t*16 + lane%16.
+// output row of quad e4 (see the fragment order below); partial sums of rows >= M are never moved
+template <int MT>
+__device__ __forceinline__ int quad_row(int e4)
+{
+    const int reg = e4 >> 4;
+    return ((reg >> 2) % MT) * 16 + 4 * (((e4 * 4) & 63) >> 4) + (reg & 3);
+}
+
 template <int MT>
 __device__ __forceinline__ void store_quad(_Float16 *__restrict__ y, float4v v, int e4, int first_col, int M, int N)
 {
@@ -334,13 +342,15 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
         float4v *mine4 = reinterpret_cast<float4v *>(mine);
 #pragma unroll
         for (int q = 0; q < Q; ++q)
-            if (!kRagged || tid + kThreads * q < E4) mine4[tid + kThreads * q] = sum[q];
+            if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
+                mine4[tid + kThreads * q] = sum[q];
         return;
     }
     // the last workgroup of this column unit to arrive sums all S partials in split order
 #pragma unroll
     for (int q = 0; q < Q; ++q)
-        if (!kRagged || tid + kThreads * q < E4) store_partial(mine + (size_t)(tid + kThreads * q) * 4, sum[q]);
+        if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
+            store_partial(mine + (size_t)(tid + kThreads * q) * 4, sum[q]);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partials have reached device scope
     __syncthreads();
     if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -352,7 +362,7 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
     for (int s = 0; s < S; ++s) {
 #pragma unroll
         for (int q = 0; q < Q; ++q)
-            if (!kRagged || tid + kThreads * q < E4)
+            if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
                 sum[q] += load_partial(all + ((size_t)s * E4 + tid + kThreads * q) * 4);
     }
 #pragma unroll
@@ -499,7 +509,7 @@ __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW
         const int e4 = lane + 64 * q;
         const float4v v = out4[wave * E4 + e4];
         if (S == 1) store_quad<MT>(y, v, e4, first_col, M, N);
-        else part4[e4] = v;
+        else if (quad_row<MT>(e4) < M) part4[e4] = v;
     }
 }
 
@@ -521,7 +531,8 @@ __global__ __launch_bounds__(kReduceThreads) void splitk_reduce_kernel(const flo
     for (int s = 0; s < S; ++s) {
 #pragma unroll
         for (int q = 0; q < Q; ++q)
-            if (!kRagged || tid + kReduceThreads * q < E4) sum[q] += all[(size_t)s * E4 + tid + kReduceThreads * q];
+            if ((!kRagged || tid + kReduceThreads * q < E4) && quad_row<MT>(tid + kReduceThreads * q) < M)
+                sum[q] += all[(size_t)s * E4 + tid + kReduceThreads * q];
     }
 #pragma unroll
     for (int q = 0; q < Q; ++q)
