@@ -20,7 +20,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kHeadDim = 128;
 constexpr int kKeyBlock = 32;
-constexpr int kVStride = 132;   // halves per LDS row of V (264 B): the four 16-lane groups hit disjoint banks
+constexpr int kVtStride = 36;    // halves per LDS row of the transposed V tile (72 B: 8-byte aligned, 16 rows -> 16 banks)
+constexpr int kOStride = 132;    // floats per LDS row of the output staging tile
 constexpr int kAttnThreads = 256;
 constexpr int kRowsPad = 64;
 constexpr int kMaxSplits = 16;   // key ranges per head (the merge keeps one value per range in registers)
@@ -36,7 +37,10 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     float *__restrict__ part_ml, int M, int P, int Hq, int Hkv,
     float scale_log2e, int nsplit)
 {
-    __shared__ _Float16 vs[2][kKeyBlock][kVStride];   // V tile of the current and of the next key block
+    // V tile of the current and of the next key block, TRANSPOSED: vt[d][key ^ 4*((d>>4)&7)], so a
+    // lane's eight keys for one head-dim column are two 8-byte reads
+    __shared__ _Float16 vt[2][kHeadDim][kVtStride];
+    __shared__ float ot[4][16][kOStride];   // per-wavefront output tile for row-contiguous stores
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane >> 4, c = lane & 15;
@@ -56,54 +60,58 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     for (int j = 0; j < 4; ++j)
         qf[j] = *reinterpret_cast<const half8v *>(q + ((size_t)my_row * Hq + h) * kHeadDim + 32 * j + 8 * r);
 
-    float m_run = NEG_INF, l_run = 0.f;
     float4v o[8];
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) o[dt] = (float4v){0.f, 0.f, 0.f, 0.f};
 
     // the workgroup stages each 32-key V block once (32 B per thread) and all four wavefronts read it
     const int st_key = tid >> 3, st_chunk = (tid & 7) * 2;
+    const _Float16 *vbase = v + (size_t)kvh * kHeadDim + st_chunk * 8;
+    const _Float16 *kbase = k + (size_t)kvh * kHeadDim + 8 * r;
     auto load_v = [&](int blk, u32x4 (&reg)[2]) {
-        int src = min(blk * kKeyBlock + st_key, T - 1);
-        const _Float16 *p = v + (size_t)src * kv_stride + kvh * kHeadDim + st_chunk * 8;
+        int src = blk * kKeyBlock + st_key;
+        if (blk * kKeyBlock + kKeyBlock > T) src = min(src, T - 1);   // uniform: only the last block is ragged
+        const _Float16 *p = vbase + (size_t)src * kv_stride;
         reg[0] = *reinterpret_cast<const u32x4 *>(p);
         reg[1] = *reinterpret_cast<const u32x4 *>(p + 8);
     };
     auto store_v = [&](int buf, const u32x4 (&reg)[2]) {
-        u32x2 *dst = reinterpret_cast<u32x2 *>(&vs[buf][st_key][st_chunk * 8]);
-        dst[0] = (u32x2){reg[0][0], reg[0][1]};
-        dst[1] = (u32x2){reg[0][2], reg[0][3]};
-        dst[2] = (u32x2){reg[1][0], reg[1][1]};
-        dst[3] = (u32x2){reg[1][2], reg[1][3]};
+        // this thread holds V[st_key][st_chunk*8 .. +15]: scatter it down 16 rows of the transposed tile
+        const int col = st_key ^ (4 * ((st_chunk >> 1) & 7));
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            uint32_t word = reg[i >> 3][(i >> 1) & 3];
+            uint16_t h16 = (i & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xFFFFu);
+            vt[buf][st_chunk * 8 + i][col] = __builtin_bit_cast(_Float16, h16);
+        }
     };
     // K fragments (first operand of S^T): tile a = keys key0 + 0..15, tile b = key0 + 16..31
     auto load_k = [&](int blk, half8v (&fa)[4], half8v (&fb)[4]) {
         const int key0 = blk * kKeyBlock;
-        const _Float16 *ka = k + (size_t)min(key0 + c, T - 1) * kv_stride + kvh * kHeadDim + 8 * r;
-        const _Float16 *kb = k + (size_t)min(key0 + 16 + c, T - 1) * kv_stride + kvh * kHeadDim + 8 * r;
+        int ra = key0 + c, rb = key0 + 16 + c;
+        if (key0 + kKeyBlock > T) {   // uniform: only the last block is ragged
+            ra = min(ra, T - 1);
+            rb = min(rb, T - 1);
+        }
+        const _Float16 *ka = kbase + (size_t)ra * kv_stride;
+        const _Float16 *kb = kbase + (size_t)rb * kv_stride;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             fa[j] = *reinterpret_cast<const half8v *>(ka + 32 * j);
             fb[j] = *reinterpret_cast<const half8v *>(kb + 32 * j);
         }
     };
-    u32x4 vreg[2];
-    half8v kfa[4], kfb[4];
-    if (b0 < b1) {
-        load_v(b0, vreg);
-        load_k(b0, kfa, kfb);
-        store_v(0, vreg);
-    }
+    // Two register sets for K fragments and for V rows give a prefetch distance of two key blocks:
+    // a set is refilled for block b+2 as soon as block b has consumed it.
+    u32x4 vreg0[2], vreg1[2];
+    half8v k0a[4], k0b[4], k1a[4], k1b[4];
+    float m_run = NEG_INF, l_run = 0.f;
     int cur = 0;
-    for (int blk = b0; blk < b1; ++blk) {
+    auto block = [&](int blk, half8v (&kfa)[4], half8v (&kfb)[4], u32x4 (&v_store)[2], u32x4 (&v_load)[2]) {
         const int key0 = blk * kKeyBlock;
+        const int ahead = blk + 2 < b1 ? blk + 2 : b1 - 1;   // clamped: loads stay unconditional
         __syncthreads();   // tile `cur` is complete; nobody still reads the other tile
-        // prefetch the next block's V rows and K fragments (the last block re-reads itself: the
-        // loads stay unconditional so that their completion can be counted exactly)
-        const int nxt = blk + 1 < b1 ? blk + 1 : blk;
-        half8v nfa[4], nfb[4];
-        load_v(nxt, vreg);
-        load_k(nxt, nfa, nfb);
+        load_v(ahead, v_load);
         __builtin_amdgcn_sched_barrier(0);
         float4v sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -111,15 +119,22 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
             sa = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfa[j], qf[j], sa, 0, 0, 0);
             sb = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfb[j], qf[j], sb, 0, 0, 0);
         }
+        load_k(ahead, kfa, kfb);   // the fragments just consumed make room for block blk + 2
+        __builtin_amdgcn_sched_barrier(0);
         // lane (r, c): sa[i] = score of key key0 + 4r + i, sb[i] = key0 + 16 + 4r + i, query row my_row
         float s[8];
+        if (key0 + kKeyBlock <= P) {   // uniform: a block of committed prefix keys, all visible
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int key = key0 + 4 * r + (i & 3) + (i >> 2) * 16;
-            bool vis = key < P;
-            if (!vis && key < T) vis = mask[(size_t)my_row * M + (key - P)] != 0;
-            float raw = (i < 4) ? sa[i & 3] : sb[i & 3];
-            s[i] = vis ? raw * scale_log2e : NEG_INF;
+            for (int i = 0; i < 8; ++i) s[i] = ((i < 4) ? sa[i & 3] : sb[i & 3]) * scale_log2e;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int key = key0 + 4 * r + (i & 3) + (i >> 2) * 16;
+                bool vis = key < P;
+                if (!vis && key < T) vis = mask[(size_t)my_row * M + (key - P)] != 0;
+                float raw = (i < 4) ? sa[i & 3] : sb[i & 3];
+                s[i] = vis ? raw * scale_log2e : NEG_INF;
+            }
         }
         float m_blk = s[0];
 #pragma unroll
@@ -141,30 +156,39 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
         psum += __shfl_xor(psum, 32, 64);
         l_run = l_run * alpha + psum;
         m_run = m_new;
-        // accumulator rows are 4r + i: fetch their rescale factors from the lanes that own those rows
-        float a_row[4];
+        // accumulator rows are 4r + i: when some row's running maximum moved, fetch the rescale factors
+        // from the lanes that own those rows (after the first few blocks this is rare)
+        if (__any(alpha != 1.0f)) {
+            float a_row[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a_row[i] = __shfl(alpha, 4 * r + i, 64);
+            for (int i = 0; i < 4; ++i) a_row[i] = __shfl(alpha, 4 * r + i, 64);
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[dt][i] *= a_row[i];
+        }
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-            half8v vb;   // second operand: V[key slot][dt*16 + c], slots = keys 4r+p and 16+4r+p
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                vb[p] = vs[cur][4 * r + p][dt * 16 + c];
-                vb[4 + p] = vs[cur][16 + 4 * r + p][dt * 16 + c];
-            }
-            float4v acc = o[dt];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) acc[i] *= a_row[i];
-            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, vb, acc, 0, 0, 0);
+            // second operand: V[key slot][dt*16 + c], slots = keys 4r+p (tile a) and 16+4r+p (tile b)
+            const _Float16 *rowp = &vt[cur][dt * 16 + c][0];
+            u32x2 lo = *reinterpret_cast<const u32x2 *>(rowp + 4 * (r ^ dt));
+            u32x2 hi = *reinterpret_cast<const u32x2 *>(rowp + 4 * ((4 + r) ^ dt));
+            u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, __builtin_bit_cast(half8v, both), o[dt], 0, 0, 0);
         }
-        store_v(cur ^ 1, vreg);
+        store_v(cur ^ 1, v_store);   // V rows of block blk + 1, requested two blocks ago
         cur ^= 1;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            kfa[j] = nfa[j];
-            kfb[j] = nfb[j];
-        }
+    };
+    if (b0 < b1) {
+        load_v(b0, vreg0);
+        load_k(b0, k0a, k0b);
+        load_v(b0 + 1 < b1 ? b0 + 1 : b0, vreg1);
+        load_k(b0 + 1 < b1 ? b0 + 1 : b0, k1a, k1b);
+        store_v(0, vreg0);
+    }
+    for (int blk = b0; blk < b1; blk += 2) {
+        block(blk, k0a, k0b, vreg1, vreg0);
+        if (blk + 1 < b1) block(blk + 1, k1a, k1b, vreg0, vreg1);
     }
 
     // o[dt][i] belongs to query row row0 + 4r + i, column dt*16 + c
@@ -174,31 +198,39 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
         l_row[i] = __shfl(l_run, 4 * r + i, 64);
         m_row[i] = __shfl(m_run, 4 * r + i, 64);
     }
-    if (nsplit == 1) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int row = row0 + 4 * r + i;
-            if (row < M) {
-                float inv = 1.f / l_row[i];
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt)
-                    out[((size_t)row * Hq + h) * kHeadDim + dt * 16 + c] = (_Float16)(o[dt][i] * inv);
-            }
-        }
-        return;
-    }
-    // partial state of this key range: unnormalised output rows plus (running max, running sum);
-    // a second kernel merges the ranges (the kernel boundary makes them visible, at no fence cost)
-    float *po = part_o + (size_t)blockIdx.x * kRowsPad * kHeadDim;
-    float *pml = part_ml + (size_t)blockIdx.x * kRowsPad * 2;
+    // turn the fragment-ordered tile into rows: lane (r, c) owns rows 4r+i, columns dt*16+c
+    const bool last = nsplit == 1;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        int row = row0 + 4 * r + i;
+        const float inv = last ? 1.f / l_row[i] : 1.f;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) po[row * kHeadDim + dt * 16 + c] = o[dt][i];
-        if (c == 0) {
-            pml[row * 2] = m_row[i];
-            pml[row * 2 + 1] = l_row[i];
+        for (int dt = 0; dt < 8; ++dt) ot[wave][4 * r + i][dt * 16 + c] = o[dt][i] * inv;
+    }
+    // (same wavefront writes and reads its own tile: LDS keeps program order, no barrier needed)
+    float *po = part_o + (size_t)blockIdx.x * kRowsPad * kHeadDim;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int idx = u * 64 + lane, trow = idx >> 5, d4 = idx & 31;
+        const int row = row0 + trow;
+        if (row < M) {
+            const float4v val = *reinterpret_cast<const float4v *>(&ot[wave][trow][d4 * 4]);
+            if (last) {
+                typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+                half4v hv = {(_Float16)val[0], (_Float16)val[1], (_Float16)val[2], (_Float16)val[3]};
+                *reinterpret_cast<half4v *>(out + ((size_t)row * Hq + h) * kHeadDim + d4 * 4) = hv;
+            } else {
+                *reinterpret_cast<float4v *>(po + row * kHeadDim + d4 * 4) = val;
+            }
+        }
+    }
+    if (!last && c == 0) {
+        // partial state of this key range: a second kernel merges the ranges (the kernel boundary
+        // makes them visible, at no fence cost)
+        float *pml = part_ml + (size_t)blockIdx.x * kRowsPad * 2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            pml[(row0 + 4 * r + i) * 2] = m_row[i];
+            pml[(row0 + 4 * r + i) * 2 + 1] = l_row[i];
         }
     }
 }
