@@ -51,8 +51,10 @@ const char *w4a16_strerror(int code);
  * "tiles_per_wave" (0 = heuristic, else 2, 4 or 8 sixteen-column tiles per wavefront),
  * "waves_per_wg" (0 = heuristic; 4, 8 or 16 wavefronts per workgroup that split K; 1 selects the
  * variant whose four wavefronts split the columns and share x through LDS), "prefetch_depth" (0 =
- * heuristic, else 1, 2 or 4 groups of codes in flight per wavefront); a combination that is not
- * compiled makes w4a16_gemm return W4A16_EUNSUP,
+ * heuristic, else 1, 2 or 4 groups of codes in flight per wavefront), "k_sets" (0 = heuristic, else
+ * 1, 2 or 3: forces the M > 16 variant whose workgroup has 4 * k_sets wavefronts, four column
+ * quarters times k_sets interleaved sets of quantisation groups; waves_per_wg and fused_reduce are
+ * then ignored); a combination that is not compiled makes w4a16_gemm return W4A16_EUNSUP,
  * "attn_splits" (0 = heuristic, else the number of key ranges per head in tree_verify_attn).
  * Returns W4A16_EINVAL for an unknown name or an out-of-range value.  Not thread-safe. */
 int w4a16_set_param(const char *name, int value);

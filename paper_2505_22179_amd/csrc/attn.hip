@@ -44,7 +44,12 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane >> 4, c = lane & 15;
-    const int h = blockIdx.x / nsplit, sp = blockIdx.x % nsplit;
+    // Workgroups are dealt to the eight XCDs round-robin by index, and each XCD has its own L2.
+    // Renumber so that the workgroups of one KV head (consecutive logical ids) share an XCD and
+    // its K/V rows are fetched into one L2 instead of all eight.
+    int lid = blockIdx.x;
+    if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int h = lid / nsplit, sp = lid % nsplit;
     const int kvh = h / (Hq / Hkv);
     const int T = P + M;
     const int nblk = (T + kKeyBlock - 1) / kKeyBlock;
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
         for (int dt = 0; dt < 8; ++dt) ot[wave][4 * r + i][dt * 16 + c] = o[dt][i] * inv;
     }
     // (same wavefront writes and reads its own tile: LDS keeps program order, no barrier needed)
-    float *po = part_o + (size_t)blockIdx.x * kRowsPad * kHeadDim;
+    float *po = part_o + (size_t)lid * kRowsPad * kHeadDim;
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
         const int idx = u * 64 + lane, trow = idx >> 5, d4 = idx & 31;
@@ -226,7 +231,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     if (!last && c == 0) {
         // partial state of this key range: a second kernel merges the ranges (the kernel boundary
         // makes them visible, at no fence cost)
-        float *pml = part_ml + (size_t)blockIdx.x * kRowsPad * 2;
+        float *pml = part_ml + (size_t)lid * kRowsPad * 2;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             pml[(row0 + 4 * r + i) * 2] = m_row[i];

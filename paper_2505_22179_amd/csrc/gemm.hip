@@ -76,6 +76,21 @@ __device__ __forceinline__ u32x4 load_tile(const uint8_t *rec, int t, int lane)
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(rec + t * 1024 + lane * 16));
 }
 
+// a pointer the compiler can keep in scalar registers: both halves are read from the first lane
+typedef const __attribute__((address_space(1))) uint8_t *global_bytes;   // global, not generic: no flat loads
+__device__ __forceinline__ global_bytes uniform_ptr(const uint8_t *p)
+{
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (global_bytes)(((uint64_t)hi << 32) | lo);
+}
+template <typename T>
+__device__ __forceinline__ T load_global(global_bytes p)
+{
+    return *(const __attribute__((address_space(1))) T *)p;
+}
+
 template <int MT>
 __device__ __forceinline__ void load_operands(GroupOperands<MT> &f, const uint8_t *rec,
                                               const _Float16 *const (&xp)[MT], int g, int c)
@@ -513,6 +528,192 @@ __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW
     }
 }
 
+// One quantisation group for this wavefront's TW column tiles, tile after tile with no software
+// pipelining: few live registers, so that several wavefronts share a SIMD and the hardware overlaps
+// one wavefront's code expansion (vector ALU) with another's matrix instructions.  The code
+// registers of a tile are refilled, REFILL permitting, as soon as the tile is expanded.
+template <int MT, int TW, bool ALWAYS_REFILL>
+__device__ __forceinline__ void compute_group_lean(const u32x4 (&a)[MT][4], QuantWords &f, u32x4 (&w)[TW],
+                                                   float4v (&acc)[TW][MT], const uint8_t *refill_rec, bool refill,
+                                                   int t0, int c, int lane, const DequantConsts &magic)
+{
+    const TileQuant<TW> q = tile_quant<TW>(f, t0);
+    const global_bytes rec = uniform_ptr(refill_rec);
+    const uint32_t tile_off = (uint32_t)(t0 * 1024 + lane * 16);
+    if (ALWAYS_REFILL || refill) {
+        f.s = load_global<u32x4>(rec + (uint32_t)(kScalesOff + c * 16));
+        f.z = load_global<uint32_t>(rec + (uint32_t)(kZerosOff + c * 4));
+    }
+#pragma unroll
+    for (int t = 0; t < TW; ++t) {
+        const uint32_t z = (q.zbits >> (4 * t)) & 0xFu;
+        const uint32_t zz = z | (z << 16);
+        const half2v zneg = as_h2(zz | 0xE400E400u);            // -(1024 + z)
+        const half2v zneg16 = as_h2((zz << 4) | 0xD400D400u);   // -(64 + z)
+        float4v part[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) part[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const half8v b = dequant8(w[t][j], zneg, zneg16, magic);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                part[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a[mt][j]), b, part[mt], 0, 0, 0);
+        }
+        if (ALWAYS_REFILL || refill)
+            w[t] = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4 *)(rec + (tile_off + (uint32_t)(t * 1024))));
+        uint32_t s2 = q.sw[t >> 1];
+        _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (s2 >> 16) : (s2 & 0xFFFFu)));
+        float s = (float)sh;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[t][mt] += s * part[mt];
+        // tiles stay apart: expanding several ahead of the matrix pipe would cost the registers
+        // that the co-resident wavefronts need, and they are what hides this tile's latency
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// High-occupancy variant for M > 16.  A workgroup of 4*KS wavefronts owns a column unit of 4*TW
+// tiles; wavefront (kset, colq) = (index / 4, index % 4) works on the TW tiles of column quarter
+// colq and on every KS-th quantisation group starting at kset, so KS wavefronts share each SIMD.
+// Per step the workgroup parks the x fragments of KS consecutive groups in LDS (operand order,
+// double-buffered, one barrier per step); the KS partial sums of a column meet in LDS at the end.
+template <int MT, int TW, int KS, int DEPTH>
+__global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
+    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
+    float *__restrict__ partial, int M, int N, int K, int groups, int S)
+{
+    extern __shared__ float4v lds4[];
+    constexpr int R = 4 * TW * MT;                 // accumulator registers per lane
+    constexpr int E4 = R * 16;                     // float4 results per wavefront
+    constexpr int kBufQuads = KS * MT * 4 * 64;    // 16-byte fragments of one step's x tiles
+    u32x4 *xa = reinterpret_cast<u32x4 *>(lds4);   // [2][KS][MT*4][64]
+    float4v *out4 = lds4;                          // [4*KS wavefronts][E4], reuses the x tiles after the loop
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int colq = wave & 3, kset = wave >> 2;
+    const int r = lane >> 4, c = lane & 15;
+    const int wg_unit = blockIdx.x / S, ks = blockIdx.x % S;
+    const int unit = wg_unit * 4 + colq;
+    const int tiles_total = pad_cols(N) / 16;
+    const bool active = unit * TW < tiles_total;   // a ragged last workgroup has idle column quarters
+    const int tile_first = active ? unit * TW : 0;
+    const int nb = tile_first >> 3, t0 = tile_first & 7;
+    const int g_begin = (int)((long long)groups * ks / S);
+    const int g_end = (int)((long long)groups * (ks + 1) / S);
+    const int n = g_end - g_begin;
+    const int steps = (n + KS - 1) / KS;           // workgroup-uniform
+    const int full = n / KS;                       // steps in which every k set has a group
+    const int mine = n > kset ? (n - kset + KS - 1) / KS : 0;   // groups of this wavefront: g_begin + kset + KS*i
+
+    // x fragment this lane fetches for its k set: k step colq, row tile mt (byte offsets from a
+    // wavefront-uniform base, so the loads address with a scalar base and a 32-bit lane offset)
+    uint32_t xoff[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        int row = mt * 16 + c;
+        row = row < M ? row : M - 1;   // rows >= M are never read; their products are never stored
+        xoff[mt] = (uint32_t)(((size_t)row * K + colq * 32 + r * 8) * sizeof(_Float16));
+    }
+    const uint8_t *xbase = reinterpret_cast<const uint8_t *>(x + (size_t)(g_begin + kset) * kGroup);
+    const uint8_t *recw = packed + record_offset(nb, g_begin + (kset < n ? kset : 0), groups);   // group 0 of this wavefront
+
+    float4v acc[TW][MT];
+#pragma unroll
+    for (int t = 0; t < TW; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[t][mt] = (float4v){0.f, 0.f, 0.f, 0.f};
+
+    u32x4 w[DEPTH][TW];
+    QuantWords qw[DEPTH];
+    u32x4 xreg[MT];
+    u32x4 a[MT][4];
+    const DequantConsts magic = dequant_consts();
+    auto load_x = [&](int i) {
+        const global_bytes xb = uniform_ptr(xbase + (size_t)i * (KS * kGroup * sizeof(_Float16)));
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) xreg[mt] = load_global<u32x4>(xb + xoff[mt]);
+    };
+    auto park_x = [&](int buf) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) xa[buf * kBufQuads + ((kset * MT + mt) * 4 + colq) * 64 + lane] = xreg[mt];
+    };
+    auto fetch_a = [&](int buf) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[mt][j] = xa[buf * kBufQuads + ((kset * MT + mt) * 4 + j) * 64 + lane];
+    };
+    auto rec_of = [&](int i) { return recw + (size_t)i * (KS * kRecordBytes); };
+
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+        if (d < mine) {
+            const uint8_t *rec = rec_of(d);
+            qw[d].s = *reinterpret_cast<const u32x4 *>(rec + kScalesOff + c * 16);
+            qw[d].z = *reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4);
+#pragma unroll
+            for (int t = 0; t < TW; ++t) w[d][t] = load_tile(rec, t0 + t, lane);
+        }
+    if (mine > 0) {
+        load_x(0);
+        park_x(0);
+    }
+    int i = 0;
+    // steady state: every wavefront has a group in this step and DEPTH steps further on
+    for (; i + 2 * DEPTH <= full; i += DEPTH) {
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
+            const int gi = i + u;
+            __syncthreads();   // x tiles of step gi are parked; nobody still reads the other buffer
+            load_x(gi + 1);
+            fetch_a(gi & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_group_lean<MT, TW, true>(a, qw[u], w[u], acc, rec_of(gi + DEPTH), true, t0, c, lane, magic);
+            park_x((gi & 1) ^ 1);
+        }
+    }
+    // drain
+#pragma unroll
+    for (int u = 0; u < 2 * DEPTH; ++u) {
+        const int gi = i + u;
+        if (gi < steps) {   // uniform over the workgroup
+            __syncthreads();
+            const bool more = gi + 1 < mine;
+            if (more) load_x(gi + 1);
+            if (gi < mine) {
+                fetch_a(gi & 1);
+                compute_group_lean<MT, TW, false>(a, qw[u % DEPTH], w[u % DEPTH], acc, rec_of(gi + DEPTH),
+                                                  gi + DEPTH < mine, t0, c, lane, magic);
+            }
+            if (more) park_x((gi & 1) ^ 1);
+        }
+    }
+
+    // every wavefront parks its accumulators in fragment order; the KS partial sums of a column
+    // quarter are then added and leave as row-contiguous quads
+    __syncthreads();   // the x tiles are dead: every wavefront has left the group loop
+    float *mine_lds = reinterpret_cast<float *>(out4 + wave * E4);
+#pragma unroll
+    for (int t = 0; t < TW; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int k4 = 0; k4 < 4; ++k4) mine_lds[((t * MT + mt) * 4 + k4) * 64 + lane] = acc[t][mt][k4];
+    __syncthreads();
+    if (!active) return;
+    const int first_col = nb * kBlockCols + t0 * 16;
+    float4v *part4 = reinterpret_cast<float4v *>(partial) + ((size_t)unit * S + ks) * E4;
+    for (int q = kset; q < E4 / 64; q += KS) {
+        const int e4 = lane + 64 * q;
+        float4v v = out4[colq * E4 + e4];
+#pragma unroll
+        for (int s = 1; s < KS; ++s) v += out4[(s * 4 + colq) * E4 + e4];
+        if (S == 1) store_quad<MT>(y, v, e4, first_col, M, N);
+        else if (quad_row<MT>(e4) < M) part4[e4] = v;
+    }
+}
+
 // second pass of the two-kernel split-K mode: one workgroup per column unit
 constexpr int kReduceThreads = 256;
 template <int MT, int TW>
@@ -549,9 +750,11 @@ struct Plan {
     int depth;   // groups of codes in flight per wavefront (1, 2 or 4)
     int S;       // workgroups splitting K for one column unit
     int fused;   // S > 1: 1 = last workgroup of a unit sums the partials, 0 = a second kernel does
+    int ks;      // 0, or the number of interleaved K sets of the high-occupancy column-split variant
+                 // (4*ks wavefronts per workgroup; nw is then 0)
 };
 
-struct TunedRow { int N, K, mt, tw, nw, depth, S, fused; };
+struct TunedRow { int N, K, mt, tw, nw, depth, S, fused, ks; };
 static const TunedRow kTuned[] = {
 #include "tuned_plans.inc"
 };
@@ -568,8 +771,22 @@ static const TunedRow kTuned[] = {
 #define W4_NS_VARIANTS(Y)                                                                           \
     Y(2, 4, 1) Y(2, 4, 2) Y(2, 8, 1) Y(3, 4, 1) Y(3, 4, 2) Y(3, 8, 1) Y(4, 4, 1) Y(4, 4, 2) Y(4, 8, 1) Y(1, 8, 1) Y(1, 8, 2)
 
-static bool variant_exists(int mt, int tw, int nw, int depth)
+// high-occupancy column-split variant: Z(MT, TW, KS, DEPTH)
+#define W4_CS_VARIANTS(Z)                                                                           \
+    Z(2, 2, 1, 2) Z(2, 2, 2, 2) Z(2, 4, 1, 2) Z(2, 4, 2, 2) Z(2, 8, 1, 2)                                     \
+    Z(3, 2, 1, 2) Z(3, 2, 2, 2) Z(3, 4, 1, 2)                                                         \
+    Z(4, 2, 1, 2) Z(4, 2, 2, 2) Z(4, 4, 1, 2)                                                         \
+    Z(4, 8, 1, 1) Z(3, 8, 1, 2) Z(3, 8, 1, 1) Z(4, 4, 1, 1) Z(3, 4, 2, 1) Z(2, 4, 2, 1) Z(2, 8, 2, 1) Z(2, 4, 3, 1) Z(4, 4, 2, 1) Z(3, 4, 1, 1) \
+    Z(2, 2, 3, 2) Z(3, 2, 3, 1) Z(2, 2, 3, 1) Z(4, 2, 2, 1) Z(3, 2, 2, 1) Z(2, 2, 2, 1)
+
+static bool variant_exists(int mt, int tw, int nw, int depth, int ks = 0)
 {
+#define Z(MT_, TW_, KS_, D_) if (ks == KS_ && mt == MT_ && tw == TW_ && depth == D_) return true;
+    if (ks > 0) {
+        W4_CS_VARIANTS(Z)
+        return false;
+    }
+#undef Z
 #define Y(MT_, TW_, D_) if (nw == 1 && mt == MT_ && tw == TW_ && depth == D_) return true;
     W4_NS_VARIANTS(Y)
 #undef Y
@@ -588,12 +805,19 @@ static Plan choose_plan(int mt, int N, int K)
 {
     const Params &p = params();
     const int groups = K / kGroup, tiles = pad_cols(N) / 16;
-    Plan best = {0, 0, 0, 0, 1};
-    const bool free_choice = !p.tiles_per_wave && !p.waves_per_wg && !p.prefetch_depth && !p.split_k;
+    Plan best = {0, 0, 0, 0, 1, 0};
+    const bool free_choice = !p.tiles_per_wave && !p.waves_per_wg && !p.prefetch_depth && !p.split_k && !p.k_sets;
     if (free_choice) {
         for (const TunedRow &r : kTuned)
-            if (r.N == N && r.K == K && r.mt == mt && variant_exists(mt, r.tw, r.nw, r.depth))
-                best = {r.tw, r.nw, r.depth, r.S, r.fused};
+            if (r.N == N && r.K == K && r.mt == mt && variant_exists(mt, r.tw, r.nw, r.depth, r.ks))
+                best = {r.tw, r.nw, r.depth, r.S, r.fused, r.ks};
+    }
+    if (p.k_sets > 0) {   // forced: the high-occupancy column-split variant
+        const int tw = p.tiles_per_wave ? p.tiles_per_wave : 4, depth = p.prefetch_depth ? p.prefetch_depth : 2;
+        int s = p.split_k > 0 ? p.split_k : 1;
+        if (s > groups) s = groups;
+        if (variant_exists(mt, tw, 0, depth, p.k_sets)) best = {tw, 0, depth, s, 0, p.k_sets};
+        return best;
     }
     if (best.tw == 0) {
         const int forced_s = p.split_k > 0 ? (p.split_k < groups ? p.split_k : groups) : 0;
@@ -617,7 +841,7 @@ static Plan choose_plan(int mt, int N, int K)
                         cost += (mt > 1 && nw > 4) ? 0.3 : 0.0;                 // registers: big tiles want 4 wavefronts
                         cost += (mt == 1 && nw == 4 && units * s < 384) ? 0.3 : 0.0;
                         if (groups % (s * kways) != 0) cost += 0.2;            // uneven work per wavefront
-                        if (cost < best_cost) { best_cost = cost; best = {tw, nw, depth, s, mt == 1}; }
+                        if (cost < best_cost) { best_cost = cost; best = {tw, nw, depth, s, mt == 1, 0}; }
                     }
                 }
             }
@@ -681,9 +905,41 @@ static int launch_ns(const void *x, const void *packed, void *y, int M, int N, i
     return launch_status();
 }
 
+template <int MT, int TW, int KS, int DEPTH>
+static int launch_cs(const void *x, const void *packed, void *y, int M, int N, int K, int S, void *workspace,
+                     hipStream_t stream)
+{
+    static bool lds_ok = false;
+    const size_t lds_bytes = (size_t)KS * TW * MT * 4096;   // 4*KS wavefronts' results; the x tiles (KS * MT * 8 KB) fit inside
+    if (lds_bytes > 160 * 1024) return W4A16_EUNSUP;
+    if (!lds_ok && lds_bytes > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_cs_kernel<MT, TW, KS, DEPTH>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
+            return W4A16_EHIP;
+        lds_ok = true;
+    }
+    const int groups = K / kGroup, units = pad_cols(N) / 16 / TW;
+    float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
+    hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH>), dim3((unsigned)((units + 3) / 4 * S)), dim3(256 * KS),
+                       lds_bytes, stream, (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, M, N, K,
+                       groups, S);
+    if (S > 1)
+        hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
+                           (const float *)partial, (_Float16 *)y, M, N, S);
+    return launch_status();
+}
+
 static int dispatch(int mt, const Plan &pl, const void *x, const void *packed, void *y, int M, int N, int K,
                     void *workspace, hipStream_t stream)
 {
+#define Z(MT_, TW_, KS_, D_)                                                       \
+    if (mt == MT_ && pl.ks == KS_ && pl.tw == TW_ && pl.depth == D_)               \
+        return launch_cs<MT_, TW_, KS_, D_>(x, packed, y, M, N, K, pl.S, workspace, stream);
+    if (pl.ks > 0) {
+        W4_CS_VARIANTS(Z)
+        return W4A16_EUNSUP;
+    }
+#undef Z
 #define X(MT_, TW_, NW_, D_)                                                       \
     if (mt == MT_ && pl.tw == TW_ && pl.nw == NW_ && pl.depth == D_)               \
         return launch<MT_, TW_, NW_, D_>(x, packed, y, M, N, K, pl.S, pl.fused, workspace, stream);

@@ -30,7 +30,8 @@ struct Params {
     int attn_splits = 0;   // 0 = heuristic
     int tiles_per_wave = 0;   // 0 = heuristic, else 2, 4 or 8
     int waves_per_wg = 0;     // 0 = heuristic, else 4, 8 or 16
-    int prefetch_depth = 0;   // 0 = heuristic, else 1, 2 or 4
+    int prefetch_depth = 0;   // 0 = heuristic, else 1, 2, 3 or 4
+    int k_sets = 0;           // 0 = heuristic, else 1..3: force the high-occupancy column-split kernel
 };
 Params &params();
 

@@ -160,6 +160,7 @@ static int *param_slot(const char *name)
     if (!strcmp(name, "tiles_per_wave")) return &p.tiles_per_wave;
     if (!strcmp(name, "waves_per_wg")) return &p.waves_per_wg;
     if (!strcmp(name, "prefetch_depth")) return &p.prefetch_depth;
+    if (!strcmp(name, "k_sets")) return &p.k_sets;
     return nullptr;
 }
 

@@ -2,7 +2,7 @@
 
 For every (layer shape, M bucket of 16 rows) it times each compiled kernel variant -- tiles per
 wavefront, wavefronts per workgroup, prefetch depth, K splits, fused or two-kernel reduction --
-through the library's ablation knobs, on weights rotated through more than 512 MB so the
+through the library's ablation knobs (for M > 16 also the high-occupancy column-split variant and its K sets), on weights rotated through more than 512 MB so the
 last-level cache never serves them, and writes the winners as rows of csrc/tuned_plans.inc.  The
 library falls back to a generic rule for shapes that have no row.
 
@@ -22,7 +22,7 @@ from . import binding as B
 from . import inputs as I
 
 G = 128
-KNOBS = ("tiles_per_wave", "waves_per_wg", "prefetch_depth", "split_k", "fused_reduce")
+KNOBS = ("tiles_per_wave", "waves_per_wg", "prefetch_depth", "split_k", "fused_reduce", "k_sets")
 
 
 def weight_bytes(K: int, N: int) -> int:
@@ -77,7 +77,16 @@ def set_knobs(values) -> None:
         B.w4a16_set_param(k, v)
 
 
-def candidates(N: int, K: int):
+def candidates(N: int, K: int, M: int):
+    if M > 16:   # high-occupancy column-split workgroups (k_sets > 0), compiled for M > 16 only
+        for tw in (8, 4, 2):
+            for ks in (1, 2, 3):
+                for depth in (1, 2):
+                    for S in (1, 2, 3, 4, 5, 6, 8):
+                        wgs = ((N // 16) // tw + 3) // 4 * S
+                        if wgs < 160 or wgs > 2048 or S * ks * 2 > K // G:
+                            continue
+                        yield (tw, 0, depth, S, 0, ks)
     for tw in (8, 4, 2):
         for nw in (1, 4, 8, 16):   # 1 = column-split workgroup sharing x through LDS
             for depth in (1, 2, 4):
@@ -86,7 +95,7 @@ def candidates(N: int, K: int):
                     waves = units * S * (nw if nw > 1 else 1)
                     if waves < 768 or waves > 16384 or S * max(nw, 2) > K // G or (nw == 1 and fused == 1 and S > 1):
                         continue
-                    yield (tw, nw, depth, S, fused)
+                    yield (tw, nw, depth, S, fused, 0)
 
 
 def tune_shape(name: str, K: int, N: int, Ms, ws, log):
@@ -98,7 +107,7 @@ def tune_shape(name: str, K: int, N: int, Ms, ws, log):
         x = torch.randn((M, K), device="cuda").to(torch.float16)
         y = torch.empty((M, N), dtype=torch.float16, device="cuda")
         res = {}
-        for plan in candidates(N, K):
+        for plan in candidates(N, K, M):
             set_knobs(plan)
             try:
                 res[plan] = time_graph(lambda c: B.w4a16_gemm(x, packs[c], y, M, N, K, G, ws), copies)
@@ -107,9 +116,9 @@ def tune_shape(name: str, K: int, N: int, Ms, ws, log):
         best = min(res.values())
         top = sorted(res.items(), key=lambda kv: kv[1])[:4]
         log(f"{name} K={K} N={N} M={M}: ideal {wb / 8e6:.1f} us | " +
-            " ".join(f"[tw{p[0]} nw{p[1]} d{p[2]} S{p[3]}{'f' if p[4] else 'k'} {us:.1f}us]" for p, us in top))
+            " ".join(f"[tw{p[0]} {'ks%d' % p[5] if p[5] else 'nw%d' % p[1]} d{p[2]} S{p[3]}{'f' if p[4] else 'k'} {us:.1f}us]" for p, us in top))
         per_bucket[(M + 15) // 16].append({p: us / best for p, us in res.items()})
-    set_knobs((0, 0, 0, 0, 2))
+    set_knobs((0, 0, 0, 0, 2, 0))
     rows = []
     for mt, runs in sorted(per_bucket.items()):
         common = set(runs[0])
@@ -140,7 +149,7 @@ def main() -> None:
             rows += tune_shape(f"{which}.{name}", K, N, Ms, ws, log)
     with open(args.out, "w") as f:
         f.write("// Tuned launch shapes, written by `python -m paper_2505_22179_amd.tune` on an MI355X.\n")
-        f.write("// {N, K, row tiles, tiles per wavefront, wavefronts per workgroup, prefetch depth, K splits, fused reduce}\n")
+        f.write("// {N, K, row tiles, tiles per wavefront, wavefronts per workgroup, prefetch depth, K splits, fused reduce, K sets}\n")
         for r in rows:
             f.write("{" + ", ".join(str(v) for v in r) + "},\n")
     log(f"wrote {len(rows)} rows to {args.out}")

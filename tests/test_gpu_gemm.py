@@ -24,7 +24,7 @@ def big_ws():
 @pytest.fixture(autouse=True)
 def _reset_knobs():
     yield
-    for k in ("split_k", "tiles_per_wave", "waves_per_wg", "prefetch_depth"):
+    for k in ("split_k", "tiles_per_wave", "waves_per_wg", "prefetch_depth", "k_sets"):
         B.w4a16_set_param(k, 0)
     B.w4a16_set_param("fused_reduce", 2)
 
@@ -91,6 +91,37 @@ def test_parity_wide_workgroups(M, K, N, big_ws):
     for variant in VARIANTS_M16:
         set_variant(*variant)
         check_gemm(run_gemm(inp, packed, big_ws), y32, f"M={M} K={K} N={N} variant={variant}")
+        assert np.array_equal(run_gemm(ex, ex_packed, big_ws).view(np.uint16), ex16.view(np.uint16)), variant
+
+
+# high-occupancy column-split workgroups, M > 16 only: (tiles_per_wave, k_sets, prefetch_depth, split_k)
+VARIANTS_CS = [(2, 1, 2, 1), (2, 2, 2, 1), (2, 2, 2, 3), (4, 1, 2, 1), (4, 1, 2, 2), (4, 2, 2, 1)]
+
+
+def set_cs_variant(tw, ks, depth, split):
+    B.w4a16_set_param("tiles_per_wave", tw)
+    B.w4a16_set_param("k_sets", ks)
+    B.w4a16_set_param("prefetch_depth", depth)
+    B.w4a16_set_param("split_k", split)
+
+
+@pytest.mark.parametrize("M,K,N", [s for s in SMALL if s[0] > 16] + [(40, 640, 136), (64, 8192, 2056)])
+def test_parity_high_occupancy(M, K, N, big_ws):
+    """the variant whose workgroup interleaves several K sets per column quarter; covers K ranges
+    shorter than the prefetch ring, group counts that do not divide by the number of sets, idle
+    column quarters in the last workgroup, and K split across workgroups on top"""
+    print(f"gemm parity (high occupancy) M={M} K={K} N={N}", flush=True)
+    inp = I.make_linear(5800 + M + K + N, M, K, N)
+    packed = B.pack_from_numpy(inp)
+    y32, _, _ = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
+    ex = I.make_linear(5900 + M, M, K, N, x_kind="small_int", scale_kind="pow2")
+    ex_packed = B.pack_from_numpy(ex)
+    _, _, ex16 = R.w4a16_gemm(ex.x, ex.qweight, ex.scales, ex.qzeros, 128, want64=False)
+    for variant in VARIANTS_CS:
+        if variant[0] == 4 and variant[1] == 2 and M > 32:
+            continue   # compiled for at most two row tiles
+        set_cs_variant(*variant)
+        check_gemm(run_gemm(inp, packed, big_ws), y32, f"M={M} K={K} N={N} (tw, ks, depth, split)={variant}")
         assert np.array_equal(run_gemm(ex, ex_packed, big_ws).view(np.uint16), ex16.view(np.uint16)), variant
 
 
