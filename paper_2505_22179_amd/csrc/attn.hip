@@ -284,7 +284,7 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const float *__res
 static int attn_splits(int M, int P, int Hq)
 {
     int nblk = (P + M + kKeyBlock - 1) / kKeyBlock;
-    int want = params().attn_splits > 0 ? params().attn_splits : (512 + Hq - 1) / Hq;
+    int want = params().attn_splits > 0 ? params().attn_splits : (256 + Hq - 1) / Hq;   // about one workgroup per compute unit
     if (want > nblk) want = nblk;
     if (want > kMaxSplits) want = kMaxSplits;
     return want < 1 ? 1 : want;

@@ -819,6 +819,16 @@ static Plan choose_plan(int mt, int N, int K)
         if (variant_exists(mt, tw, 0, depth, p.k_sets)) best = {tw, 0, depth, s, 0, p.k_sets};
         return best;
     }
+    if (best.tw == 0 && free_choice && mt > 1) {
+        // no measured row: the high-occupancy variant with two K sets, about one workgroup per
+        // compute unit, wide tiles only when the columns alone fill the chip
+        const int tw = tiles / 16 >= 200 ? 4 : 2;
+        const int units = (tiles / tw + 3) / 4;
+        int s = (256 + units / 2) / units;
+        if (s > groups / 4) s = groups / 4;   // two groups per K set at least
+        if (s < 1) s = 1;
+        if (variant_exists(mt, tw, 0, 1, 2)) best = {tw, 0, 1, s, 0, 2};
+    }
     if (best.tw == 0) {
         const int forced_s = p.split_k > 0 ? (p.split_k < groups ? p.split_k : groups) : 0;
         double best_cost = 1e30;

@@ -82,7 +82,7 @@ def candidates(N: int, K: int, M: int):
         for tw in (8, 4, 2):
             for ks in (1, 2, 3):
                 for depth in (1, 2):
-                    for S in (1, 2, 3, 4, 5, 6, 8):
+                    for S in (1, 2, 3, 4, 5, 6, 8, 10, 12, 16):
                         wgs = ((N // 16) // tw + 3) // 4 * S
                         if wgs < 160 or wgs > 2048 or S * ks * 2 > K // G:
                             continue
