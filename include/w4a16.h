@@ -54,7 +54,10 @@ const char *w4a16_strerror(int code);
  * heuristic, else 1, 2 or 4 groups of codes in flight per wavefront), "k_sets" (0 = heuristic, else
  * 1, 2 or 3: forces the M > 16 variant whose workgroup has 4 * k_sets wavefronts, four column
  * quarters times k_sets interleaved sets of quantisation groups; waves_per_wg and fused_reduce are
- * then ignored); a combination that is not compiled makes w4a16_gemm return W4A16_EUNSUP,
+ * then ignored), "flat_groups" (0 = heuristic, else 4, 7 or 8: forces the M <= 4 variant in which a
+ * wavefront owns that many quantisation groups and requests all of their weights up front; needs
+ * K / 128 == split_k * waves_per_wg * flat_groups); a combination that is not compiled, or that
+ * does not fit the shape, makes w4a16_gemm return W4A16_EUNSUP,
  * "attn_splits" (0 = heuristic, else the number of key ranges per head in tree_verify_attn).
  * Returns W4A16_EINVAL for an unknown name or an out-of-range value.  Not thread-safe. */
 int w4a16_set_param(const char *name, int value);
@@ -102,6 +105,14 @@ int w4a16_dequant(const void *packed, float *W, int N, int K, int G, void *strea
  * have been initialised with w4a16_workspace_init. */
 int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, int G,
                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Measurement aid, not part of the method: enqueues a kernel that only reads the first
+ * bytes - bytes % 16 bytes of `buf` with 16-byte streaming loads (one 32 KB chunk per workgroup)
+ * and writes nothing, except -- practically never -- one 32-bit word to `sink` (4-byte aligned, device)
+ * so that the loads cannot be dropped.  Timed beside w4a16_gemm on the same packed buffer it
+ * gives the read bandwidth this GPU reaches at that size, the ceiling the paper's memory-bound
+ * decoding argument (section 2.1) refers to. */
+int w4a16_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
 
 /* Scratch needed by tree_verify_attn for these sizes (partial softmax states of the key splits). */
 size_t tree_verify_attn_workspace_bytes(int M, int P, int Hq, int Hkv, int D);

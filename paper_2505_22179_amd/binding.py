@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("W4A16_LIB") or os.path.join(_HERE, "lib", "libw4a16.s
 EXPORTS = (
     "w4a16_version", "w4a16_strerror", "w4a16_set_param", "w4a16_get_param", "w4a16_packed_bytes",
     "w4a16_workspace_bytes", "w4a16_workspace_init", "w4a16_pack", "w4a16_unpack", "w4a16_dequant",
-    "w4a16_gemm", "tree_verify_attn_workspace_bytes", "tree_verify_attn",
+    "w4a16_gemm", "w4a16_read_probe", "tree_verify_attn_workspace_bytes", "tree_verify_attn",
 )
 
 _lib = None
@@ -49,6 +49,7 @@ def load() -> ctypes.CDLL:
     L.w4a16_unpack.argtypes = [vp, vp, vp, vp, i, i, i, vp]
     L.w4a16_dequant.argtypes = [vp, vp, i, i, i, vp]
     L.w4a16_gemm.argtypes = [vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.w4a16_read_probe.argtypes = [vp, sz, vp, vp]
     L.tree_verify_attn_workspace_bytes.restype = sz
     L.tree_verify_attn_workspace_bytes.argtypes = [i, i, i, i, i]
     L.tree_verify_attn.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, ctypes.c_float, vp, sz, vp]
@@ -124,6 +125,10 @@ def w4a16_dequant(packed, W, N: int, K: int, G: int = 128) -> None:
 def w4a16_gemm(x, packed, y, M: int, N: int, K: int, G: int, workspace) -> None:
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().w4a16_gemm(_ptr(x), _ptr(packed), _ptr(y), M, N, K, G, _ptr(workspace), nbytes, _stream()), "w4a16_gemm")
+
+
+def w4a16_read_probe(buf, nbytes: int, sink) -> None:
+    _check(load().w4a16_read_probe(_ptr(buf), int(nbytes), _ptr(sink), _stream()), "w4a16_read_probe")
 
 
 def tree_verify_attn(q, k, v, mask, out, M: int, P: int, Hq: int, Hkv: int, D: int, scale: float, workspace) -> None:

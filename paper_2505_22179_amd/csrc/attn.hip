@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ k, const _Float16 *__restrict__ v,
     const uint8_t *__restrict__ mask, _Float16 *__restrict__ out, float *__restrict__ part_o,
     float *__restrict__ part_ml, int M, int P, int Hq, int Hkv,
-    float scale_log2e, int nsplit)
+    float scale_log2e, int nsplit, int bq, int brem)
 {
     // V tile of the current and of the next key block, TRANSPOSED: vt[d][key ^ 4*((d>>4)&7)], so a
     // lane's eight keys for one head-dim column are two 8-byte reads
@@ -52,8 +52,8 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     const int h = lid / nsplit, sp = lid % nsplit;
     const int kvh = h / (Hq / Hkv);
     const int T = P + M;
-    const int nblk = (T + kKeyBlock - 1) / kKeyBlock;
-    const int b0 = (int)((long long)nblk * sp / nsplit), b1 = (int)((long long)nblk * (sp + 1) / nsplit);
+    // key blocks of this split: bq = nblk / nsplit each, the first brem = nblk % nsplit one more (host-computed)
+    const int b0 = sp * bq + (sp < brem ? sp : brem), b1 = b0 + bq + (sp < brem ? 1 : 0);
     const int row0 = wave * 16;
     const int my_row = min(row0 + c, M - 1);   // rows >= M repeat row M-1 and are never stored
     const size_t kv_stride = (size_t)Hkv * kHeadDim;
@@ -326,9 +326,10 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
     float *part_o = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
     float *part_ml = part_o + (size_t)Hq * ns * kRowsPad * kHeadDim;
     const float scale_log2e = scale * 1.4426950408889634f;
+    const int nblk = (P + M + kKeyBlock - 1) / kKeyBlock;
     hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)(Hq * ns)), dim3(kAttnThreads), 0, (hipStream_t)stream,
                        (const _Float16 *)q, (const _Float16 *)k, (const _Float16 *)v, mask, (_Float16 *)out,
-                       part_o, part_ml, M, P, Hq, Hkv, scale_log2e, ns);
+                       part_o, part_ml, M, P, Hq, Hkv, scale_log2e, ns, nblk / ns, nblk % ns);
     if (ns > 1) {
         const int quads = M * Hq * (kHeadDim / 4);
         hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0,

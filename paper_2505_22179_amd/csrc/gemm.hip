@@ -217,10 +217,21 @@ __device__ __forceinline__ void store_quad(_Float16 *__restrict__ y, float4v v, 
     }
 }
 
+constexpr int kFlatMaxRows = 4;   // most rows the all-loads-up-front variant stages
+
 // wavefronts per SIMD the register allocator must leave room for: one workgroup has to fit
 constexpr int min_waves_per_simd(int mt, int tw, int nw, int depth)
 {
     return nw / 4;
+}
+
+// Groups [begin, end) of K split ks: every split gets gq = groups / S groups and the first
+// grem = groups % S one more.  Quotient and remainder come from the host: no division on the GPU.
+struct KRange { int begin, end; };
+__device__ __forceinline__ KRange k_range(int ks, int gq, int grem)
+{
+    const int begin = ks * gq + (ks < grem ? ks : grem);
+    return {begin, begin + gq + (ks < grem ? 1 : 0)};
 }
 
 // coherent-at-device-scope accesses for the split-K partials: they bypass the per-XCD L2's
@@ -238,28 +249,102 @@ __device__ __forceinline__ float4v load_partial(const float *p)
     return v;
 }
 
+// Epilogue shared by the K-split kernels: the NW wavefronts' accumulators are summed through LDS
+// in wave order; the sum is stored (S == 1), handed to the second kernel as a partial, or -- fused
+// mode -- published with device-scope stores, after which the last workgroup of the column unit to
+// take a ticket adds the S partials in split order and stores the result.
+template <int MT, int TW, int NW>
+__device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4v *lds4, uint32_t &ticket_sh,
+                                            _Float16 *__restrict__ y, float *__restrict__ partial,
+                                            uint32_t *__restrict__ tickets, int M, int N, int S, int fused, int unit,
+                                            int ks, int nb, int t0, int tid, int lane, int wave)
+{
+    constexpr int kThreads = NW * 64;
+    constexpr int R = 4 * TW * MT;
+    constexpr int E4 = R * 16;
+    constexpr int Q = (E4 + kThreads - 1) / kThreads;
+    constexpr bool kRagged = (E4 % kThreads) != 0;
+    // sum the wavefronts' accumulators through LDS in wave order
+    float *lds = reinterpret_cast<float *>(lds4);
+#pragma unroll
+    for (int t = 0; t < TW; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                lds[(wave * R + (t * MT + mt) * 4 + i) * 64 + lane] = acc[t][mt][i];
+    __syncthreads();
+    const int first_col = nb * kBlockCols + t0 * 16;
+    float4v sum[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        int e4 = tid + kThreads * q;
+        float4v v = (float4v){0.f, 0.f, 0.f, 0.f};
+        if (!kRagged || e4 < E4) {
+            v = lds4[e4];
+#pragma unroll
+            for (int w2 = 1; w2 < NW; ++w2) v += lds4[w2 * E4 + e4];
+        }
+        sum[q] = v;
+    }
+    if (S == 1) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            if (!kRagged || tid + kThreads * q < E4) store_quad<MT>(y, sum[q], tid + kThreads * q, first_col, M, N);
+        return;
+    }
+    float *mine = partial + ((size_t)unit * S + ks) * E4 * 4;
+    if (!fused) {
+        float4v *mine4 = reinterpret_cast<float4v *>(mine);
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
+                mine4[tid + kThreads * q] = sum[q];
+        return;
+    }
+    // the last workgroup of this column unit to arrive sums all S partials in split order
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+        if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
+            store_partial(mine + (size_t)(tid + kThreads * q) * 4, sum[q]);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partials have reached device scope
+    __syncthreads();
+    if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (ticket_sh != (uint32_t)(S - 1)) return;
+    const float *all = partial + (size_t)unit * S * E4 * 4;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) sum[q] = (float4v){0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < S; ++s) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
+                sum[q] += load_partial(all + ((size_t)s * E4 + tid + kThreads * q) * 4);
+    }
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+        if (!kRagged || tid + kThreads * q < E4) store_quad<MT>(y, sum[q], tid + kThreads * q, first_col, M, N);
+    if (tid == 0) __hip_atomic_store(&tickets[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // MT row tiles of 16, TW column tiles per wavefront, NW wavefronts per workgroup (all on the same
 // columns, each on its own quantisation groups), DEPTH groups of codes in flight per wavefront.
 template <int MT, int TW, int NW, int DEPTH>
 __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) void gemm_kernel(
     const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
-    float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused)
+    float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused,
+    int gq, int grem)
 {
     extern __shared__ float4v lds4[];
     __shared__ uint32_t ticket_sh;
-    constexpr int kThreads = NW * 64;
-    constexpr int R = 4 * TW * MT;   // accumulator registers per lane
-    constexpr int E4 = R * 16;       // float4 results per column unit (R * 64 floats)
-    constexpr int Q = (E4 + kThreads - 1) / kThreads;   // float4 per thread in the epilogue
-    constexpr bool kRagged = (E4 % kThreads) != 0;       // small units: some threads own no quad
     constexpr int U = DEPTH > 2 ? DEPTH : 2;             // unroll: ring position and x-fragment buffer are static
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps the group loop scalar
     const int r = lane >> 4, c = lane & 15;
-    const int unit = blockIdx.x / S, ks = blockIdx.x % S;        // column unit = TW tiles
+    const int unit = blockIdx.y, ks = blockIdx.x;                // column unit = TW tiles; grid = (S, units)
     const int nb = (unit * TW) >> 3, t0 = (unit * TW) & 7;
-    const int g_begin = (int)((long long)groups * ks / S);
-    const int g_end = (int)((long long)groups * (ks + 1) / S);
+    const KRange kr = k_range(ks, gq, grem);
+    const int g_begin = kr.begin, g_end = kr.end;
 
     const _Float16 *xp[MT];
 #pragma unroll
@@ -323,67 +408,88 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
         }
     }
 
-    // sum the wavefronts' accumulators through LDS in wave order
-    float *lds = reinterpret_cast<float *>(lds4);
+    finish_unit<MT, TW, NW>(acc, lds4, ticket_sh, y, partial, tickets, M, N, S, fused, unit, ks, nb, t0, tid, lane, wave);
+}
+
+// Variant for M <= 4 and short K ranges: a wavefront owns exactly NG quantisation groups and asks
+// for ALL of their codes, scales and zero-points before it computes anything, so the whole weight
+// range of the workgroup is in flight at once and nothing in the arithmetic can delay a load.
+// The x rows of the workgroup's K range (NW * NG groups) are fetched first -- the oldest loads, so
+// waiting for them never waits for weights -- and parked in LDS, from where every wavefront reads
+// its first MFMA operands (rows >= M repeat row M-1; their products are never stored).
+template <int TW, int NW, int NG>
+__global__ __launch_bounds__(NW * 64) void gemm_flat_kernel(
+    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
+    float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused)
+{
+    extern __shared__ float4v lds4[];
+    __shared__ uint32_t ticket_sh;
+    constexpr int kThreads = NW * 64;
+    constexpr int kRow16 = NW * NG * 16;          // 16-byte words of x per staged row
+    constexpr int kRowStride16 = kRow16 + 1;      // LDS row stride (one word of padding)
+    constexpr int XL = (kFlatMaxRows * kRow16 + kThreads - 1) / kThreads;   // x words per thread
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane >> 4, c = lane & 15;
+    const int unit = blockIdx.y, ks = blockIdx.x;   // grid = (S, units); groups == S * NW * NG
+    const int nb = (unit * TW) >> 3, t0 = (unit * TW) & 7;
+    const int g_begin = ks * (NW * NG);
+
+    // 1. x rows of this K range
+    u32x4 xr[XL];
+    u32x4 *xs = reinterpret_cast<u32x4 *>(lds4);
 #pragma unroll
-    for (int t = 0; t < TW; ++t)
+    for (int l = 0; l < XL; ++l) {
+        const int u = tid + kThreads * l, row = u / kRow16, col = u % kRow16;
+        if (row < M) xr[l] = *reinterpret_cast<const u32x4 *>(x + (size_t)row * K + (size_t)g_begin * kGroup + col * 8);
+    }
+    // 2. every weight byte of this wavefront: groups g_begin + wave + NW * i
+    const uint8_t *recw = packed + record_offset(nb, g_begin + wave, groups);
+    u32x4 w[NG][TW];
+    QuantWords qw[NG];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+    for (int i = 0; i < NG; ++i) {
+        const uint8_t *rec = recw + (size_t)i * (NW * kRecordBytes);
+        qw[i].s = *reinterpret_cast<const u32x4 *>(rec + kScalesOff + c * 16);
+        qw[i].z = *reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                lds[(wave * R + (t * MT + mt) * 4 + i) * 64 + lane] = acc[t][mt][i];
+        for (int t = 0; t < TW; ++t) w[i][t] = load_tile(rec, t0 + t, lane);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // 3. park x
+#pragma unroll
+    for (int l = 0; l < XL; ++l) {
+        const int u = tid + kThreads * l, row = u / kRow16, col = u % kRow16;
+        if (row < M) xs[row * kRowStride16 + col] = xr[l];
+    }
     __syncthreads();
-    const int first_col = nb * kBlockCols + t0 * 16;
-    float4v sum[Q];
+
+    float4v acc[TW][1];
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        int e4 = tid + kThreads * q;
-        float4v v = (float4v){0.f, 0.f, 0.f, 0.f};
-        if (!kRagged || e4 < E4) {
-            v = lds4[e4];
+    for (int t = 0; t < TW; ++t) acc[t][0] = (float4v){0.f, 0.f, 0.f, 0.f};
+    const DequantConsts magic = dequant_consts();
+    const u32x4 *xrow = xs + (c < M ? c : M - 1) * kRowStride16 + r;
 #pragma unroll
-            for (int w2 = 1; w2 < NW; ++w2) v += lds4[w2 * E4 + e4];
+    for (int i = 0; i < NG; ++i) {
+        u32x4 a[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = xrow[(wave + NW * i) * 16 + j * 4];
+        const TileQuant<TW> q = tile_quant<TW>(qw[i], t0);
+#pragma unroll
+        for (int t = 0; t < TW; ++t) {
+            half8v b[4];
+            dequant_tile<TW>(b, w[i][t], q, t, magic);
+            float4v part = (float4v){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a[j]), b[j], part, 0, 0, 0);
+            uint32_t s2 = q.sw[t >> 1];
+            _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (s2 >> 16) : (s2 & 0xFFFFu)));
+            acc[t][0] += (float)sh * part;
         }
-        sum[q] = v;
     }
-    if (S == 1) {
-#pragma unroll
-        for (int q = 0; q < Q; ++q)
-            if (!kRagged || tid + kThreads * q < E4) store_quad<MT>(y, sum[q], tid + kThreads * q, first_col, M, N);
-        return;
-    }
-    float *mine = partial + (size_t)blockIdx.x * E4 * 4;
-    if (!fused) {
-        float4v *mine4 = reinterpret_cast<float4v *>(mine);
-#pragma unroll
-        for (int q = 0; q < Q; ++q)
-            if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
-                mine4[tid + kThreads * q] = sum[q];
-        return;
-    }
-    // the last workgroup of this column unit to arrive sums all S partials in split order
-#pragma unroll
-    for (int q = 0; q < Q; ++q)
-        if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
-            store_partial(mine + (size_t)(tid + kThreads * q) * 4, sum[q]);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partials have reached device scope
-    __syncthreads();
-    if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    if (ticket_sh != (uint32_t)(S - 1)) return;
-    const float *all = partial + (size_t)unit * S * E4 * 4;
-#pragma unroll
-    for (int q = 0; q < Q; ++q) sum[q] = (float4v){0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < S; ++s) {
-#pragma unroll
-        for (int q = 0; q < Q; ++q)
-            if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
-                sum[q] += load_partial(all + ((size_t)s * E4 + tid + kThreads * q) * 4);
-    }
-#pragma unroll
-    for (int q = 0; q < Q; ++q)
-        if (!kRagged || tid + kThreads * q < E4) store_quad<MT>(y, sum[q], tid + kThreads * q, first_col, M, N);
-    if (tid == 0) __hip_atomic_store(&tickets[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();   // the x rows are dead: the epilogue reuses their LDS
+    finish_unit<1, TW, NW>(acc, lds4, ticket_sh, y, partial, tickets, M, N, S, fused, unit, ks, nb, t0, tid, lane, wave);
 }
 
 // Variant for larger M, where re-reading x dominates the on-chip traffic: the four wavefronts of a
@@ -397,7 +503,7 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
 template <int MT, int TW, int DEPTH>
 __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW == 4 && DEPTH == 2))) ? 2 : 1)) void gemm_ns_kernel(
     const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
-    float *__restrict__ partial, int M, int N, int K, int groups, int S)
+    float *__restrict__ partial, int M, int N, int K, int groups, int S, int gq, int grem)
 {
     extern __shared__ float4v lds4[];
     constexpr int R = 4 * TW * MT;            // accumulator registers per lane
@@ -409,14 +515,14 @@ __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane >> 4, c = lane & 15;
-    const int wg_unit = blockIdx.x / S, ks = blockIdx.x % S;
+    const int wg_unit = blockIdx.y, ks = blockIdx.x;   // grid = (S, workgroup units)
     const int unit = wg_unit * 4 + wave;                          // this wavefront's column unit
     const int tiles_total = pad_cols(N) / 16;
     const bool active = unit * TW < tiles_total;                  // a ragged last workgroup has idle wavefronts
     const int tile_first = active ? unit * TW : 0;
     const int nb = tile_first >> 3, t0 = tile_first & 7;
-    const int g_begin = (int)((long long)groups * ks / S);
-    const int g_end = (int)((long long)groups * (ks + 1) / S);
+    const KRange kr = k_range(ks, gq, grem);
+    const int g_begin = kr.begin, g_end = kr.end;
     const int n = g_end - g_begin;
 
     // x fragment this lane fetches for the workgroup: k step = wave, row tile mt
@@ -581,7 +687,7 @@ __device__ __forceinline__ void compute_group_lean(const u32x4 (&a)[MT][4], Quan
 template <int MT, int TW, int KS, int DEPTH>
 __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
     const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
-    float *__restrict__ partial, int M, int N, int K, int groups, int S)
+    float *__restrict__ partial, int M, int N, int K, int groups, int S, int gq, int grem)
 {
     extern __shared__ float4v lds4[];
     constexpr int R = 4 * TW * MT;                 // accumulator registers per lane
@@ -593,14 +699,14 @@ __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int colq = wave & 3, kset = wave >> 2;
     const int r = lane >> 4, c = lane & 15;
-    const int wg_unit = blockIdx.x / S, ks = blockIdx.x % S;
+    const int wg_unit = blockIdx.y, ks = blockIdx.x;   // grid = (S, workgroup units)
     const int unit = wg_unit * 4 + colq;
     const int tiles_total = pad_cols(N) / 16;
     const bool active = unit * TW < tiles_total;   // a ragged last workgroup has idle column quarters
     const int tile_first = active ? unit * TW : 0;
     const int nb = tile_first >> 3, t0 = tile_first & 7;
-    const int g_begin = (int)((long long)groups * ks / S);
-    const int g_end = (int)((long long)groups * (ks + 1) / S);
+    const KRange kr = k_range(ks, gq, grem);
+    const int g_begin = kr.begin, g_end = kr.end;
     const int n = g_end - g_begin;
     const int steps = (n + KS - 1) / KS;           // workgroup-uniform
     const int full = n / KS;                       // steps in which every k set has a group
@@ -752,12 +858,33 @@ struct Plan {
     int fused;   // S > 1: 1 = last workgroup of a unit sums the partials, 0 = a second kernel does
     int ks;      // 0, or the number of interleaved K sets of the high-occupancy column-split variant
                  // (4*ks wavefronts per workgroup; nw is then 0)
+    int ng;      // 0, or the groups per wavefront of the all-loads-up-front variant (M <= 4 only;
+                 // K / 128 == S * nw * ng exactly)
 };
 
 struct TunedRow { int N, K, mt, tw, nw, depth, S, fused, ks; };
 static const TunedRow kTuned[] = {
 #include "tuned_plans.inc"
 };
+struct TunedFlatRow { int N, K, m_max, tw, nw, ng, S, fused; };   // consulted first when M <= m_max
+static const TunedFlatRow kTunedFlat[] = {
+    {0, 0, 0, 0, 0, 0, 0, 0},
+#include "tuned_flat.inc"
+};
+
+// all-loads-up-front variant: F(TW, NW, NG)
+#define W4_FLAT_VARIANTS(F)                                                                         \
+    F(2, 8, 8) F(2, 16, 4) F(2, 4, 8) F(2, 8, 4) F(2, 4, 4) F(2, 8, 7) F(2, 4, 7)                                 \
+    F(4, 8, 8) F(4, 16, 4) F(4, 4, 8) F(4, 8, 4) F(4, 4, 4) F(4, 8, 7) F(4, 4, 7)                                 \
+    F(8, 8, 4) F(8, 4, 4)
+
+static bool flat_variant_exists(int tw, int nw, int ng)
+{
+#define F(TW_, NW_, NG_) if (tw == TW_ && nw == NW_ && ng == NG_) return true;
+    W4_FLAT_VARIANTS(F)
+#undef F
+    return false;
+}
 
 // the kernel variants that are compiled: X(MT, TW, NW, DEPTH)
 #define W4_VARIANTS_SMALL(X, MT)                                                                    \
@@ -801,22 +928,37 @@ static bool variant_exists(int mt, int tw, int nw, int depth, int ks = 0)
 // K splits across workgroups as that allows (each costs an fp32 partial round trip that grows
 // with M), and as many tiles per wavefront as that allows (each x fragment is reused per tile).
 // Any knob set through w4a16_set_param overrides the corresponding field.
-static Plan choose_plan(int mt, int N, int K)
+static Plan choose_plan(int M, int N, int K)
 {
     const Params &p = params();
+    const int mt = (M + 15) / 16;
     const int groups = K / kGroup, tiles = pad_cols(N) / 16;
-    Plan best = {0, 0, 0, 0, 1, 0};
+    Plan best = {0, 0, 0, 0, 1, 0, 0};
+    if (p.flat_groups > 0) {   // forced: the all-loads-up-front variant
+        const int tw = p.tiles_per_wave ? p.tiles_per_wave : 2, nw = p.waves_per_wg ? p.waves_per_wg : 8;
+        const int s = p.split_k > 0 ? p.split_k : 1;
+        if (M <= kFlatMaxRows && flat_variant_exists(tw, nw, p.flat_groups) && groups == s * nw * p.flat_groups)
+            best = {tw, nw, 0, s, p.fused_reduce == 2 ? 1 : p.fused_reduce, 0, p.flat_groups};
+        return best;
+    }
     const bool free_choice = !p.tiles_per_wave && !p.waves_per_wg && !p.prefetch_depth && !p.split_k && !p.k_sets;
     if (free_choice) {
+        for (const TunedFlatRow &r : kTunedFlat)
+            if (r.N == N && r.K == K && M <= r.m_max && M <= kFlatMaxRows && flat_variant_exists(r.tw, r.nw, r.ng) &&
+                groups == r.S * r.nw * r.ng) {
+                Plan pl = {r.tw, r.nw, 0, r.S, r.fused, 0, r.ng};
+                if (p.fused_reduce != 2) pl.fused = p.fused_reduce;
+                return pl;
+            }
         for (const TunedRow &r : kTuned)
             if (r.N == N && r.K == K && r.mt == mt && variant_exists(mt, r.tw, r.nw, r.depth, r.ks))
-                best = {r.tw, r.nw, r.depth, r.S, r.fused, r.ks};
+                best = {r.tw, r.nw, r.depth, r.S, r.fused, r.ks, 0};
     }
     if (p.k_sets > 0) {   // forced: the high-occupancy column-split variant
         const int tw = p.tiles_per_wave ? p.tiles_per_wave : 4, depth = p.prefetch_depth ? p.prefetch_depth : 2;
         int s = p.split_k > 0 ? p.split_k : 1;
         if (s > groups) s = groups;
-        if (variant_exists(mt, tw, 0, depth, p.k_sets)) best = {tw, 0, depth, s, 0, p.k_sets};
+        if (variant_exists(mt, tw, 0, depth, p.k_sets)) best = {tw, 0, depth, s, 0, p.k_sets, 0};
         return best;
     }
     if (best.tw == 0 && free_choice && mt > 1) {
@@ -827,7 +969,7 @@ static Plan choose_plan(int mt, int N, int K)
         int s = (256 + units / 2) / units;
         if (s > groups / 4) s = groups / 4;   // two groups per K set at least
         if (s < 1) s = 1;
-        if (variant_exists(mt, tw, 0, 1, 2)) best = {tw, 0, 1, s, 0, 2};
+        if (variant_exists(mt, tw, 0, 1, 2)) best = {tw, 0, 1, s, 0, 2, 0};
     }
     if (best.tw == 0) {
         const int forced_s = p.split_k > 0 ? (p.split_k < groups ? p.split_k : groups) : 0;
@@ -851,7 +993,7 @@ static Plan choose_plan(int mt, int N, int K)
                         cost += (mt > 1 && nw > 4) ? 0.3 : 0.0;                 // registers: big tiles want 4 wavefronts
                         cost += (mt == 1 && nw == 4 && units * s < 384) ? 0.3 : 0.0;
                         if (groups % (s * kways) != 0) cost += 0.2;            // uneven work per wavefront
-                        if (cost < best_cost) { best_cost = cost; best = {tw, nw, depth, s, mt == 1, 0}; }
+                        if (cost < best_cost) { best_cost = cost; best = {tw, nw, depth, s, mt == 1, 0, 0}; }
                     }
                 }
             }
@@ -884,9 +1026,9 @@ static int launch(const void *x, const void *packed, void *y, int M, int N, int 
     const int units = nblocks * kTiles / TW;
     uint32_t *tickets = reinterpret_cast<uint32_t *>(workspace);
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
-    hipLaunchKernelGGL((gemm_kernel<MT, TW, NW, DEPTH>), dim3((unsigned)(units * S)), dim3(NW * 64), lds_bytes,
+    hipLaunchKernelGGL((gemm_kernel<MT, TW, NW, DEPTH>), dim3((unsigned)S, (unsigned)units), dim3(NW * 64), lds_bytes,
                        stream, (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, tickets, M, N,
-                       K, groups, S, fused);
+                       K, groups, S, fused, groups / S, groups % S);
     if (S > 1 && !fused)
         hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
                            (const float *)partial, (_Float16 *)y, M, N, S);
@@ -907,8 +1049,9 @@ static int launch_ns(const void *x, const void *packed, void *y, int M, int N, i
     }
     const int groups = K / kGroup, units = pad_cols(N) / 16 / TW;
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
-    hipLaunchKernelGGL((gemm_ns_kernel<MT, TW, DEPTH>), dim3((unsigned)((units + 3) / 4 * S)), dim3(256), lds_bytes, stream,
-                       (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, M, N, K, groups, S);
+    hipLaunchKernelGGL((gemm_ns_kernel<MT, TW, DEPTH>), dim3((unsigned)S, (unsigned)((units + 3) / 4)), dim3(256), lds_bytes, stream,
+                       (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, M, N, K, groups, S, groups / S,
+                       groups % S);
     if (S > 1)
         hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
                            (const float *)partial, (_Float16 *)y, M, N, S);
@@ -930,11 +1073,39 @@ static int launch_cs(const void *x, const void *packed, void *y, int M, int N, i
     }
     const int groups = K / kGroup, units = pad_cols(N) / 16 / TW;
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
-    hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH>), dim3((unsigned)((units + 3) / 4 * S)), dim3(256 * KS),
+    hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH>), dim3((unsigned)S, (unsigned)((units + 3) / 4)), dim3(256 * KS),
                        lds_bytes, stream, (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, M, N, K,
-                       groups, S);
+                       groups, S, groups / S, groups % S);
     if (S > 1)
         hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
+                           (const float *)partial, (_Float16 *)y, M, N, S);
+    return launch_status();
+}
+
+template <int TW, int NW, int NG>
+static int launch_flat(const void *x, const void *packed, void *y, int M, int N, int K, int S, int fused,
+                       void *workspace, hipStream_t stream)
+{
+    static bool lds_ok = false;
+    const size_t x_bytes = (size_t)M * (NW * NG * 16 + 1) * 16, sum_bytes = (size_t)NW * 4 * TW * 64 * sizeof(float);
+    const size_t lds_bytes = x_bytes > sum_bytes ? x_bytes : sum_bytes;
+    const size_t lds_max = (size_t)kFlatMaxRows * (NW * NG * 16 + 1) * 16 > sum_bytes
+                               ? (size_t)kFlatMaxRows * (NW * NG * 16 + 1) * 16 : sum_bytes;
+    if (lds_max > 160 * 1024) return W4A16_EUNSUP;
+    if (!lds_ok && lds_max > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_flat_kernel<TW, NW, NG>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max) != hipSuccess)
+            return W4A16_EHIP;
+        lds_ok = true;
+    }
+    const int groups = K / kGroup, units = pad_cols(N) / 16 / TW;
+    uint32_t *tickets = reinterpret_cast<uint32_t *>(workspace);
+    float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
+    hipLaunchKernelGGL((gemm_flat_kernel<TW, NW, NG>), dim3((unsigned)S, (unsigned)units), dim3(NW * 64), lds_bytes,
+                       stream, (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, tickets, M, N,
+                       K, groups, S, fused);
+    if (S > 1 && !fused)
+        hipLaunchKernelGGL((splitk_reduce_kernel<1, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
                            (const float *)partial, (_Float16 *)y, M, N, S);
     return launch_status();
 }
@@ -942,6 +1113,14 @@ static int launch_cs(const void *x, const void *packed, void *y, int M, int N, i
 static int dispatch(int mt, const Plan &pl, const void *x, const void *packed, void *y, int M, int N, int K,
                     void *workspace, hipStream_t stream)
 {
+#define F(TW_, NW_, NG_)                                                           \
+    if (pl.tw == TW_ && pl.nw == NW_ && pl.ng == NG_)                              \
+        return launch_flat<TW_, NW_, NG_>(x, packed, y, M, N, K, pl.S, pl.fused, workspace, stream);
+    if (pl.ng > 0) {
+        W4_FLAT_VARIANTS(F)
+        return W4A16_EUNSUP;
+    }
+#undef F
 #define Z(MT_, TW_, KS_, D_)                                                       \
     if (mt == MT_ && pl.ks == KS_ && pl.tw == TW_ && pl.depth == D_)               \
         return launch_cs<MT_, TW_, KS_, D_>(x, packed, y, M, N, K, pl.S, workspace, stream);
@@ -974,9 +1153,9 @@ size_t w4a16_workspace_bytes(int M_max, int N, int K, int G)
     if (check_weight_shape(N, K, G) != W4A16_OK || M_max < 1 || M_max > W4A16_MAX_M) return 0;
     const int nblocks = pad_cols(N) / kBlockCols;
     size_t need = 0;
-    for (int mt = 1; mt <= (M_max + 15) / 16; ++mt) {
-        const Plan pl = choose_plan(mt, N, K);
-        size_t b = pl.tw ? partial_bytes(mt, nblocks, pl) : 0;
+    for (int m = 1; m <= M_max; ++m) {   // the plan depends on M only through a few thresholds: cheap enough
+        const Plan pl = choose_plan(m, N, K);
+        size_t b = pl.tw ? partial_bytes((m + 15) / 16, nblocks, pl) : 0;
         if (b > need) need = b;
     }
     return kTicketBytes + need;
@@ -993,7 +1172,7 @@ int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, 
     if (misaligned(x) || misaligned(packed) || misaligned(y) || misaligned(workspace)) return W4A16_EALIGN;
     const int nblocks = pad_cols(N) / kBlockCols;
     const int mt = (M + 15) / 16;
-    Plan pl = choose_plan(mt, N, K);
+    Plan pl = choose_plan(M, N, K);
     if (pl.tw == 0) return W4A16_EUNSUP;
     if (pl.S > 1 && nblocks * kTiles / pl.tw > kMaxTickets) pl.S = 1;
     if (pl.S > 1) {

@@ -125,6 +125,30 @@ __global__ void fill_zero_kernel(uint32_t *p, size_t words)
     if (i < words) p[i] = 0u;
 }
 
+// plain streaming read of `n16` 16-byte words: the bandwidth ceiling the GEMM is compared with.
+// Workgroup b reads the contiguous 32 KB chunk b with all of its loads in flight at once, the
+// fastest of the patterns tried on this GPU (strided grids and larger chunks were slower).
+typedef uint32_t probe_word __attribute__((ext_vector_type(4)));
+constexpr size_t kProbeChunk16 = 2048;   // 16-byte words per workgroup
+__global__ __launch_bounds__(256) void read_probe_kernel(const probe_word *__restrict__ p, size_t n16, uint32_t *sink)
+{
+    const size_t base = (size_t)blockIdx.x * kProbeChunk16 + threadIdx.x;
+    uint32_t acc = 0;
+    if (base - threadIdx.x + kProbeChunk16 <= n16) {
+        probe_word v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + base + u * 256);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    } else {
+        for (size_t i = base; i < n16; i += 256) {
+            const probe_word v = __builtin_nontemporal_load(p + i);
+            acc ^= v.x ^ v.y ^ v.z ^ v.w;
+        }
+    }
+    if (acc == 0x9E3779B9u) *sink = acc;   // keeps the loads alive; practically never taken
+}
+
 static Params g_params;
 Params &params() { return g_params; }
 
@@ -161,6 +185,7 @@ static int *param_slot(const char *name)
     if (!strcmp(name, "waves_per_wg")) return &p.waves_per_wg;
     if (!strcmp(name, "prefetch_depth")) return &p.prefetch_depth;
     if (!strcmp(name, "k_sets")) return &p.k_sets;
+    if (!strcmp(name, "flat_groups")) return &p.flat_groups;
     return nullptr;
 }
 
@@ -193,6 +218,18 @@ int w4a16_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
     size_t words = kTicketBytes / 4;
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
                        (hipStream_t)stream, (uint32_t *)workspace, words);
+    return launch_status();
+}
+
+int w4a16_read_probe(const void *buf, size_t bytes, void *sink, void *stream)
+{
+    if (!buf || !sink) return W4A16_ENULL;
+    if (misaligned(buf) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return W4A16_EALIGN;
+    if (bytes < 16) return W4A16_EINVAL;
+    const size_t n16 = bytes / 16, wgs = (n16 + kProbeChunk16 - 1) / kProbeChunk16;
+    if (wgs > 0x7fffffffu) return W4A16_EUNSUP;
+    hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)wgs), dim3(256), 0, (hipStream_t)stream,
+                       (const probe_word *)buf, n16, (uint32_t *)sink);
     return launch_status();
 }
 

@@ -24,7 +24,7 @@ def big_ws():
 @pytest.fixture(autouse=True)
 def _reset_knobs():
     yield
-    for k in ("split_k", "tiles_per_wave", "waves_per_wg", "prefetch_depth", "k_sets"):
+    for k in ("split_k", "tiles_per_wave", "waves_per_wg", "prefetch_depth", "k_sets", "flat_groups"):
         B.w4a16_set_param(k, 0)
     B.w4a16_set_param("fused_reduce", 2)
 
@@ -123,6 +123,38 @@ def test_parity_high_occupancy(M, K, N, big_ws):
         set_cs_variant(*variant)
         check_gemm(run_gemm(inp, packed, big_ws), y32, f"M={M} K={K} N={N} (tw, ks, depth, split)={variant}")
         assert np.array_equal(run_gemm(ex, ex_packed, big_ws).view(np.uint16), ex16.view(np.uint16)), variant
+
+
+# all-loads-up-front kernel, M <= 4 only: (tiles_per_wave, waves_per_wg, flat_groups, split_k, fused_reduce);
+# it needs K / 128 == split_k * waves_per_wg * flat_groups exactly
+VARIANTS_FLAT = [(2, 8, 8, 1, 1), (2, 16, 4, 1, 1), (2, 4, 7, 2, 1), (2, 8, 7, 2, 0), (4, 8, 4, 1, 1), (4, 4, 8, 3, 1),
+                 (4, 8, 7, 1, 1), (8, 4, 4, 2, 0), (8, 8, 4, 1, 1)]
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+@pytest.mark.parametrize("N", [136, 1000])
+def test_parity_flat(M, N, big_ws):
+    """every wavefront requests all of its weights before computing; x rows staged in LDS"""
+    print(f"gemm parity (flat) M={M} N={N}", flush=True)
+    for tw, nw, ng, split, fused in VARIANTS_FLAT:
+        K = split * nw * ng * 128
+        inp = I.make_linear(6100 + M + N + K, M, K, N)
+        packed = B.pack_from_numpy(inp)
+        y32, _, _ = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
+        ex = I.make_linear(6200 + M + K, M, K, N, x_kind="small_int", scale_kind="pow2")
+        ex_packed = B.pack_from_numpy(ex)
+        _, _, ex16 = R.w4a16_gemm(ex.x, ex.qweight, ex.scales, ex.qzeros, 128, want64=False)
+        set_variant(tw, nw, 0, split, fused)
+        B.w4a16_set_param("flat_groups", ng)
+        check_gemm(run_gemm(inp, packed, big_ws), y32, f"M={M} K={K} N={N} flat (tw, nw, ng, split, fused)={(tw, nw, ng, split, fused)}")
+        assert np.array_equal(run_gemm(ex, ex_packed, big_ws).view(np.uint16), ex16.view(np.uint16)), (tw, nw, ng, split, fused)
+    # a K that the forced variant cannot tile, or M > 4, is reported, not computed wrongly
+    B.w4a16_set_param("flat_groups", 8)
+    set_variant(2, 8, 0, 1, 1)
+    inp = I.make_linear(6300, 5, 8192, 128)
+    with pytest.raises(B.W4A16Error) as e:
+        run_gemm(inp, B.pack_from_numpy(inp), big_ws)
+    assert e.value.code == -4
 
 
 def test_uncompiled_variant_is_reported():
