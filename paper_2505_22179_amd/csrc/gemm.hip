@@ -142,6 +142,76 @@ __device__ __forceinline__ void dequant_tile(half8v (&b)[4], const u32x4 &w, con
     for (int j = 0; j < 4; ++j) b[j] = dequant8(w[j], zneg, zneg16, magic);
 }
 
+
+// ---- offset-code arithmetic for one row tile (M <= 16) ------------------------------------------
+// With few rows the vector ALU, not the matrix pipe, is the scarce unit, and two thirds of its work
+// per weight is turning the biased code into (q - z).  Here the second operand keeps the bias:
+// 0x6400 | q is 1024 + q in the low-nibble positions and 0x6400 | (q << 4) is 1024 + 16 q in the
+// high-nibble ones, where the x fragment carries x / 16 instead of x (exact in fp16 but for the
+// lowest subnormal bits).  Writing a' for that fragment, one group and one column give
+//     T = sum_k a'_k b_k = sum_k x_k q_k + 1024 sum_k a'_k,
+// so with C = 1024 sum_k a'_k and X = sum_k x_k (two more products of the same fragment with
+// constant operands, shared by all column tiles) the group's term is s (T - C - z X).  T - C is
+// formed inside the matrix pipe by starting the accumulation from -C.  All sums are fp32: inputs
+// whose products are exact stay exact; otherwise the cancellation of the 1024 bias costs about ten
+// bits of the fp32 significand in each group's term, which leaves it far more precise than the
+// fp16 result.
+constexpr bool kOffsetCodes = true;   // one-row-tile kernels use the arithmetic above
+
+__device__ __forceinline__ half8v offset8(uint32_t w, const DequantConsts &k)
+{
+    const uint32_t w2 = w >> 8;
+    const u32x4 v = {(w & k.mask_lo) | k.magic, (w & k.mask_hi) | k.magic, (w2 & k.mask_lo) | k.magic,
+                     (w2 & k.mask_hi) | k.magic};
+    return __builtin_bit_cast(half8v, v);
+}
+
+__device__ __forceinline__ void offset_tile(half8v (&b)[4], const u32x4 &w, const DequantConsts &magic)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) b[j] = offset8(w[j], magic);
+}
+
+// x fragment -> a': the four values that meet high-nibble codes (halves 2, 3, 6, 7) are divided by 16
+__device__ __forceinline__ void prescale_fragment(u32x4 &a)
+{
+    const half2v sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
+    a[1] = __builtin_bit_cast(uint32_t, as_h2(a[1]) * sixteenth);
+    a[3] = __builtin_bit_cast(uint32_t, as_h2(a[3]) * sixteenth);
+}
+
+// -C and X of one group for MT row tiles (every column of the result holds the same value)
+template <int MT>
+__device__ __forceinline__ void group_sums(const u32x4 (&a)[MT][4], float4v (&negc)[MT], float4v (&xs)[MT])
+{
+    const u32x4 bias = {0xE400E400u, 0xE400E400u, 0xE400E400u, 0xE400E400u};     // -1024 everywhere
+    const u32x4 ones = {0x3C003C00u, 0x4C004C00u, 0x3C003C00u, 0x4C004C00u};     // 1 or 16: undoes the / 16
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        negc[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
+        xs[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            negc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a[mt][j]),
+                                                               __builtin_bit_cast(half8v, bias), negc[mt], 0, 0, 0);
+            xs[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a[mt][j]),
+                                                             __builtin_bit_cast(half8v, ones), xs[mt], 0, 0, 0);
+        }
+    }
+}
+
+// acc += s (part - z X) for the rows that exist: register i of a lane is row 4 * (lane / 16) + i
+__device__ __forceinline__ void fold_offset(float4v &acc, const float4v &part, const float4v &xs, float s, float zf,
+                                            bool more_rows)
+{
+    acc[0] += s * (part[0] - zf * xs[0]);
+    if (more_rows) {   // uniform: M > 1
+        asm volatile("");   // keeps this a branch: if-converted, M = 1 would pay for all four rows
+#pragma unroll
+        for (int i = 1; i < 4; ++i) acc[i] += s * (part[i] - zf * xs[i]);
+    }
+}
+
 // One quantisation group for this wavefront's TW column tiles, software-pipelined over tiles:
 // while the matrix pipe works on tile t (its operand `bc` was expanded one stage earlier), the
 // vector ALU expands tile t+1 -- or tile 0 of the wavefront's next group at the last stage -- and
@@ -149,25 +219,39 @@ __device__ __forceinline__ void dequant_tile(half8v (&b)[4], const u32x4 &w, con
 // so the code stream never stalls on its own arithmetic.
 //   f, w      operands and codes of this group;  fn, wn  those of the next group (ring neighbour)
 //   bc        in: expanded tile 0 of this group; out: expanded tile 0 of the next group
-template <int MT, int TW, bool ALWAYS_REFILL>
-__device__ __forceinline__ void compute_group(const u32x4 (&a)[MT][4], const QuantWords &f, const QuantWords &fn,
+template <int MT, int TW, bool ALWAYS_REFILL, bool OFF = false>
+__device__ __forceinline__ void compute_group(u32x4 (&a)[MT][4], const QuantWords &f, const QuantWords &fn,
                                               u32x4 (&w)[TW], u32x4 (&wn)[TW], half8v (&bc)[4],
                                               float4v (&acc)[TW][MT], const uint8_t *refill_rec, bool refill,
-                                              bool next_group, int t0, int lane, const DequantConsts &magic)
+                                              bool next_group, int t0, int lane, const DequantConsts &magic,
+                                              bool more_rows = true)
 {
     const TileQuant<TW> q = tile_quant<TW>(f, t0);
     const TileQuant<TW> qn = tile_quant<TW>(fn, t0);
+    float4v negc[MT], xs[MT];
+    if constexpr (OFF) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) prescale_fragment(a[mt][j]);
+        group_sums<MT>(a, negc, xs);
+    }
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
         // tile t was expanded during the previous stage: its code registers are free again
         if (ALWAYS_REFILL || refill) w[t] = load_tile(refill_rec, t0 + t, lane);
         __builtin_amdgcn_sched_barrier(0);   // loads stay where they are written
         half8v bn[4];
-        if (t + 1 < TW) dequant_tile<TW>(bn, w[t + 1 < TW ? t + 1 : 0], q, t + 1, magic);
-        else if (ALWAYS_REFILL || next_group) dequant_tile<TW>(bn, wn[0], qn, 0, magic);
+        if constexpr (OFF) {
+            if (t + 1 < TW) offset_tile(bn, w[t + 1 < TW ? t + 1 : 0], magic);
+            else if (ALWAYS_REFILL || next_group) offset_tile(bn, wn[0], magic);
+        } else {
+            if (t + 1 < TW) dequant_tile<TW>(bn, w[t + 1 < TW ? t + 1 : 0], q, t + 1, magic);
+            else if (ALWAYS_REFILL || next_group) dequant_tile<TW>(bn, wn[0], qn, 0, magic);
+        }
         float4v part[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) part[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
+        for (int mt = 0; mt < MT; ++mt) part[mt] = OFF ? negc[mt] : (float4v){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -177,13 +261,19 @@ __device__ __forceinline__ void compute_group(const u32x4 (&a)[MT][4], const Qua
         uint32_t s2 = q.sw[t >> 1];
         _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (s2 >> 16) : (s2 & 0xFFFFu)));
         float s = (float)sh;
+        if constexpr (OFF) {
+            const float zf = (float)((q.zbits >> (4 * t)) & 0xFu);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[t][mt] += s * part[mt];
+            for (int mt = 0; mt < MT; ++mt) fold_offset(acc[t][mt], part[mt], xs[mt], s, zf, more_rows);
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[t][mt] += s * part[mt];
+        }
         // interleave: one matrix instruction, then a share of the next tile's expansion
 #pragma unroll
         for (int i = 0; i < 4 * MT; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, (40 + 4 * MT - 1) / (4 * MT), 0);   // VALU
+            __builtin_amdgcn_sched_group_barrier(0x002, ((OFF ? 24 : 40) + 4 * MT - 1) / (4 * MT), 0);   // VALU
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -338,6 +428,7 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
     extern __shared__ float4v lds4[];
     __shared__ uint32_t ticket_sh;
     constexpr int U = DEPTH > 2 ? DEPTH : 2;             // unroll: ring position and x-fragment buffer are static
+    constexpr bool kOff = kOffsetCodes && MT == 1;       // offset-code arithmetic for a single row tile
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps the group loop scalar
     const int r = lane >> 4, c = lane & 15;
@@ -379,7 +470,8 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
     half8v bc[4];
     if (n_w > 0) {
         load_operands<MT>(fa, recw, xp, g0, c);
-        dequant_tile<TW>(bc, w[0][0], tile_quant<TW>(fa.q, t0), 0, magic);
+        if constexpr (kOff) offset_tile(bc, w[0][0], magic);
+        else dequant_tile<TW>(bc, w[0][0], tile_quant<TW>(fa.q, t0), 0, magic);
     }
     int i = 0;
     // steady state: every group handled here has a successor DEPTH groups ahead, so all loads are
@@ -389,9 +481,9 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
         for (int u = 0; u < U; ++u) {
             const int gi = i + u;
             load_operands<MT>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
-            compute_group<MT, TW, true>(((u & 1) ? fb : fa).a, ((u & 1) ? fb : fa).q, ((u & 1) ? fa : fb).q, w[u % DEPTH],
-                                        w[(u + 1) % DEPTH], bc, acc,
-                                        recw + (size_t)(gi + DEPTH) * kStep, true, true, t0, lane, magic);
+            compute_group<MT, TW, true, kOff>(((u & 1) ? fb : fa).a, ((u & 1) ? fb : fa).q, ((u & 1) ? fa : fb).q,
+                                              w[u % DEPTH], w[(u + 1) % DEPTH], bc, acc,
+                                              recw + (size_t)(gi + DEPTH) * kStep, true, true, t0, lane, magic, M > 1);
         }
     }
     // drain: at most U + DEPTH - 1 groups left; ring position and fragment buffer stay static
@@ -401,10 +493,10 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
         if (gi < n_w) {   // uniform
             if (gi + 1 < n_w)
                 load_operands<MT>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
-            compute_group<MT, TW, false>(((u & 1) ? fb : fa).a, ((u & 1) ? fb : fa).q, ((u & 1) ? fa : fb).q, w[u % DEPTH],
-                                         w[(u + 1) % DEPTH], bc, acc,
-                                         recw + (size_t)(gi + DEPTH) * kStep, gi + DEPTH < n_w, gi + 1 < n_w, t0, lane,
-                                         magic);
+            compute_group<MT, TW, false, kOff>(((u & 1) ? fb : fa).a, ((u & 1) ? fb : fa).q, ((u & 1) ? fa : fb).q,
+                                               w[u % DEPTH], w[(u + 1) % DEPTH], bc, acc,
+                                               recw + (size_t)(gi + DEPTH) * kStep, gi + DEPTH < n_w, gi + 1 < n_w, t0,
+                                               lane, magic, M > 1);
         }
     }
 
@@ -460,7 +552,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat_kernel(
 #pragma unroll
     for (int l = 0; l < XL; ++l) {
         const int u = tid + kThreads * l, row = u / kRow16, col = u % kRow16;
-        if (row < M) xs[row * kRowStride16 + col] = xr[l];
+        if (row < M) {
+            if constexpr (kOffsetCodes) prescale_fragment(xr[l]);
+            xs[row * kRowStride16 + col] = xr[l];
+        }
     }
     __syncthreads();
 
@@ -475,17 +570,26 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) a[j] = xrow[(wave + NW * i) * 16 + j * 4];
         const TileQuant<TW> q = tile_quant<TW>(qw[i], t0);
+        float4v negc[1], xsum[1];
+        if constexpr (kOffsetCodes) {
+            const u32x4 (&a1)[1][4] = reinterpret_cast<const u32x4 (&)[1][4]>(a);
+            group_sums<1>(a1, negc, xsum);
+        }
 #pragma unroll
         for (int t = 0; t < TW; ++t) {
             half8v b[4];
-            dequant_tile<TW>(b, w[i][t], q, t, magic);
-            float4v part = (float4v){0.f, 0.f, 0.f, 0.f};
+            if constexpr (kOffsetCodes) offset_tile(b, w[i][t], magic);
+            else dequant_tile<TW>(b, w[i][t], q, t, magic);
+            float4v part = kOffsetCodes ? negc[0] : (float4v){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 part = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a[j]), b[j], part, 0, 0, 0);
             uint32_t s2 = q.sw[t >> 1];
             _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (s2 >> 16) : (s2 & 0xFFFFu)));
-            acc[t][0] += (float)sh * part;
+            if constexpr (kOffsetCodes)
+                fold_offset(acc[t][0], part, xsum[0], (float)sh, (float)((q.zbits >> (4 * t)) & 0xFu), M > 1);
+            else
+                acc[t][0] += (float)sh * part;
         }
     }
     __syncthreads();   // the x rows are dead: the epilogue reuses their LDS

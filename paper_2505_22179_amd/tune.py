@@ -8,7 +8,7 @@ library falls back to a generic rule for shapes that have no row.
 
     python -m paper_2505_22179_amd.tune --out gpurun_out/tuned_plans.inc [--shapes 70b,8b]
 
-Rebuild the library after copying the output over csrc/tuned_plans.inc.
+Rebuild the library after copying the outputs over csrc/tuned_plans.inc and csrc/tuned_flat.inc.
 """
 from __future__ import annotations
 
@@ -22,7 +22,8 @@ from . import binding as B
 from . import inputs as I
 
 G = 128
-KNOBS = ("tiles_per_wave", "waves_per_wg", "prefetch_depth", "split_k", "fused_reduce", "k_sets")
+KNOBS = ("tiles_per_wave", "waves_per_wg", "prefetch_depth", "split_k", "fused_reduce", "k_sets", "flat_groups")
+FLAT_MAX_M = 4   # the all-loads-up-front variant stages at most this many rows
 
 
 def weight_bytes(K: int, N: int) -> int:
@@ -86,7 +87,7 @@ def candidates(N: int, K: int, M: int):
                         wgs = ((N // 16) // tw + 3) // 4 * S
                         if wgs < 160 or wgs > 2048 or S * ks * 2 > K // G:
                             continue
-                        yield (tw, 0, depth, S, 0, ks)
+                        yield (tw, 0, depth, S, 0, ks, 0)
     for tw in (8, 4, 2):
         for nw in (1, 4, 8, 16):   # 1 = column-split workgroup sharing x through LDS
             for depth in (1, 2, 4):
@@ -95,7 +96,19 @@ def candidates(N: int, K: int, M: int):
                     waves = units * S * (nw if nw > 1 else 1)
                     if waves < 768 or waves > 16384 or S * max(nw, 2) > K // G or (nw == 1 and fused == 1 and S > 1):
                         continue
-                    yield (tw, nw, depth, S, fused, 0)
+                    yield (tw, nw, depth, S, fused, 0, 0)
+
+
+def flat_candidates(N: int, K: int):
+    """all-loads-up-front variant (M <= FLAT_MAX_M): K / G must equal S * nw * ng exactly"""
+    for tw in (2, 4, 8):
+        for nw in (4, 8, 16):
+            for ng in (4, 7, 8):
+                for S in (1, 2, 3, 4, 6, 8):
+                    if K // G != S * nw * ng:
+                        continue
+                    for fused in ((1,) if S == 1 else (1, 0)):
+                        yield (tw, nw, 0, S, fused, 0, ng)
 
 
 def tune_shape(name: str, K: int, N: int, Ms, ws, log):
@@ -103,6 +116,7 @@ def tune_shape(name: str, K: int, N: int, Ms, ws, log):
     copies = max(3, int(700e6 // wb) + 1)
     packs = make_packed(K, N, copies)
     per_bucket = collections.defaultdict(list)   # mt -> list of {plan: us}
+    flat_runs = []                               # M <= FLAT_MAX_M: ({flat plan: us}, best non-flat us)
     for M in Ms:
         x = torch.randn((M, K), device="cuda").to(torch.float16)
         y = torch.empty((M, N), dtype=torch.float16, device="cuda")
@@ -114,26 +128,48 @@ def tune_shape(name: str, K: int, N: int, Ms, ws, log):
             except B.W4A16Error:
                 continue   # variant not compiled for this M
         best = min(res.values())
+        if M <= FLAT_MAX_M:
+            fres = {}
+            for plan in flat_candidates(N, K):
+                set_knobs(plan)
+                try:
+                    fres[plan] = time_graph(lambda c: B.w4a16_gemm(x, packs[c], y, M, N, K, G, ws), copies)
+                except B.W4A16Error:
+                    continue
+            flat_runs.append((fres, best))
+            if fres:
+                fp, fus = min(fres.items(), key=lambda kv: kv[1])
+                log(f"{name} K={K} N={N} M={M}: best all-loads-up-front [tw{fp[0]} nw{fp[1]} ng{fp[6]} S{fp[3]}{'f' if fp[4] else 'k'} {fus:.1f}us] vs {best:.1f}us")
         top = sorted(res.items(), key=lambda kv: kv[1])[:4]
         log(f"{name} K={K} N={N} M={M}: ideal {wb / 8e6:.1f} us | " +
             " ".join(f"[tw{p[0]} {'ks%d' % p[5] if p[5] else 'nw%d' % p[1]} d{p[2]} S{p[3]}{'f' if p[4] else 'k'} {us:.1f}us]" for p, us in top))
         per_bucket[(M + 15) // 16].append({p: us / best for p, us in res.items()})
-    set_knobs((0, 0, 0, 0, 2, 0))
+    set_knobs((0, 0, 0, 0, 2, 0, 0))
     rows = []
     for mt, runs in sorted(per_bucket.items()):
         common = set(runs[0])
         for r in runs[1:]:
             common &= set(r)
         plan = min(common, key=lambda p: sum(r[p] for r in runs))
-        rows.append((N, K, mt) + plan)
+        rows.append((N, K, mt) + plan[:6])
+    flat_rows = []
+    if flat_runs and all(f for f, _ in flat_runs):
+        common = set(flat_runs[0][0])
+        for f, _ in flat_runs[1:]:
+            common &= set(f)
+        if common:
+            plan = min(common, key=lambda p: sum(f[p] / b for f, b in flat_runs))
+            if sum(f[plan] / b for f, b in flat_runs) < 0.98 * len(flat_runs):   # a clear win at every small M together
+                flat_rows.append((N, K, FLAT_MAX_M, plan[0], plan[1], plan[6], plan[3], plan[4]))
     del packs
     torch.cuda.empty_cache()
-    return rows
+    return rows, flat_rows
 
 
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", required=True)
+    ap.add_argument("--flat-out", default=None, help="rows for csrc/tuned_flat.inc (default: <out>.flat)")
     ap.add_argument("--shapes", default="70b,8b")
     ap.add_argument("--M", default="1,4,8,16,32,48,64")
     args = ap.parse_args()
@@ -143,16 +179,24 @@ def main() -> None:
     def log(s):
         print(s, file=sys.stderr, flush=True)
 
-    rows = []
+    rows, flat_rows = [], []
     for which in args.shapes.split(","):
         for name, K, N in (I.LLAMA3_70B if which == "70b" else I.LLAMA3_8B):
-            rows += tune_shape(f"{which}.{name}", K, N, Ms, ws, log)
+            r, f = tune_shape(f"{which}.{name}", K, N, Ms, ws, log)
+            rows += r
+            flat_rows += f
     with open(args.out, "w") as f:
         f.write("// Tuned launch shapes, written by `python -m paper_2505_22179_amd.tune` on an MI355X.\n")
         f.write("// {N, K, row tiles, tiles per wavefront, wavefronts per workgroup, prefetch depth, K splits, fused reduce, K sets}\n")
         for r in rows:
             f.write("{" + ", ".join(str(v) for v in r) + "},\n")
-    log(f"wrote {len(rows)} rows to {args.out}")
+    flat_out = args.flat_out or args.out + ".flat"
+    with open(flat_out, "w") as f:
+        f.write("// Tuned launch shapes of the all-loads-up-front variant, written by `python -m paper_2505_22179_amd.tune`.\n")
+        f.write("// {N, K, largest M, tiles per wavefront, wavefronts per workgroup, groups per wavefront, K splits, fused reduce}\n")
+        for r in flat_rows:
+            f.write("{" + ", ".join(str(v) for v in r) + "},\n")
+    log(f"wrote {len(rows)} rows to {args.out} and {len(flat_rows)} rows to {flat_out}")
 
 
 if __name__ == "__main__":
