@@ -27,6 +27,7 @@ sys.path.insert(0, ROOT)
 from paper_2505_22179_amd import binding as B  # noqa: E402
 from paper_2505_22179_amd import inputs as I  # noqa: E402
 
+MFMA_F16_PEAK_FLOPS = 2.5e15   # dense fp16 matrix peak of MI355X
 HBM_PEAK_GBPS = 8000.0
 G = 128
 
@@ -189,6 +190,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--quick", action="store_true", help="headline only (used under the profiler)")
+    ap.add_argument("--quick-m", type=int, default=1,
+                    help="with --quick: run at this M instead of 1 (profiler runs at other token counts; not the headline)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -202,16 +205,18 @@ def main():
     big = Layer(I.LLAMA3_70B, args.copies, seed=70)
     log("70B layer packed")
     sweep = {}
-    for M in ((1,) if args.quick else I.M_SWEEP_70B):
+    quick_ms = (args.quick_m,)
+    for M in (quick_ms if args.quick else I.M_SWEEP_70B):
         ms = time_steps(lambda c, M=M: big.step(M, c), args.steps, args.warmup, use_graph, args.copies)
         sweep[M] = ms
         log(f"70B M={M}: {ms * 1e3:.1f} us/layer  {big.bytes / ms / 1e6:.0f} GB/s")
-    ms1 = sweep[1]
+    hm = args.quick_m if args.quick else 1   # M of the headline (1 except under --quick --quick-m)
+    ms1 = sweep[hm]
     value = big.bytes / ms1 / 1e6   # GB/s
 
     # dominant kernel: the gate_up GEMM (55 % of the layer's bytes), timed alone, back to back
     per_gemm = {}
-    for M in ((1,) if args.quick else (1, 64)):
+    for M in (quick_ms if args.quick else (1, 64)):
         per_gemm[M] = {}
         for gi, (name, K, N) in enumerate(I.LLAMA3_70B):
             if args.quick and gi != 2:
@@ -220,10 +225,23 @@ def main():
             ms = time_steps(lambda c, M=M, gi=gi: big.step(M, c, only=gi), args.steps, args.warmup, use_graph, nc)
             per_gemm[M][name] = {"us": ms * 1e3, "GBps": weight_bytes(K, N) / ms / 1e6}
             log(f"70B {name} M={M}: {ms * 1e3:.2f} us  {weight_bytes(K, N) / ms / 1e6:.0f} GB/s")
-    gu = per_gemm[1]["gate_up"]
+    gu = per_gemm[hm]["gate_up"]
+    # the same buffers through the plain streaming-read probe: the bandwidth this GPU reaches at each size
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    plain = {}
+    for gi, (name, K, N) in enumerate(I.LLAMA3_70B):
+        if args.quick and gi != 2:
+            continue
+        nc = big.solo_copies(gi)
+        nbytes = big.packed[0][gi].numel()
+        ms = time_steps(lambda c, gi=gi, nbytes=nbytes: B.w4a16_read_probe(big.packed[c][gi], nbytes, sink),
+                        args.steps, args.warmup, use_graph, nc)
+        plain[name] = {"us": ms * 1e3, "GBps": nbytes / ms / 1e6}
+        log(f"70B {name} plain read of the packed buffer: {ms * 1e3:.2f} us  {nbytes / ms / 1e6:.0f} GB/s")
     roofline = {"bound": "hbm", "achieved": gu["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": gu["GBps"] / HBM_PEAK_GBPS, "traffic": None,
-                "kernel": "gemm_kernel<1> on 70B gate_up (K=8192, N=57344, M=1)",
+                "frac": gu["GBps"] / HBM_PEAK_GBPS, "traffic": measured_traffic(),
+                "plain_read_GBps": plain["gate_up"]["GBps"], "frac_of_plain_read": gu["GBps"] / plain["gate_up"]["GBps"],
+                "kernel": f"the GEMM kernel of 70B gate_up (K=8192, N=57344, M={hm})",
                 "algorithmic_bytes_per_launch": weight_bytes(8192, 57344), "us_per_launch": gu["us"]}
 
     extra = {}
@@ -261,18 +279,22 @@ def main():
                                              "frac_of_hbm_peak": bytes70 / ms / 1e6 / HBM_PEAK_GBPS,
                                              "ratio_vs_M1": ms / ms1} for M, ms in sweep.items()}
         extra["llama3_70b_per_gemm"] = {str(M): d for M, d in per_gemm.items()}
+        extra["llama3_70b_plain_read"] = dict(plain, layer_us=sum(d["us"] for d in plain.values()),
+                                              gemm_layer_over_plain_read=ms1 * 1e3 / sum(d["us"] for d in plain.values()))
+        flops64 = sum(2.0 * 64 * K * N for (_, K, N) in I.LLAMA3_70B)
+        extra["mfma_utilisation_M64"] = flops64 / (sweep[64] * 1e-3) / MFMA_F16_PEAK_FLOPS
         extra["latency_ratio_M64_over_M1"] = sweep[64] / ms1
         extra["paper_context"] = ("whole-model A100 figures, not comparable: verification/decoding time ratio 1.58 at "
                                   "n=48 (W4A16 70B), 1.80 at n=60 (W4A16 8B); end-to-end 2.78x over autoregressive, "
                                   "1.31x over EAGLE-2")
 
     result = {
-        "metric": "weight-HBM GB/s of the W4A16 GEMMs of one Llama-3-70B layer at M=1 (us/layer in ms_per_step)",
+        "metric": f"weight-HBM GB/s of the W4A16 GEMMs of one Llama-3-70B layer at M={hm} (us/layer in ms_per_step)",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": "Llama-3-70B decoder-layer linear set (qkv 8192->10240, o_proj 8192->8192, "
-                               "gate_up 8192->57344, down 28672->8192), W4A16 G=128, M=1; sweep M in {1,4,8,16,32,64}",
+                               "gate_up 8192->57344, down 28672->8192), W4A16 G=128, M=" + str(hm) + "; sweep M in {1,4,8,16,32,64}",
                    "weight_copies_rotated": args.copies, "hip_graph": use_graph, "device": dev},
         "frac_of_hbm_peak": value / HBM_PEAK_GBPS,
         "roofline": roofline,
