@@ -1,14 +1,12 @@
 // tree_verify_attn: attention of the tree-verification pass (paper section 2.1) on gfx950.
 //
-// One workgroup handles one query head and one contiguous range of keys; each of its four
-// wavefronts owns a 16-row tile of the (at most 64) draft-token query rows.  Scores are computed
-// transposed, S^T = K . Q^T, with 16x16x32 fp16 MFMA steps over the head dimension, so that a lane
-// ends up with eight scores of ONE query row (keys 4r..4r+3 of two 16-key tiles): exactly the
-// first-operand fragment the P.V product needs, with no shuffle in between.  The tree mask is
-// applied to the draft keys, softmax runs online in fp32 (base-2 exponentials), and V reaches the
-// second MFMA operand through a double-buffered LDS tile shared by the four wavefronts, because
-// the contraction there runs over keys while V is stored with the head dimension contiguous.  Key ranges are combined by a second small
-// kernel, in range order, so the result does not depend on scheduling.
+// Scores are computed transposed, S^T = K . Q^T, with 16x16x32 fp16 MFMA steps over the head
+// dimension, so that a lane ends up with eight scores of ONE query row: exactly the operand
+// fragment the P.V product needs, with no shuffle in between.  The tree mask is applied to the
+// draft keys only, softmax runs online in fp32 (base-2 exponentials), and V reaches its MFMA
+// operand through a transposed LDS tile, because the contraction there runs over keys while V is
+// stored with the head dimension contiguous.  Key ranges of different workgroups are combined by
+// a second small kernel, in range order, so the result does not depend on scheduling.
 #include "internal.h"
 
 namespace w4 {
@@ -20,10 +18,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kHeadDim = 128;
 constexpr int kKeyBlock = 32;
-constexpr int kVtStride = 36;    // halves per LDS row of the transposed V tile (72 B: 8-byte aligned, 16 rows -> 16 banks)
-constexpr int kOStride = 132;    // floats per LDS row of the output staging tile
 constexpr int kAttnThreads = 256;
 constexpr int kRowsPad = 64;
+constexpr int kAttnLdsBytes = 4 * 136 * 64 * 4;   // four exchange slots (they cover the four 8 KB V tiles)
 constexpr int kMaxSplits = 16;   // key ranges per head (the merge keeps one value per range in registers)
 
 __device__ __forceinline__ float xor_max(float v, int lane_mask)
@@ -31,16 +28,33 @@ __device__ __forceinline__ float xor_max(float v, int lane_mask)
     return fmaxf(v, __shfl_xor(v, lane_mask, 64));
 }
 
+constexpr float kLowest = -1.0e30f;   // "no key seen yet": finite, so differences of two of them are 0, not NaN
+
+// One workgroup = one query head x one contiguous range of 32-key steps.  The four wavefronts split
+// the KEYS, not the rows: wavefront w takes steps w, w + 4, ... of the range and carries, for all
+// (up to 64) query rows, its own online-softmax state -- running maximum, running sum and an
+// unnormalised output tile -- so K and V rows are fetched once per workgroup (no wavefront re-reads
+// another's keys), the main loop has no workgroup barrier, and the four states meet once, at the
+// end, through LDS.
+//
+// Per step a lane's registers hold, for row tile rt (rows 16 rt + c) and lane (r, c):
+//   S^T = K . Q^T     sa[rt][i], sb[rt][i]: keys 4r + i of the step's two 16-key tiles, row 16 rt + c
+//                     -- eight scores of ONE query row, which after exp2 and fp16 rounding are, as they
+//                     stand, the second operand P^T of the next product (contraction slot 8r + p:
+//                     p < 4 the first tile's key 4r + p, p >= 4 the second tile's key 4r + p - 4)
+//   O^T += V^T . P^T  o[dt][rt][i]: head-dim element 16 dt + 4r + i of row 16 rt + c: the row index
+//                     is the lane's c again, so the rescale factor of a row is lane-local
+// V^T (first operand: head-dim element 16 dt + c, the eight keys of contraction slots 8r ..) comes
+// from a per-wavefront LDS tile vt[d][32 keys in slot order], written as 8-byte units of four keys
+// and read as one 16-byte load per dt; 16-byte chunks are XOR-swizzled by bits of d against bank
+// conflicts.  The same wavefront writes and reads the tile: LDS keeps its program order.
 __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ k, const _Float16 *__restrict__ v,
     const uint8_t *__restrict__ mask, _Float16 *__restrict__ out, float *__restrict__ part_o,
     float *__restrict__ part_ml, int M, int P, int Hq, int Hkv,
     float scale_log2e, int nsplit, int bq, int brem)
 {
-    // V tile of the current and of the next key block, TRANSPOSED: vt[d][key ^ 4*((d>>4)&7)], so a
-    // lane's eight keys for one head-dim column are two 8-byte reads
-    __shared__ _Float16 vt[2][kHeadDim][kVtStride];
-    __shared__ float ot[4][16][kOStride];   // per-wavefront output tile for row-contiguous stores
+    extern __shared__ float4v smem4[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane >> 4, c = lane & 15;
@@ -52,190 +66,241 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     const int h = lid / nsplit, sp = lid % nsplit;
     const int kvh = h / (Hq / Hkv);
     const int T = P + M;
-    // key blocks of this split: bq = nblk / nsplit each, the first brem = nblk % nsplit one more (host-computed)
+    // key steps of this split: bq = nblk / nsplit each, the first brem = nblk % nsplit one more (host-computed)
     const int b0 = sp * bq + (sp < brem ? sp : brem), b1 = b0 + bq + (sp < brem ? 1 : 0);
-    const int row0 = wave * 16;
-    const int my_row = min(row0 + c, M - 1);   // rows >= M repeat row M-1 and are never stored
     const size_t kv_stride = (size_t)Hkv * kHeadDim;
-    const float NEG_INF = -__builtin_inff();
 
-    // Q^T fragment (second operand): lane (r, c) holds q[my_row, h, 32 j + 8 r .. +7]
-    half8v qf[4];
+    int row[4];   // rows >= M repeat row M-1 and are never stored
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        qf[j] = *reinterpret_cast<const half8v *>(q + ((size_t)my_row * Hq + h) * kHeadDim + 32 * j + 8 * r);
-
-    float4v o[8];
+    for (int rt = 0; rt < 4; ++rt) row[rt] = min(rt * 16 + c, M - 1);
+    // Tree mask as one 64-bit word per query row (bit j = draft key j visible), built once by the
+    // workgroups whose key range reaches the draft keys: a byte load per key inside the step loop
+    // would put some thirty dependent memory round trips on the critical path of the last steps.
+    __shared__ uint64_t row_bits[kRowsPad];
+    uint64_t mbits[4] = {0, 0, 0, 0};
+    const bool reaches_draft = b1 * kKeyBlock > P;   // uniform over the workgroup
+    uint8_t mask_byte[16];   // requested first, used after the Q, K and V requests: the oldest loads
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) o[dt] = (float4v){0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < 16; ++i) {
+        const int mrow = wave * 16 + i;
+        mask_byte[i] = (reaches_draft && mrow < M && lane < M) ? mask[(size_t)mrow * M + lane] : 0;
+    }
+    // Q^T fragments (second operand of S^T): lane (r, c) holds q[row, h, 32 j + 8 r .. +7]
+    half8v qf[4][4];
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            qf[rt][j] = *reinterpret_cast<const half8v *>(q + ((size_t)row[rt] * Hq + h) * kHeadDim + 32 * j + 8 * r);
 
-    // the workgroup stages each 32-key V block once (32 B per thread) and all four wavefronts read it
-    const int st_key = tid >> 3, st_chunk = (tid & 7) * 2;
-    const _Float16 *vbase = v + (size_t)kvh * kHeadDim + st_chunk * 8;
+    float4v o[8][4];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) o[dt][rt] = (float4v){0.f, 0.f, 0.f, 0.f};
+    float m_run[4], l_run[4];   // l_run: this lane's share (its keys 4r + i) of the row's sum
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) {
+        m_run[rt] = kLowest;
+        l_run[rt] = 0.f;
+    }
+
+    // this wavefront's transposed V tile: 128 rows (d) x 64 B (32 keys in contraction-slot order)
+    uint8_t *vt = reinterpret_cast<uint8_t *>(smem4) + wave * (kHeadDim * 64);
     const _Float16 *kbase = k + (size_t)kvh * kHeadDim + 8 * r;
-    auto load_v = [&](int blk, u32x4 (&reg)[2]) {
-        int src = blk * kKeyBlock + st_key;
-        if (blk * kKeyBlock + kKeyBlock > T) src = min(src, T - 1);   // uniform: only the last block is ragged
-        const _Float16 *p = vbase + (size_t)src * kv_stride;
-        reg[0] = *reinterpret_cast<const u32x4 *>(p);
-        reg[1] = *reinterpret_cast<const u32x4 *>(p + 8);
-    };
-    auto store_v = [&](int buf, const u32x4 (&reg)[2]) {
-        // this thread holds V[st_key][st_chunk*8 .. +15]: scatter it down 16 rows of the transposed tile
-        const int col = st_key ^ (4 * ((st_chunk >> 1) & 7));
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            uint32_t word = reg[i >> 3][(i >> 1) & 3];
-            uint16_t h16 = (i & 1) ? (uint16_t)(word >> 16) : (uint16_t)(word & 0xFFFFu);
-            vt[buf][st_chunk * 8 + i][col] = __builtin_bit_cast(_Float16, h16);
-        }
-    };
-    // K fragments (first operand of S^T): tile a = keys key0 + 0..15, tile b = key0 + 16..31
-    auto load_k = [&](int blk, half8v (&fa)[4], half8v (&fb)[4]) {
-        const int key0 = blk * kKeyBlock;
-        int ra = key0 + c, rb = key0 + 16 + c;
-        if (key0 + kKeyBlock > T) {   // uniform: only the last block is ragged
-            ra = min(ra, T - 1);
-            rb = min(rb, T - 1);
-        }
-        const _Float16 *ka = kbase + (size_t)ra * kv_stride;
-        const _Float16 *kb = kbase + (size_t)rb * kv_stride;
+    // V staging: lane (g, ch) = (lane % 8, lane / 8) fetches keys 4g .. 4g+3 of the step, head-dim
+    // chunks ch and ch + 8 (eight elements each); key group g sits in 8-byte unit 2 (g % 4) + g / 4
+    const int vg = lane & 7, vch = lane >> 3;
+    const _Float16 *vbase = v + (size_t)kvh * kHeadDim + vch * 8;
+    auto load_k = [&](int step, half8v (&fa)[4], half8v (&fb)[4]) {
+        const int key0 = step * kKeyBlock;
+        const int ra = key0 + c, rb = key0 + 16 + c;
+        const bool ragged = key0 + kKeyBlock > T;   // uniform: only the last step
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            fa[j] = *reinterpret_cast<const half8v *>(ka + 32 * j);
-            fb[j] = *reinterpret_cast<const half8v *>(kb + 32 * j);
+            fa[j] = *reinterpret_cast<const half8v *>(kbase + (size_t)(ragged ? min(ra, T - 1) : ra) * kv_stride + 32 * j);
+            fb[j] = *reinterpret_cast<const half8v *>(kbase + (size_t)(ragged ? min(rb, T - 1) : rb) * kv_stride + 32 * j);
         }
     };
-    // Two register sets for K fragments and for V rows give a prefetch distance of two key blocks:
-    // a set is refilled for block b+2 as soon as block b has consumed it.
-    u32x4 vreg0[2], vreg1[2];
-    half8v k0a[4], k0b[4], k1a[4], k1b[4];
-    float m_run = NEG_INF, l_run = 0.f;
-    int cur = 0;
-    auto block = [&](int blk, half8v (&kfa)[4], half8v (&kfb)[4], u32x4 (&v_store)[2], u32x4 (&v_load)[2]) {
-        const int key0 = blk * kKeyBlock;
-        const int ahead = blk + 2 < b1 ? blk + 2 : b1 - 1;   // clamped: loads stay unconditional
-        __syncthreads();   // tile `cur` is complete; nobody still reads the other tile
-        load_v(ahead, v_load);
-        __builtin_amdgcn_sched_barrier(0);
-        float4v sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+    auto load_v = [&](int step, u32x4 (&vr)[2][4]) {
+        const int key0 = step * kKeyBlock;
+        const int rv = key0 + 4 * vg;
+        const bool ragged = key0 + kKeyBlock > T;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfa[j], qf[j], sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfb[j], qf[j], sb, 0, 0, 0);
+        for (int it = 0; it < 2; ++it)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                vr[it][kk] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)(ragged ? min(rv + kk, T - 1) : rv + kk) * kv_stride + it * 64);
+    };
+    auto park_v = [&](const u32x4 (&vr)[2][4]) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+#pragma unroll
+            for (int dd = 0; dd < 8; ++dd) {
+                const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;   // the odd or the even halves of two words
+                u32x2 unit;
+                unit[0] = __builtin_amdgcn_perm(vr[it][1][dd >> 1], vr[it][0][dd >> 1], sel);
+                unit[1] = __builtin_amdgcn_perm(vr[it][3][dd >> 1], vr[it][2][dd >> 1], sel);
+                const int d = (vch + 8 * it) * 8 + dd;
+                const int chunk = (vg & 3) ^ ((d >> 1) & 3) ^ ((d >> 3) & 3);
+                *reinterpret_cast<u32x2 *>(vt + d * 64 + chunk * 16 + (vg >> 2) * 8) = unit;
+            }
+    };
+    // One 32-key step.  The K fragments and the V rows of the wavefront's next step are requested
+    // into the very registers this step has just emptied (V after its rows are parked in LDS, K after
+    // the score products), so one register set each gives a prefetch distance of most of a step.
+    auto step_fn = [&](int step, int next, half8v (&fa)[4], half8v (&fb)[4], u32x4 (&vr)[2][4]) {
+        const int key0 = step * kKeyBlock;
+        park_v(vr);
+        load_v(next, vr);
+        __builtin_amdgcn_sched_barrier(0);
+        float4v sa[4], sb[4];
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+            sa[rt] = (float4v){0.f, 0.f, 0.f, 0.f};
+            sb[rt] = (float4v){0.f, 0.f, 0.f, 0.f};
         }
-        load_k(ahead, kfa, kfb);   // the fragments just consumed make room for block blk + 2
-        __builtin_amdgcn_sched_barrier(0);
-        // lane (r, c): sa[i] = score of key key0 + 4r + i, sb[i] = key0 + 16 + 4r + i, query row my_row
-        float s[8];
-        if (key0 + kKeyBlock <= P) {   // uniform: a block of committed prefix keys, all visible
 #pragma unroll
-            for (int i = 0; i < 8; ++i) s[i] = ((i < 4) ? sa[i & 3] : sb[i & 3]) * scale_log2e;
-        } else {
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) {
+                sa[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[j], qf[rt][j], sa[rt], 0, 0, 0);
+                sb[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[j], qf[rt][j], sb[rt], 0, 0, 0);
+            }
+        load_k(next, fa, fb);
+        __builtin_amdgcn_sched_barrier(0);
+        half8v pb[4];
+        const bool prefix_only = key0 + kKeyBlock <= P;   // uniform: committed keys, all visible
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+            float s[8];
+            if (prefix_only) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) s[i] = ((i < 4) ? sa[rt][i & 3] : sb[rt][i & 3]) * scale_log2e;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int key = key0 + 4 * r + (i & 3) + (i >> 2) * 16;
+                    const int j = key - P;   // draft key index; bits at and beyond M are clear
+                    const bool vis = j < 0 || (j < 64 && ((mbits[rt] >> j) & 1));
+                    const float raw = (i < 4) ? sa[rt][i & 3] : sb[rt][i & 3];
+                    s[i] = vis ? raw * scale_log2e : -__builtin_inff();
+                }
+            }
+            float m_blk = s[0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) m_blk = fmaxf(m_blk, s[i]);
+            m_blk = xor_max(m_blk, 16);
+            m_blk = xor_max(m_blk, 32);
+            const float m_new = fmaxf(m_run[rt], m_blk);
+            const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+            float psum = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                int key = key0 + 4 * r + (i & 3) + (i >> 2) * 16;
-                bool vis = key < P;
-                if (!vis && key < T) vis = mask[(size_t)my_row * M + (key - P)] != 0;
-                float raw = (i < 4) ? sa[i & 3] : sb[i & 3];
-                s[i] = vis ? raw * scale_log2e : NEG_INF;
+                const float pv = __builtin_amdgcn_exp2f(s[i] - m_new);
+                psum += pv;
+                pb[rt][i] = (_Float16)pv;
             }
-        }
-        float m_blk = s[0];
+            l_run[rt] = l_run[rt] * alpha + psum;
+            m_run[rt] = m_new;
+            if (__any(alpha != 1.0f)) {   // after the first steps a row's maximum rarely moves
 #pragma unroll
-        for (int i = 1; i < 8; ++i) m_blk = fmaxf(m_blk, s[i]);
-        m_blk = xor_max(m_blk, 16);
-        m_blk = xor_max(m_blk, 32);
-        float m_new = fmaxf(m_run, m_blk);
-        float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
-        float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // 0 when nothing was seen before
-        float psum = 0.f;
-        half8v pa;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            float p = __builtin_amdgcn_exp2f(s[i] - m_safe);
-            psum += p;
-            pa[i] = (_Float16)p;
-        }
-        psum += __shfl_xor(psum, 16, 64);
-        psum += __shfl_xor(psum, 32, 64);
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-        // accumulator rows are 4r + i: when some row's running maximum moved, fetch the rescale factors
-        // from the lanes that own those rows (after the first few blocks this is rare)
-        if (__any(alpha != 1.0f)) {
-            float a_row[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a_row[i] = __shfl(alpha, 4 * r + i, 64);
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) o[dt][i] *= a_row[i];
+                for (int dt = 0; dt < 8; ++dt) o[dt][rt] *= alpha;
+            }
         }
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-            // second operand: V[key slot][dt*16 + c], slots = keys 4r+p (tile a) and 16+4r+p (tile b)
-            const _Float16 *rowp = &vt[cur][dt * 16 + c][0];
-            u32x2 lo = *reinterpret_cast<const u32x2 *>(rowp + 4 * (r ^ dt));
-            u32x2 hi = *reinterpret_cast<const u32x2 *>(rowp + 4 * ((4 + r) ^ dt));
-            u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
-            o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa, __builtin_bit_cast(half8v, both), o[dt], 0, 0, 0);
+            const int d = dt * 16 + c;
+            const int chunk = r ^ ((d >> 1) & 3) ^ ((d >> 3) & 3);
+            const half8v va = *reinterpret_cast<const half8v *>(vt + d * 64 + chunk * 16);
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) o[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], o[dt][rt], 0, 0, 0);
         }
-        store_v(cur ^ 1, v_store);   // V rows of block blk + 1, requested two blocks ago
-        cur ^= 1;
     };
-    if (b0 < b1) {
-        load_v(b0, vreg0);
-        load_k(b0, k0a, k0b);
-        load_v(b0 + 1 < b1 ? b0 + 1 : b0, vreg1);
-        load_k(b0 + 1 < b1 ? b0 + 1 : b0, k1a, k1b);
-        store_v(0, vreg0);
-    }
-    for (int blk = b0; blk < b1; blk += 2) {
-        block(blk, k0a, k0b, vreg1, vreg0);
-        if (blk + 1 < b1) block(blk + 1, k1a, k1b, vreg0, vreg1);
-    }
 
-    // o[dt][i] belongs to query row row0 + 4r + i, column dt*16 + c
-    float l_row[4], m_row[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        l_row[i] = __shfl(l_run, 4 * r + i, 64);
-        m_row[i] = __shfl(m_run, 4 * r + i, 64);
+    half8v ka[4], kb[4];
+    u32x4 vr[2][4];
+    const int first = b0 + wave;
+    if (first < b1) {
+        load_k(first, ka, kb);
+        load_v(first, vr);
     }
-    // turn the fragment-ordered tile into rows: lane (r, c) owns rows 4r+i, columns dt*16+c
+    if (reaches_draft) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint64_t bits = __ballot(mask_byte[i] != 0);
+            if (lane == 0) row_bits[wave * 16 + i] = bits;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) mbits[rt] = row_bits[row[rt]];
+    }
+    for (int step = first; step < b1; step += 4)
+        step_fn(step, step + 4 < b1 ? step + 4 : step, ka, kb, vr);   // past the end: the same rows again, unused
+
+    // a row's sum over this wavefront's keys: add the four lanes (r = 0..3) that share the row
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) {
+        l_run[rt] += __shfl_xor(l_run[rt], 16, 64);
+        l_run[rt] += __shfl_xor(l_run[rt], 32, 64);
+    }
+    // The four wavefronts' states meet in LDS: each parks its whole state (32 accumulator quads and
+    // 8 state values per lane, lane-contiguous), and after one barrier wavefront w combines, in
+    // wavefront order, the head-dim tiles 2w and 2w + 1 of all four and stores them.
+    float4v *xq = smem4;                                                             // [4 slots][32 quads][64 lanes]
+    float *xs = reinterpret_cast<float *>(smem4 + 4 * 32 * 64);                      // [4 slots][8 values][64 lanes]
+    __syncthreads();   // every wavefront has left its V tile: the exchange reuses that LDS
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) xq[(wave * 32 + dt * 4 + rt) * 64 + lane] = o[dt][rt];
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) {
+        xs[(wave * 8 + rt) * 64 + lane] = m_run[rt];
+        xs[(wave * 8 + 4 + rt) * 64 + lane] = l_run[rt];
+    }
+    __syncthreads();
     const bool last = nsplit == 1;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float inv = last ? 1.f / l_row[i] : 1.f;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) ot[wave][4 * r + i][dt * 16 + c] = o[dt][i] * inv;
-    }
-    // (same wavefront writes and reads its own tile: LDS keeps program order, no barrier needed)
     float *po = part_o + (size_t)lid * kRowsPad * kHeadDim;
+    float *pml = part_ml + (size_t)lid * kRowsPad * 2;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const int idx = u * 64 + lane, trow = idx >> 5, d4 = idx & 31;
-        const int row = row0 + trow;
-        if (row < M) {
-            const float4v val = *reinterpret_cast<const float4v *>(&ot[wave][trow][d4 * 4]);
-            if (last) {
-                typedef _Float16 half4v __attribute__((ext_vector_type(4)));
-                half4v hv = {(_Float16)val[0], (_Float16)val[1], (_Float16)val[2], (_Float16)val[3]};
-                *reinterpret_cast<half4v *>(out + ((size_t)row * Hq + h) * kHeadDim + d4 * 4) = hv;
-            } else {
-                *reinterpret_cast<float4v *>(po + row * kHeadDim + d4 * 4) = val;
+    for (int rt = 0; rt < 4; ++rt) {
+        float ms[4], wgt[4], m_all = kLowest, l_all = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+            ms[w2] = xs[(w2 * 8 + rt) * 64 + lane];
+            m_all = fmaxf(m_all, ms[w2]);
+        }
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+            wgt[w2] = __builtin_amdgcn_exp2f(ms[w2] - m_all);
+            l_all += wgt[w2] * xs[(w2 * 8 + 4 + rt) * 64 + lane];
+        }
+        const int orow = rt * 16 + c;
+        const float inv = last ? 1.f / l_all : 1.f;
+#pragma unroll
+        for (int dd = 0; dd < 2; ++dd) {
+            const int dt = 2 * wave + dd;
+            float4v val = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) val += wgt[w2] * xq[(w2 * 32 + dt * 4 + rt) * 64 + lane];
+            val *= inv;
+            // row 16 rt + c, head-dim elements 16 dt + 4r .. + 3: four consecutive outputs
+            if (orow < M) {
+                if (last) {
+                    typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+                    half4v hv = {(_Float16)val[0], (_Float16)val[1], (_Float16)val[2], (_Float16)val[3]};
+                    *reinterpret_cast<half4v *>(out + ((size_t)orow * Hq + h) * kHeadDim + dt * 16 + 4 * r) = hv;
+                } else {
+                    *reinterpret_cast<float4v *>(po + orow * kHeadDim + dt * 16 + 4 * r) = val;
+                }
             }
         }
-    }
-    if (!last && c == 0) {
-        // partial state of this key range: a second kernel merges the ranges (the kernel boundary
-        // makes them visible, at no fence cost)
-        float *pml = part_ml + (size_t)lid * kRowsPad * 2;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            pml[(row0 + 4 * r + i) * 2] = m_row[i];
-            pml[(row0 + 4 * r + i) * 2 + 1] = l_row[i];
+        if (!last && wave == 0 && r == 0 && orow < M) {
+            // partial state of this key range: a second kernel merges the ranges (the kernel boundary
+            // makes them visible, at no fence cost)
+            pml[orow * 2] = m_all;
+            pml[orow * 2 + 1] = l_all;
         }
     }
 }
@@ -271,7 +336,7 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const float *__res
     float4v num = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < kMaxSplits; ++s) {
-        float wgt = (ms[s] == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms[s] - m_all);
+        float wgt = (ms[s] == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms[s] - m_all);   // ranges without a visible key: l = 0
         den += wgt * ls[s];
         num += wgt * os[s];
     }
@@ -327,7 +392,14 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
     float *part_ml = part_o + (size_t)Hq * ns * kRowsPad * kHeadDim;
     const float scale_log2e = scale * 1.4426950408889634f;
     const int nblk = (P + M + kKeyBlock - 1) / kKeyBlock;
-    hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)(Hq * ns)), dim3(kAttnThreads), 0, (hipStream_t)stream,
+    static bool lds_ok = false;   // LDS above 64 KB needs an opt-in, once
+    if (!lds_ok) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes) != hipSuccess)
+            return W4A16_EHIP;
+        lds_ok = true;
+    }
+    hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)(Hq * ns)), dim3(kAttnThreads), kAttnLdsBytes, (hipStream_t)stream,
                        (const _Float16 *)q, (const _Float16 *)k, (const _Float16 *)v, mask, (_Float16 *)out,
                        part_o, part_ml, M, P, Hq, Hkv, scale_log2e, ns, nblk / ns, nblk % ns);
     if (ns > 1) {
