@@ -305,7 +305,9 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     }
 }
 
-// merge of the key ranges: one thread per four consecutive output elements, ranges in order
+// merge of the key ranges: one thread per four consecutive output elements, ranges in order;
+// NS = compiled upper bound of the number of ranges (all loads of a thread are issued at once)
+template <int NS>
 __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const float *__restrict__ part_o,
                                                               const float *__restrict__ part_ml,
                                                               _Float16 *__restrict__ out, int M, int Hq, int nsplit)
@@ -316,10 +318,10 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const float *__res
     const float NEG_INF = -__builtin_inff();
     const float *hml = part_ml + (size_t)h * nsplit * kRowsPad * 2;
     const float4v *ho = reinterpret_cast<const float4v *>(part_o + (size_t)h * nsplit * kRowsPad * kHeadDim);
-    float ms[kMaxSplits], ls[kMaxSplits];
-    float4v os[kMaxSplits];
+    float ms[NS], ls[NS];
+    float4v os[NS];
 #pragma unroll
-    for (int s = 0; s < kMaxSplits; ++s) {
+    for (int s = 0; s < NS; ++s) {
         ms[s] = NEG_INF;
         ls[s] = 0.f;
         os[s] = (float4v){0.f, 0.f, 0.f, 0.f};
@@ -331,11 +333,11 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const float *__res
     }
     float m_all = NEG_INF;
 #pragma unroll
-    for (int s = 0; s < kMaxSplits; ++s) m_all = fmaxf(m_all, ms[s]);
+    for (int s = 0; s < NS; ++s) m_all = fmaxf(m_all, ms[s]);
     float den = 0.f;
     float4v num = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int s = 0; s < kMaxSplits; ++s) {
+    for (int s = 0; s < NS; ++s) {
         float wgt = (ms[s] == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms[s] - m_all);   // ranges without a visible key: l = 0
         den += wgt * ls[s];
         num += wgt * os[s];
@@ -404,8 +406,16 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
                        part_o, part_ml, M, P, Hq, Hkv, scale_log2e, ns, nblk / ns, nblk % ns);
     if (ns > 1) {
         const int quads = M * Hq * (kHeadDim / 4);
-        hipLaunchKernelGGL(tree_attn_merge_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0,
-                           (hipStream_t)stream, (const float *)part_o, (const float *)part_ml, (_Float16 *)out, M, Hq, ns);
+        const dim3 grid((unsigned)((quads + 255) / 256));
+        if (ns <= 4)
+            hipLaunchKernelGGL(tree_attn_merge_kernel<4>, grid, dim3(256), 0, (hipStream_t)stream, (const float *)part_o,
+                               (const float *)part_ml, (_Float16 *)out, M, Hq, ns);
+        else if (ns <= 8)
+            hipLaunchKernelGGL(tree_attn_merge_kernel<8>, grid, dim3(256), 0, (hipStream_t)stream, (const float *)part_o,
+                               (const float *)part_ml, (_Float16 *)out, M, Hq, ns);
+        else
+            hipLaunchKernelGGL(tree_attn_merge_kernel<kMaxSplits>, grid, dim3(256), 0, (hipStream_t)stream,
+                               (const float *)part_o, (const float *)part_ml, (_Float16 *)out, M, Hq, ns);
     }
     return launch_status();
 }
