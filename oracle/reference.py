@@ -9,7 +9,11 @@ Tree-verify attention (paper section 2.1: the target model scores all n draft-tr
 forward pass; a draft token may attend to the committed prefix, to itself and to its ancestors in
 the tree): plain numpy in fp64, written below.
 
-Pin status.  The paper prints no worked numerical example for either operation, so beyond the
+Greedy tree acceptance and K/V compaction (the integer step right after verification): plain
+Python below; pinned in tests/test_oracle_accept.py by brute force over all root paths, chain
+closed forms, planted paths and library gathers.
+
+Pin status.  The paper prints no worked numerical example for any of these operations, so beyond the
 pins in tests/test_oracle_*.py (nibble-order fixtures, round trips, closed forms, exact rational
 brute force, numpy/torch library cross-checks, structural invariants) the numerics are unpinned
 by the paper and this oracle is the definition.
@@ -157,3 +161,48 @@ def tree_verify_attn(q, k, v, mask, scale: float | None = None):
             p /= p.sum()
             out[i, h, :] = p @ v64[visible, kh, :]
     return out, out.astype(np.float16)
+
+
+# ---------------------------------------------------------------------------------------------
+# greedy acceptance of a verified draft tree and compaction of the accepted K/V rows
+
+
+def tree_accept(parent, token, target):
+    """Greedy draft-then-verify acceptance on a tree draft (paper section 2.1: the target model
+    verifies the n draft-tree tokens in one pass and accepts some of them; section 4: verifying a
+    tree turns it into a sequence).  Node 0 is the root, i.e. the last committed token; parent[i] < i.
+    token[i] is the draft token at node i, target[i] the target model's greedy next token after
+    the sequence ending in node i.  The walk starts at the root; at node cur, a child is accepted
+    iff its draft token equals target[cur]; among several such children the lowest index is taken;
+    the walk stops at the first node without an accepted child.
+    Returns (path, next_token): the accepted node indices, root first, and target[path[-1]], the
+    token the target model itself contributes after the last accepted node.  Pure integer work."""
+    parent = [int(p) for p in parent]
+    token = [int(t) for t in token]
+    target = [int(t) for t in target]
+    n = len(parent)
+    assert n >= 1 and parent[0] < 0 and all(0 <= parent[i] < i for i in range(1, n))
+    path = [0]
+    cur = 0
+    while True:
+        nxt = -1
+        for i in range(cur + 1, n):
+            if parent[i] == cur and token[i] == target[cur]:
+                nxt = i
+                break
+        if nxt < 0:
+            break
+        path.append(nxt)
+        cur = nxt
+    return path, target[cur]
+
+
+def kv_compact(k, v, path, P: int):
+    """After acceptance the cache keeps the accepted nodes only, in order: cache row P + j receives
+    the K and V rows of node path[j] (stored at row P + path[j]) for every j < len(path).  Rows
+    below P and rows from P + len(path) on are left as they are.  Returns new arrays."""
+    k2, v2 = np.array(k, copy=True), np.array(v, copy=True)
+    for j, node in enumerate(path):
+        k2[P + j] = k[P + node]
+        v2[P + j] = v[P + node]
+    return k2, v2

@@ -174,3 +174,35 @@ def make_attn(seed: int, M: int = 60, P: int = 2048, Hq: int = 64, Hkv: int = 8,
     else:
         raise ValueError(tree)
     return AttnInputs(M, P, Hq, Hkv, D, q, k, v, mask, parent, 1.0 / float(np.sqrt(D)))
+
+
+def make_verify(seed: int, parent: np.ndarray, vocab: int = 128256, p_accept: float = 0.7):
+    """Draft tokens and target-model greedy tokens for a draft tree (stand-ins for a draft model's
+    beam-search tokens and the target model's argmax, which need trained weights).  Siblings carry
+    distinct tokens, as the children of a beam-search node do.  For every node the target token
+    equals the token of one of its children (picked uniformly) with probability p_accept, and is
+    otherwise a token none of its children carries.  Returns (token int32 [n], target int32 [n])."""
+    rng = np.random.default_rng(seed)
+    n = len(parent)
+    children = [[] for _ in range(n)]
+    for i in range(1, n):
+        children[int(parent[i])].append(i)
+    token = np.zeros(n, dtype=np.int32)
+    token[0] = int(rng.integers(0, vocab))
+    for p in range(n):
+        if children[p]:
+            draws = rng.choice(vocab, size=len(children[p]), replace=False)
+            for ch, t in zip(children[p], draws):
+                token[ch] = int(t)
+    target = np.zeros(n, dtype=np.int32)
+    for p in range(n):
+        kids = children[p]
+        if kids and rng.random() < p_accept:
+            target[p] = token[kids[int(rng.integers(0, len(kids)))]]
+        else:
+            taken = {int(token[ch]) for ch in kids}
+            t = int(rng.integers(0, vocab))
+            while t in taken:
+                t = int(rng.integers(0, vocab))
+            target[p] = t
+    return token, target
