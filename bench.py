@@ -268,7 +268,17 @@ def main():
 
         ms_attn = time_steps(attn, args.steps, args.warmup, use_graph, kv_copies)
         ms_tree = time_steps(tree_step, args.steps, args.warmup, use_graph, args.copies)
-        extra["tree_verify_step_M60"] = {"attn_us": ms_attn * 1e3, "step_us": ms_tree * 1e3}
+        # greedy acceptance of the verified tree + compaction of the accepted K/V rows (integer step after verify)
+        tok, tgt = I.make_verify(I.seed_for(5, 1), a.parent, p_accept=0.8)
+        d_parent = torch.from_numpy(a.parent.astype("int32")).cuda()
+        d_tok, d_tgt = torch.from_numpy(tok).cuda(), torch.from_numpy(tgt).cuda()
+        d_path = torch.empty(a.M, dtype=torch.int32, device="cuda")
+        d_res = torch.empty(2, dtype=torch.int32, device="cuda")
+        ms_acc = time_steps(lambda c: B.tree_accept(d_parent, d_tok, d_tgt, a.M, d_path, d_res, ks[c % kv_copies],
+                                                    vs[c % kv_copies], a.P, a.Hkv, a.D),
+                            args.steps, args.warmup, use_graph, kv_copies)
+        extra["tree_verify_step_M60"] = {"attn_us": ms_attn * 1e3, "step_us": ms_tree * 1e3,
+                                         "accept_and_compact_us": ms_acc * 1e3, "accepted_nodes": int(d_res[0].item())}
         log(f"tree-verify: attn {ms_attn * 1e3:.1f} us, step {ms_tree * 1e3:.1f} us")
         del big, ks, vs
         torch.cuda.empty_cache()

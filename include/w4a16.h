@@ -129,6 +129,25 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
                      int M, int P, int Hq, int Hkv, int D, float scale,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/* Greedy acceptance of a verified draft tree and compaction of the accepted K/V rows -- the integer
+ * step that follows tree_verify_attn and the target model's remaining layers (paper section 2.1:
+ * draft-then-verify, the target accepts some of the n draft-tree tokens; section 4: verifying a tree
+ * turns it into a sequence).  Node 0 is the root (the last committed token); parent[i] < i for i > 0
+ * and parent[0] < 0.  token[i] is the draft token at node i, target[i] the target model's greedy next
+ * token after the sequence that ends in node i.  Starting at the root, a child of the current node is
+ * accepted iff its draft token equals the current node's target token (the lowest index among several);
+ * the walk stops at the first node without an accepted child.
+ *   path   int32 [M], out: accepted node indices, root first; unused entries are -1
+ *   result int32 [2], out: [0] = number of accepted nodes (root included), [1] = target[last accepted
+ *          node], the token the target model itself contributes
+ *   k, v   fp16 [P+M, Hkv, D], both given or both NULL: when given, cache row P + j receives row
+ *          P + path[j] for every accepted position j, in place; all other rows are left untouched
+ * parent, token, target, path, result: device pointers, 4-byte aligned; k, v: 16-byte aligned,
+ * Hkv * D * 2 a multiple of 16.  1 <= M <= 64.  The kernel stays in bounds and terminates for any
+ * content of parent (an entry that breaks parent[i] < i merely makes node i unreachable). */
+int tree_accept(const int32_t *parent, const int32_t *token, const int32_t *target, int M, int32_t *path,
+                int32_t *result, void *k, void *v, int P, int Hkv, int D, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("W4A16_LIB") or os.path.join(_HERE, "lib", "libw4a16.s
 EXPORTS = (
     "w4a16_version", "w4a16_strerror", "w4a16_set_param", "w4a16_get_param", "w4a16_packed_bytes",
     "w4a16_workspace_bytes", "w4a16_workspace_init", "w4a16_pack", "w4a16_unpack", "w4a16_dequant",
-    "w4a16_gemm", "w4a16_read_probe", "tree_verify_attn_workspace_bytes", "tree_verify_attn",
+    "w4a16_gemm", "w4a16_read_probe", "tree_verify_attn_workspace_bytes", "tree_verify_attn", "tree_accept",
 )
 
 _lib = None
@@ -53,6 +53,7 @@ def load() -> ctypes.CDLL:
     L.tree_verify_attn_workspace_bytes.restype = sz
     L.tree_verify_attn_workspace_bytes.argtypes = [i, i, i, i, i]
     L.tree_verify_attn.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, ctypes.c_float, vp, sz, vp]
+    L.tree_accept.argtypes = [vp, vp, vp, i, vp, vp, vp, vp, i, i, i, vp]
     _lib = L
     return L
 
@@ -135,6 +136,11 @@ def tree_verify_attn(q, k, v, mask, out, M: int, P: int, Hq: int, Hkv: int, D: i
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().tree_verify_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(mask), _ptr(out), M, P, Hq, Hkv, D,
                                    float(scale), _ptr(workspace), nbytes, _stream()), "tree_verify_attn")
+
+
+def tree_accept(parent, token, target, M: int, path, result, k=None, v=None, P: int = 0, Hkv: int = 0, D: int = 0) -> None:
+    _check(load().tree_accept(_ptr(parent), _ptr(token), _ptr(target), M, _ptr(path), _ptr(result), _ptr(k), _ptr(v),
+                              P, Hkv, D, _stream()), "tree_accept")
 
 
 # ---- conveniences for tests and the benchmark (still marshalling only) ----

@@ -348,6 +348,59 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const float *__res
     *reinterpret_cast<half4v *>(out + ((size_t)row * Hq + h) * kHeadDim + d4 * 4) = hv;
 }
 
+// Greedy acceptance of a verified draft tree, then compaction of the accepted K/V rows.
+// Wavefront 0 walks the tree with lane i = node i: at node cur it broadcasts target[cur], every lane
+// tests "my parent is cur and my token is that", and the lowest set bit of the ballot is the next
+// node.  cur grows strictly, so the walk ends after at most M rounds whatever the input holds.
+// Then all 256 threads move the accepted rows: thread t owns 16-byte column chunk t of every row and
+// copies row path[j] to row j for j = 1, 2, ... in this order; path[j] >= j and the path is
+// increasing, so a row is never overwritten before it has been read, and threads never share bytes.
+__global__ __launch_bounds__(256) void tree_accept_kernel(const int32_t *__restrict__ parent,
+                                                          const int32_t *__restrict__ token,
+                                                          const int32_t *__restrict__ target, int M,
+                                                          int32_t *__restrict__ path, int32_t *__restrict__ result,
+                                                          u32x4 *k, u32x4 *v, int P, int row_chunks)
+{
+    __shared__ int32_t path_sh[kRowsPad];
+    __shared__ int32_t n_sh;
+    const int tid = threadIdx.x;
+    if (tid < 64) {
+        const int lane = tid;
+        const bool node = lane < M;
+        const int32_t my_parent = node ? parent[lane] : -2;
+        const int32_t my_token = node ? token[lane] : 0;
+        const int32_t my_target = node ? target[lane] : 0;
+        int cur = 0, n = 1;
+        int32_t mine = lane == 0 ? 0 : -1;   // path entry of position `lane`
+        for (;;) {
+            const int32_t want = __shfl(my_target, cur, 64);
+            const uint64_t hits = __ballot(node && lane > cur && my_parent == cur && my_token == want);
+            if (hits == 0) break;
+            cur = __builtin_ctzll(hits);
+            if (lane == n) mine = cur;
+            ++n;
+        }
+        const int32_t next_token = __shfl(my_target, cur, 64);   // the target model's own token after the last accepted node
+        path_sh[lane] = mine;
+        if (node) path[lane] = mine;
+        if (lane == 0) {
+            n_sh = n;
+            result[0] = n;
+            result[1] = next_token;
+        }
+    }
+    __syncthreads();
+    if (k == nullptr) return;
+    const int n = n_sh;
+    for (int item = tid; item < 2 * row_chunks; item += 256) {
+        u32x4 *base = (item < row_chunks ? k : v) + (size_t)P * row_chunks + (item < row_chunks ? item : item - row_chunks);
+        for (int j = 1; j < n; ++j) {
+            const int src = path_sh[j];
+            if (src != j) base[(size_t)j * row_chunks] = base[(size_t)src * row_chunks];
+        }
+    }
+}
+
 static int attn_splits(int M, int P, int Hq)
 {
     int nblk = (P + M + kKeyBlock - 1) / kKeyBlock;
@@ -417,6 +470,28 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
             hipLaunchKernelGGL(tree_attn_merge_kernel<kMaxSplits>, grid, dim3(256), 0, (hipStream_t)stream,
                                (const float *)part_o, (const float *)part_ml, (_Float16 *)out, M, Hq, ns);
     }
+    return launch_status();
+}
+
+int tree_accept(const int32_t *parent, const int32_t *token, const int32_t *target, int M, int32_t *path,
+                int32_t *result, void *k, void *v, int P, int Hkv, int D, void *stream)
+{
+    if (M < 1 || P < 0) return W4A16_EINVAL;
+    if (M > W4A16_MAX_M) return W4A16_EUNSUP;
+    if (!parent || !token || !target || !path || !result) return W4A16_ENULL;
+    if ((k == nullptr) != (v == nullptr)) return W4A16_ENULL;
+    int row_chunks = 0;
+    if (k) {
+        if (Hkv < 1 || D < 1) return W4A16_EINVAL;
+        if (((size_t)Hkv * D * 2) % 16 != 0) return W4A16_EUNSUP;
+        if (misaligned(k) || misaligned(v)) return W4A16_EALIGN;
+        row_chunks = (int)((size_t)Hkv * D * 2 / 16);
+    }
+    if ((reinterpret_cast<uintptr_t>(parent) | reinterpret_cast<uintptr_t>(token) | reinterpret_cast<uintptr_t>(target) |
+         reinterpret_cast<uintptr_t>(path) | reinterpret_cast<uintptr_t>(result)) & 3u)
+        return W4A16_EALIGN;
+    hipLaunchKernelGGL(tree_accept_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, parent, token, target, M, path,
+                       result, (u32x4 *)k, (u32x4 *)v, P, row_chunks);
     return launch_status();
 }
 

@@ -14,13 +14,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared():
     text = open(os.path.join(ROOT, "include", "w4a16.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b((?:w4a16|tree_verify)_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:w4a16|tree)_\w+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported():
     lib = B.load()
     names = _declared()
-    assert "w4a16_gemm" in names and "tree_verify_attn" in names and "w4a16_pack" in names
+    assert "w4a16_gemm" in names and "tree_verify_attn" in names and "w4a16_pack" in names and "tree_accept" in names
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(B.EXPORTS) == names
@@ -103,3 +103,18 @@ def test_product_never_imports_the_oracle():
         for fn in files:
             if fn.endswith((".py", ".hip", ".h")):
                 assert not bad.search(open(os.path.join(dirpath, fn)).read()), (dirpath, fn)
+
+
+def test_tree_accept_rejects_bad_arguments_before_the_gpu():
+    L = B.load()
+    fake, fake2 = 0x1000, 0x2000
+    args = lambda **kw: [kw.get("parent", fake), fake, fake, kw.get("M", 60), fake, kw.get("result", fake),
+                         kw.get("k", fake2), kw.get("v", fake2), kw.get("P", 2048), kw.get("Hkv", 8), kw.get("D", 128), None]
+    assert L.tree_accept(*args(M=0)) == -1
+    assert L.tree_accept(*args(M=65)) == -4
+    assert L.tree_accept(*args(P=-1)) == -1
+    assert L.tree_accept(*args(parent=None)) == -2
+    assert L.tree_accept(*args(v=None)) == -2          # k without v
+    assert L.tree_accept(*args(result=0x1002)) == -3   # 4-byte alignment of the integer buffers
+    assert L.tree_accept(*args(k=0x2008)) == -3        # 16-byte alignment of the cache
+    assert L.tree_accept(*args(Hkv=1, D=4)) == -4      # rows that are not a multiple of 16 bytes
