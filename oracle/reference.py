@@ -13,6 +13,11 @@ Greedy tree acceptance and K/V compaction (the integer step right after verifica
 Python below; pinned in tests/test_oracle_accept.py by brute force over all root paths, chain
 closed forms, planted paths and library gathers.
 
+Layer glue (RMS norm, residual and SiLU-gate epilogues of the linears, rotary embedding with K/V
+append): plain numpy in fp64 at the end of this file; pinned in tests/test_oracle_layer.py by
+closed forms, one-hot inputs that reduce the linear to a table lookup, rotation invariants and the
+torch library routines.
+
 Pin status.  The paper prints no worked numerical example for any of these operations, so beyond the
 pins in tests/test_oracle_*.py (nibble-order fixtures, round trips, closed forms, exact rational
 brute force, numpy/torch library cross-checks, structural invariants) the numerics are unpinned
@@ -206,3 +211,71 @@ def kv_compact(k, v, path, P: int):
         k2[P + j] = k[P + node]
         v2[P + j] = v[P + node]
     return k2, v2
+
+
+# ---------------------------------------------------------------------------------------------
+# the other steps of a decoder layer around the four linears (paper section 2.1: one target-model
+# forward pass over the draft tokens is the unit of cost T_v(n); the target is a Llama-3 model, whose
+# layer is  h += Wo.attn(rope(Wqkv.norm(h)));  h += Wdown.(silu(Wgate.norm(h)) * Wup.norm(h)) ).
+# All in fp64 from the fp16 inputs, one rounding to fp16 at the end of each function.
+
+
+def silu(v):
+    """v * sigmoid(v) = v / (1 + exp(-v)), fp64"""
+    v = np.asarray(v, dtype=np.float64)
+    return v / (1.0 + np.exp(-v))
+
+
+def rms_norm(x, gamma, eps: float):
+    """x fp16 [M, K], gamma fp16 [K] -> (y64, y16):  y[m,k] = x[m,k] * gamma[k] / sqrt(mean_k x[m,:]^2 + eps)"""
+    x64 = np.asarray(x).astype(np.float64)
+    g64 = np.asarray(gamma).astype(np.float64)
+    ms = (x64 * x64).sum(axis=1, keepdims=True) / x64.shape[1]
+    y = x64 * g64[None, :] / np.sqrt(ms + float(eps))
+    return y, y.astype(np.float16)
+
+
+def w4a16_gemm_residual(x, qweight, scales, qzeros, residual, G: int = 128):
+    """(y64, y16):  y = residual + x . W   (the o_proj and down projections add into the hidden state)"""
+    _, y64, _ = w4a16_gemm(x, qweight, scales, qzeros, G, want64=True)
+    y = y64 + np.asarray(residual).astype(np.float64)
+    return y, y.astype(np.float16)
+
+
+def w4a16_gemm_silu_mul(x, qweight, scales, qzeros, G: int = 128):
+    """(y64, y16) of shape [M, N/2]: columns 0..N/2-1 of the weight are the gate projection, columns
+    N/2..N-1 the up projection;  y[m,n] = silu(x.W[:, n]) * (x.W[:, N/2 + n])"""
+    _, y64, _ = w4a16_gemm(x, qweight, scales, qzeros, G, want64=True)
+    half = y64.shape[1] // 2
+    assert 2 * half == y64.shape[1]
+    y = silu(y64[:, :half]) * y64[:, half:]
+    return y, y.astype(np.float16)
+
+
+def rope_append(qkv, pos, cos, sin, k_cache, v_cache, P: int, Hq: int, Hkv: int, D: int):
+    """Rotary position embedding of the q and k parts of a fused projection output and the append of
+    the new keys and values to the cache.
+    qkv fp16 [M, (Hq + 2 Hkv) D]: per row Hq query heads, then Hkv key heads, then Hkv value heads;
+    pos int [M]: position of each row (for a draft tree: prefix length + depth of the node);
+    cos, sin fp32 [n_pos, D/2]: caller's tables, entry [p, i] belongs to position p and the pair of
+    head elements (i, i + D/2):  out[i] = a[i] cos - a[i + D/2] sin,  out[i + D/2] = a[i + D/2] cos + a[i] sin.
+    Returns (q64 [M, Hq, D], q16, k_cache', v_cache') where rows P..P+M-1 of the fp16 caches
+    [>= P+M, Hkv, D] hold the rotated keys and the unchanged values; other rows are untouched."""
+    qkv = np.asarray(qkv)
+    M = qkv.shape[0]
+    assert qkv.shape[1] == (Hq + 2 * Hkv) * D and D % 2 == 0
+    a = qkv.astype(np.float64).reshape(M, Hq + 2 * Hkv, D)
+    c = np.asarray(cos).astype(np.float64)[np.asarray(pos)][:, None, :]   # [M, 1, D/2]
+    s = np.asarray(sin).astype(np.float64)[np.asarray(pos)][:, None, :]
+    h = D // 2
+
+    def rot(t):
+        lo, hi = t[..., :h], t[..., h:]
+        return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+    q = rot(a[:, :Hq])
+    k = rot(a[:, Hq:Hq + Hkv])
+    k2, v2 = np.array(k_cache, copy=True), np.array(v_cache, copy=True)
+    k2[P:P + M] = k.astype(np.float16)
+    v2[P:P + M] = qkv.reshape(M, Hq + 2 * Hkv, D)[:, Hq + Hkv:]
+    return q, q.astype(np.float16), k2, v2

@@ -206,3 +206,37 @@ def make_verify(seed: int, parent: np.ndarray, vocab: int = 128256, p_accept: fl
                 t = int(rng.integers(0, vocab))
             target[p] = t
     return token, target
+
+
+def make_hidden(seed: int, M: int, K: int, n_outlier_channels: int = 8) -> np.ndarray:
+    """fp16 [M, K] stand-in for a decoder layer's hidden state: unit normal with a few channels of
+    eight times the spread (transformer residual streams carry such outlier channels)."""
+    rng = np.random.default_rng(seed)
+    h = rng.standard_normal((M, K), dtype=np.float32)
+    if n_outlier_channels:
+        cols = rng.choice(K, size=min(n_outlier_channels, K), replace=False)
+        h[:, cols] *= 8.0
+    return h.astype(np.float16)
+
+
+def make_gamma(seed: int, K: int) -> np.ndarray:
+    """fp16 [K] norm weights around one"""
+    rng = np.random.default_rng(seed)
+    return (1.0 + 0.1 * rng.standard_normal(K, dtype=np.float32)).astype(np.float16)
+
+
+def make_rope_tables(n_pos: int, D: int = 128, base: float = 500000.0):
+    """The caller-supplied rotary tables of the boundary: cos, sin fp32 [n_pos, D/2] of the angle
+    p * base^(-2i/D) for position p and element pair i (base of the Llama-3 models)."""
+    i = np.arange(D // 2, dtype=np.float64)
+    ang = np.arange(n_pos, dtype=np.float64)[:, None] * base ** (-2.0 * i / D)[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def tree_positions(parent: np.ndarray, P: int) -> np.ndarray:
+    """int32 [n]: position of each draft-tree node = P + its depth (root at depth 0)"""
+    n = len(parent)
+    depth = np.zeros(n, dtype=np.int32)
+    for i in range(1, n):
+        depth[i] = depth[int(parent[i])] + 1
+    return (P + depth).astype(np.int32)
