@@ -106,6 +106,33 @@ int w4a16_dequant(const void *packed, float *W, int N, int K, int G, void *strea
 int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, int G,
                void *workspace, size_t workspace_bytes, void *stream);
 
+/* w4a16_gemm with the element-wise step that follows the linear in a Llama-type decoder layer fused
+ * into the store (paper section 2.1 counts a whole forward pass of the target model per
+ * verification; its layer is h += Wo.attn(..), h += Wdown.(silu(Wgate.n) * Wup.n), so every linear
+ * is followed by a residual add or by the gate):
+ *   W4A16_EPI_NONE      y[M,N]   = x . W                       (identical to w4a16_gemm)
+ *   W4A16_EPI_RESIDUAL  y[M,N]   = residual[M,N] + x . W       residual fp16, 16-byte aligned; it
+ *                                  may be y itself (in place), no other overlap is allowed
+ *   W4A16_EPI_SILU_MUL  y[M,N/2] = silu(x . Wgate) * (x . Wup), silu(t) = t / (1 + exp(-t)); `packed`
+ *                                  must come from w4a16_pack_gate_up, N % 32 == 0
+ * The sum, the residual add and the gate are evaluated in fp32 and rounded to fp16 once.
+ * `residual` must be NULL unless the epilogue is W4A16_EPI_RESIDUAL.  Everything else as for
+ * w4a16_gemm (same workspace size). */
+#define W4A16_EPI_NONE 0
+#define W4A16_EPI_RESIDUAL 1
+#define W4A16_EPI_SILU_MUL 2
+int w4a16_gemm_fused(const void *x, const void *packed, void *y, int M, int N, int K, int G, int epilogue,
+                     const void *residual, void *workspace, size_t workspace_bytes, void *stream);
+
+/* w4a16_pack for a weight whose columns 0..N/2-1 are a gate projection and N/2..N-1 the matching up
+ * projection: the packed buffer holds the 16-column tiles alternately, gate tile j, up tile j, gate
+ * tile j+1, ..., i.e. it equals w4a16_pack of the weight with its columns permuted so that
+ * permuted column 32*j + c is column 16*j + c (c < 16) or N/2 + 16*j + c - 16 (c >= 16).  This is
+ * the layout W4A16_EPI_SILU_MUL needs; every other entry point sees the permuted weight.
+ * Requires N % 32 == 0, otherwise as w4a16_pack. */
+int w4a16_pack_gate_up(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
+                       int N, int K, int G, void *stream);
+
 /* Measurement aid, not part of the method: enqueues a kernel that only reads the first
  * bytes - bytes % 16 bytes of `buf` with 16-byte streaming loads (one 32 KB chunk per workgroup)
  * and writes nothing, except -- practically never -- one 32-bit word to `sink` (4-byte aligned, device)
@@ -147,6 +174,27 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
  * content of parent (an entry that breaks parent[i] < i merely makes node i unreachable). */
 int tree_accept(const int32_t *parent, const int32_t *token, const int32_t *target, int M, int32_t *path,
                 int32_t *result, void *k, void *v, int P, int Hkv, int D, void *stream);
+
+/* Root-mean-square layer norm of the Llama-type target model (paper section 2.1 counts one whole
+ * forward pass per verification; every linear pair of a layer is fed by this norm):
+ *   y[m,k] = x[m,k] * gamma[k] / sqrt(mean_k(x[m,:]^2) + eps),  fp32 arithmetic, one rounding to fp16.
+ * x, y fp16 [M, K] (y may be x: in place), gamma fp16 [K].  Requires K % 8 == 0, K <= 16384, eps >= 0. */
+int rms_norm(const void *x, const void *gamma, void *y, int M, int K, float eps, void *stream);
+
+/* Rotary position embedding of the q and k parts of a fused qkv projection and the append of the new
+ * keys and values to the cache -- the step between the qkv linear and tree_verify_attn.
+ *   qkv       fp16 [M, (Hq + 2 Hkv) D]: per row Hq query heads, Hkv key heads, Hkv value heads
+ *   pos       int32 [M], 4-byte aligned: position of each row (draft tree: prefix length + node depth)
+ *   cos_table, sin_table  fp32 [n_pos, D/2], 4-byte aligned, the caller's tables: entry [p, i] rotates
+ *             the element pair (i, i + D/2) of every head at position p:
+ *               out[i] = a[i] cos - a[i + D/2] sin,   out[i + D/2] = a[i + D/2] cos + a[i] sin
+ *   q         fp16 [M, Hq, D], out
+ *   k_cache, v_cache  fp16 [>= P + M, Hkv, D]: rows P..P+M-1 receive the rotated keys and the values;
+ *             all other rows are left untouched
+ * fp32 arithmetic, one rounding to fp16.  A row whose position lies outside [0, n_pos) gets its
+ * values appended but its q and k rows are left untouched.  Requires D even, D <= 2048. */
+int rope_append(const void *qkv, const int32_t *pos, const float *cos_table, const float *sin_table, int n_pos,
+                void *q, void *k_cache, void *v_cache, int M, int P, int Hq, int Hkv, int D, void *stream);
 
 #ifdef __cplusplus
 }

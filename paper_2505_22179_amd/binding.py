@@ -15,8 +15,11 @@ LIB_PATH = os.environ.get("W4A16_LIB") or os.path.join(_HERE, "lib", "libw4a16.s
 EXPORTS = (
     "w4a16_version", "w4a16_strerror", "w4a16_set_param", "w4a16_get_param", "w4a16_packed_bytes",
     "w4a16_workspace_bytes", "w4a16_workspace_init", "w4a16_pack", "w4a16_unpack", "w4a16_dequant",
-    "w4a16_gemm", "w4a16_read_probe", "tree_verify_attn_workspace_bytes", "tree_verify_attn", "tree_accept",
+    "w4a16_gemm", "w4a16_gemm_fused", "w4a16_pack_gate_up", "w4a16_read_probe", "tree_verify_attn_workspace_bytes",
+    "tree_verify_attn", "tree_accept", "rms_norm", "rope_append",
 )
+
+EPI_NONE, EPI_RESIDUAL, EPI_SILU_MUL = 0, 1, 2
 
 _lib = None
 
@@ -54,6 +57,10 @@ def load() -> ctypes.CDLL:
     L.tree_verify_attn_workspace_bytes.argtypes = [i, i, i, i, i]
     L.tree_verify_attn.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, ctypes.c_float, vp, sz, vp]
     L.tree_accept.argtypes = [vp, vp, vp, i, vp, vp, vp, vp, i, i, i, vp]
+    L.w4a16_gemm_fused.argtypes = [vp, vp, vp, i, i, i, i, i, vp, vp, sz, vp]
+    L.w4a16_pack_gate_up.argtypes = [vp, vp, vp, vp, i, i, i, vp]
+    L.rms_norm.argtypes = [vp, vp, vp, i, i, ctypes.c_float, vp]
+    L.rope_append.argtypes = [vp, vp, vp, vp, i, vp, vp, vp, i, i, i, i, i, vp]
     _lib = L
     return L
 
@@ -128,6 +135,27 @@ def w4a16_gemm(x, packed, y, M: int, N: int, K: int, G: int, workspace) -> None:
     _check(load().w4a16_gemm(_ptr(x), _ptr(packed), _ptr(y), M, N, K, G, _ptr(workspace), nbytes, _stream()), "w4a16_gemm")
 
 
+def w4a16_gemm_fused(x, packed, y, M: int, N: int, K: int, G: int, epilogue: int, residual, workspace) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().w4a16_gemm_fused(_ptr(x), _ptr(packed), _ptr(y), M, N, K, G, int(epilogue), _ptr(residual),
+                                   _ptr(workspace), nbytes, _stream()), "w4a16_gemm_fused")
+
+
+def w4a16_pack_gate_up(qweight, scales, qzeros, packed, N: int, K: int, G: int = 128) -> None:
+    _check(load().w4a16_pack_gate_up(_ptr(qweight), _ptr(scales), _ptr(qzeros), _ptr(packed), N, K, G, _stream()),
+           "w4a16_pack_gate_up")
+
+
+def rms_norm(x, gamma, y, M: int, K: int, eps: float) -> None:
+    _check(load().rms_norm(_ptr(x), _ptr(gamma), _ptr(y), M, K, float(eps), _stream()), "rms_norm")
+
+
+def rope_append(qkv, pos, cos_table, sin_table, n_pos: int, q, k_cache, v_cache, M: int, P: int, Hq: int, Hkv: int,
+                D: int) -> None:
+    _check(load().rope_append(_ptr(qkv), _ptr(pos), _ptr(cos_table), _ptr(sin_table), n_pos, _ptr(q), _ptr(k_cache),
+                              _ptr(v_cache), M, P, Hq, Hkv, D, _stream()), "rope_append")
+
+
 def w4a16_read_probe(buf, nbytes: int, sink) -> None:
     _check(load().w4a16_read_probe(_ptr(buf), int(nbytes), _ptr(sink), _stream()), "w4a16_read_probe")
 
@@ -145,11 +173,11 @@ def tree_accept(parent, token, target, M: int, path, result, k=None, v=None, P: 
 
 # ---- conveniences for tests and the benchmark (still marshalling only) ----
 
-def pack_from_numpy(inp, device="cuda"):
+def pack_from_numpy(inp, device="cuda", gate_up: bool = False):
     """Upload a LinearInputs' canonical tensors and return the packed device buffer."""
     qw = torch.from_numpy(inp.qweight).to(device)
     sc = torch.from_numpy(inp.scales).to(device)
     qz = torch.from_numpy(inp.qzeros).to(device)
     packed = torch.empty(w4a16_packed_bytes(inp.N, inp.K, inp.G), dtype=torch.uint8, device=device)
-    w4a16_pack(qw, sc, qz, packed, inp.N, inp.K, inp.G)
+    (w4a16_pack_gate_up if gate_up else w4a16_pack)(qw, sc, qz, packed, inp.N, inp.K, inp.G)
     return packed

@@ -293,8 +293,18 @@ __device__ __forceinline__ int quad_row(int e4)
     return ((reg >> 2) % MT) * 16 + 4 * (((e4 * 4) & 63) >> 4) + (reg & 3);
 }
 
+// Where the finished sums go.  epi selects what is stored: the sums themselves, the sums plus a
+// residual of the same shape (which may be y itself), or -- for a weight whose 16-column tiles
+// alternate between a gate projection and an up projection -- silu(gate) * up, half as wide.
+constexpr int kEpiNone = 0, kEpiResidual = 1, kEpiSiluMul = 2;
+struct Out {
+    _Float16 *y;
+    const _Float16 *residual;
+    int epi;
+};
+
 template <int MT>
-__device__ __forceinline__ void store_quad(_Float16 *__restrict__ y, float4v v, int e4, int first_col, int M, int N)
+__device__ __forceinline__ void store_quad(const Out &o, float4v v, int e4, int first_col, int M, int N)
 {
     int ln = (e4 * 4) & 63, reg = e4 >> 4;
     int i = reg & 3, tm = reg >> 2;
@@ -302,8 +312,41 @@ __device__ __forceinline__ void store_quad(_Float16 *__restrict__ y, float4v v, 
     int m = mt * 16 + 4 * (ln >> 4) + i;
     int n = first_col + t * 16 + (ln & 15);
     if (m < M && n < N) {   // N % 8 == 0 and n % 4 == 0: the quad never straddles the edge
+        if (o.residual) {   // uniform
+            const half4v r = *reinterpret_cast<const half4v *>(o.residual + (size_t)m * N + n);
+            v += (float4v){(float)r[0], (float)r[1], (float)r[2], (float)r[3]};
+        }
         half4v h = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
-        *reinterpret_cast<half4v *>(y + (size_t)m * N + n) = h;
+        *reinterpret_cast<half4v *>(o.y + (size_t)m * N + n) = h;
+    }
+}
+
+// Gated epilogue.  In a column unit the quads of one tile are 64 * MT consecutive indices, tile after
+// tile, and the tiles alternate gate, up, gate, up ...: pair index idx (0 .. E4/2 - 1) names the gate
+// quad gate_quad(idx); its up quad lies 64 * MT further on.
+template <int MT>
+__device__ __forceinline__ int gate_quad(int idx)
+{
+    constexpr int kTileQuads = 64 * MT;
+    return idx + (idx / kTileQuads) * kTileQuads;
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.f + __expf(-g)) * u; }
+
+// stores silu(g) * u for gate quad e4 (N is the width of the packed weight; the output is N / 2 wide)
+template <int MT>
+__device__ __forceinline__ void store_gated(const Out &o, float4v g, float4v u, int e4, int first_col, int M, int N)
+{
+    int ln = (e4 * 4) & 63, reg = e4 >> 4;
+    int i = reg & 3, tm = reg >> 2;
+    int mt = tm % MT, t = tm / MT;          // t is even: a gate tile
+    int m = mt * 16 + 4 * (ln >> 4) + i;
+    int n = (first_col >> 1) + (t >> 1) * 16 + (ln & 15);
+    const int width = N >> 1;
+    if (m < M && n < width) {
+        half4v h = {(_Float16)silu_mul(g[0], u[0]), (_Float16)silu_mul(g[1], u[1]), (_Float16)silu_mul(g[2], u[2]),
+                    (_Float16)silu_mul(g[3], u[3])};
+        *reinterpret_cast<half4v *>(o.y + (size_t)m * width + n) = h;
     }
 }
 
@@ -345,7 +388,7 @@ __device__ __forceinline__ float4v load_partial(const float *p)
 // take a ticket adds the S partials in split order and stores the result.
 template <int MT, int TW, int NW>
 __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4v *lds4, uint32_t &ticket_sh,
-                                            _Float16 *__restrict__ y, float *__restrict__ partial,
+                                            const Out &y, float *__restrict__ partial,
                                             uint32_t *__restrict__ tickets, int M, int N, int S, int fused, int unit,
                                             int ks, int nb, int t0, int tid, int lane, int wave)
 {
@@ -365,6 +408,19 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
                 lds[(wave * R + (t * MT + mt) * 4 + i) * 64 + lane] = acc[t][mt][i];
     __syncthreads();
     const int first_col = nb * kBlockCols + t0 * 16;
+    if (S == 1 && y.epi == kEpiSiluMul) {   // uniform
+        for (int idx = tid; idx < E4 / 2; idx += kThreads) {
+            const int e4 = gate_quad<MT>(idx);
+            float4v g = lds4[e4], u = lds4[e4 + 64 * MT];
+#pragma unroll
+            for (int w2 = 1; w2 < NW; ++w2) {
+                g += lds4[w2 * E4 + e4];
+                u += lds4[w2 * E4 + e4 + 64 * MT];
+            }
+            store_gated<MT>(y, g, u, e4, first_col, M, N);
+        }
+        return;
+    }
     float4v sum[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
@@ -403,6 +459,20 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
     __syncthreads();
     if (ticket_sh != (uint32_t)(S - 1)) return;
     const float *all = partial + (size_t)unit * S * E4 * 4;
+    if (y.epi == kEpiSiluMul) {   // uniform
+        for (int idx = tid; idx < E4 / 2; idx += kThreads) {
+            const int e4 = gate_quad<MT>(idx);
+            if (quad_row<MT>(e4) >= M) continue;
+            float4v g = (float4v){0.f, 0.f, 0.f, 0.f}, u = g;
+            for (int s = 0; s < S; ++s) {
+                g += load_partial(all + ((size_t)s * E4 + e4) * 4);
+                u += load_partial(all + ((size_t)s * E4 + e4 + 64 * MT) * 4);
+            }
+            store_gated<MT>(y, g, u, e4, first_col, M, N);
+        }
+        if (tid == 0) __hip_atomic_store(&tickets[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
 #pragma unroll
     for (int q = 0; q < Q; ++q) sum[q] = (float4v){0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < S; ++s) {
@@ -421,7 +491,7 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
 // columns, each on its own quantisation groups), DEPTH groups of codes in flight per wavefront.
 template <int MT, int TW, int NW, int DEPTH>
 __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) void gemm_kernel(
-    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
+    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, const Out y,
     float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused,
     int gq, int grem)
 {
@@ -511,7 +581,7 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
 // its first MFMA operands (rows >= M repeat row M-1; their products are never stored).
 template <int TW, int NW, int NG>
 __global__ __launch_bounds__(NW * 64) void gemm_flat_kernel(
-    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
+    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, const Out y,
     float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused)
 {
     extern __shared__ float4v lds4[];
@@ -606,7 +676,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat_kernel(
 // case the fp32 partials go to the workspace and splitk_reduce_kernel finishes the job.
 template <int MT, int TW, int DEPTH>
 __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW == 4 && DEPTH == 2))) ? 2 : 1)) void gemm_ns_kernel(
-    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
+    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, const Out y,
     float *__restrict__ partial, int M, int N, int K, int groups, int S, int gq, int grem)
 {
     extern __shared__ float4v lds4[];
@@ -728,6 +798,13 @@ __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW
             for (int k4 = 0; k4 < 4; ++k4) mine_lds[((t * MT + mt) * 4 + k4) * 64 + lane] = acc[t][mt][k4];
     if (!active) return;
     const int first_col = nb * kBlockCols + t0 * 16;
+    if (S == 1 && y.epi == kEpiSiluMul) {   // uniform
+        for (int idx = lane; idx < E4 / 2; idx += 64) {
+            const int e4 = gate_quad<MT>(idx);
+            store_gated<MT>(y, out4[wave * E4 + e4], out4[wave * E4 + e4 + 64 * MT], e4, first_col, M, N);
+        }
+        return;
+    }
     float4v *part4 = reinterpret_cast<float4v *>(partial) + ((size_t)unit * S + ks) * E4;
 #pragma unroll
     for (int q = 0; q < E4 / 64; ++q) {
@@ -790,7 +867,7 @@ __device__ __forceinline__ void compute_group_lean(const u32x4 (&a)[MT][4], Quan
 // double-buffered, one barrier per step); the KS partial sums of a column meet in LDS at the end.
 template <int MT, int TW, int KS, int DEPTH>
 __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
-    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, _Float16 *__restrict__ y,
+    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, const Out y,
     float *__restrict__ partial, int M, int N, int K, int groups, int S, int gq, int grem)
 {
     extern __shared__ float4v lds4[];
@@ -913,6 +990,19 @@ __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
     __syncthreads();
     if (!active) return;
     const int first_col = nb * kBlockCols + t0 * 16;
+    if (S == 1 && y.epi == kEpiSiluMul) {   // uniform
+        for (int idx = kset * 64 + lane; idx < E4 / 2; idx += 64 * KS) {
+            const int e4 = gate_quad<MT>(idx);
+            float4v g = out4[colq * E4 + e4], u = out4[colq * E4 + e4 + 64 * MT];
+#pragma unroll
+            for (int s = 1; s < KS; ++s) {
+                g += out4[(s * 4 + colq) * E4 + e4];
+                u += out4[(s * 4 + colq) * E4 + e4 + 64 * MT];
+            }
+            store_gated<MT>(y, g, u, e4, first_col, M, N);
+        }
+        return;
+    }
     float4v *part4 = reinterpret_cast<float4v *>(partial) + ((size_t)unit * S + ks) * E4;
     for (int q = kset; q < E4 / 64; q += KS) {
         const int e4 = lane + 64 * q;
@@ -928,7 +1018,7 @@ __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
 constexpr int kReduceThreads = 256;
 template <int MT, int TW>
 __global__ __launch_bounds__(kReduceThreads) void splitk_reduce_kernel(const float *__restrict__ partial,
-                                                                       _Float16 *__restrict__ y, int M, int N, int S)
+                                                                       const Out y, int M, int N, int S)
 {
     constexpr int E4 = 4 * TW * MT * 16;
     constexpr int Q = (E4 + kReduceThreads - 1) / kReduceThreads;
@@ -936,6 +1026,19 @@ __global__ __launch_bounds__(kReduceThreads) void splitk_reduce_kernel(const flo
     const int unit = blockIdx.x, tid = threadIdx.x;
     const int nb = (unit * TW) >> 3, t0 = (unit * TW) & 7;
     const float4v *all = reinterpret_cast<const float4v *>(partial) + (size_t)unit * S * E4;
+    if (y.epi == kEpiSiluMul) {   // uniform
+        for (int idx = tid; idx < E4 / 2; idx += kReduceThreads) {
+            const int e4 = gate_quad<MT>(idx);
+            if (quad_row<MT>(e4) >= M) continue;
+            float4v g = (float4v){0.f, 0.f, 0.f, 0.f}, u = g;
+            for (int s = 0; s < S; ++s) {
+                g += all[(size_t)s * E4 + e4];
+                u += all[(size_t)s * E4 + e4 + 64 * MT];
+            }
+            store_gated<MT>(y, g, u, e4, nb * kBlockCols + t0 * 16, M, N);
+        }
+        return;
+    }
     float4v sum[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) sum[q] = (float4v){0.f, 0.f, 0.f, 0.f};
@@ -1114,7 +1217,7 @@ static size_t partial_bytes(int mt, int nblocks, const Plan &pl)
 }
 
 template <int MT, int TW, int NW, int DEPTH>
-static int launch(const void *x, const void *packed, void *y, int M, int N, int K, int S, int fused,
+static int launch(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, int fused,
                   void *workspace, hipStream_t stream)
 {
     static bool lds_ok = false;   // LDS above 64 KB needs an opt-in, once per kernel
@@ -1131,16 +1234,16 @@ static int launch(const void *x, const void *packed, void *y, int M, int N, int 
     uint32_t *tickets = reinterpret_cast<uint32_t *>(workspace);
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
     hipLaunchKernelGGL((gemm_kernel<MT, TW, NW, DEPTH>), dim3((unsigned)S, (unsigned)units), dim3(NW * 64), lds_bytes,
-                       stream, (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, tickets, M, N,
+                       stream, (const _Float16 *)x, (const uint8_t *)packed, y, partial, tickets, M, N,
                        K, groups, S, fused, groups / S, groups % S);
     if (S > 1 && !fused)
         hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
-                           (const float *)partial, (_Float16 *)y, M, N, S);
+                           (const float *)partial, y, M, N, S);
     return launch_status();
 }
 
 template <int MT, int TW, int DEPTH>
-static int launch_ns(const void *x, const void *packed, void *y, int M, int N, int K, int S, void *workspace,
+static int launch_ns(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, void *workspace,
                      hipStream_t stream)
 {
     static bool lds_ok = false;
@@ -1154,16 +1257,16 @@ static int launch_ns(const void *x, const void *packed, void *y, int M, int N, i
     const int groups = K / kGroup, units = pad_cols(N) / 16 / TW;
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
     hipLaunchKernelGGL((gemm_ns_kernel<MT, TW, DEPTH>), dim3((unsigned)S, (unsigned)((units + 3) / 4)), dim3(256), lds_bytes, stream,
-                       (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, M, N, K, groups, S, groups / S,
+                       (const _Float16 *)x, (const uint8_t *)packed, y, partial, M, N, K, groups, S, groups / S,
                        groups % S);
     if (S > 1)
         hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
-                           (const float *)partial, (_Float16 *)y, M, N, S);
+                           (const float *)partial, y, M, N, S);
     return launch_status();
 }
 
 template <int MT, int TW, int KS, int DEPTH>
-static int launch_cs(const void *x, const void *packed, void *y, int M, int N, int K, int S, void *workspace,
+static int launch_cs(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, void *workspace,
                      hipStream_t stream)
 {
     static bool lds_ok = false;
@@ -1178,16 +1281,16 @@ static int launch_cs(const void *x, const void *packed, void *y, int M, int N, i
     const int groups = K / kGroup, units = pad_cols(N) / 16 / TW;
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
     hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH>), dim3((unsigned)S, (unsigned)((units + 3) / 4)), dim3(256 * KS),
-                       lds_bytes, stream, (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, M, N, K,
+                       lds_bytes, stream, (const _Float16 *)x, (const uint8_t *)packed, y, partial, M, N, K,
                        groups, S, groups / S, groups % S);
     if (S > 1)
         hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
-                           (const float *)partial, (_Float16 *)y, M, N, S);
+                           (const float *)partial, y, M, N, S);
     return launch_status();
 }
 
 template <int TW, int NW, int NG>
-static int launch_flat(const void *x, const void *packed, void *y, int M, int N, int K, int S, int fused,
+static int launch_flat(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, int fused,
                        void *workspace, hipStream_t stream)
 {
     static bool lds_ok = false;
@@ -1206,15 +1309,15 @@ static int launch_flat(const void *x, const void *packed, void *y, int M, int N,
     uint32_t *tickets = reinterpret_cast<uint32_t *>(workspace);
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
     hipLaunchKernelGGL((gemm_flat_kernel<TW, NW, NG>), dim3((unsigned)S, (unsigned)units), dim3(NW * 64), lds_bytes,
-                       stream, (const _Float16 *)x, (const uint8_t *)packed, (_Float16 *)y, partial, tickets, M, N,
+                       stream, (const _Float16 *)x, (const uint8_t *)packed, y, partial, tickets, M, N,
                        K, groups, S, fused);
     if (S > 1 && !fused)
         hipLaunchKernelGGL((splitk_reduce_kernel<1, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
-                           (const float *)partial, (_Float16 *)y, M, N, S);
+                           (const float *)partial, y, M, N, S);
     return launch_status();
 }
 
-static int dispatch(int mt, const Plan &pl, const void *x, const void *packed, void *y, int M, int N, int K,
+static int dispatch(int mt, const Plan &pl, const void *x, const void *packed, const Out &y, int M, int N, int K,
                     void *workspace, hipStream_t stream)
 {
 #define F(TW_, NW_, NG_)                                                           \
@@ -1265,15 +1368,15 @@ size_t w4a16_workspace_bytes(int M_max, int N, int K, int G)
     return kTicketBytes + need;
 }
 
-int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, int G,
-               void *workspace, size_t workspace_bytes, void *stream)
+static int gemm_entry(const void *x, const void *packed, const Out &out, int M, int N, int K, int G, void *workspace,
+                      size_t workspace_bytes, void *stream)
 {
     int rc = check_weight_shape(N, K, G);
     if (rc != W4A16_OK) return rc;
     if (M < 1) return W4A16_EINVAL;
     if (M > W4A16_MAX_M) return W4A16_EUNSUP;
-    if (!x || !packed || !y) return W4A16_ENULL;
-    if (misaligned(x) || misaligned(packed) || misaligned(y) || misaligned(workspace)) return W4A16_EALIGN;
+    if (!x || !packed || !out.y) return W4A16_ENULL;
+    if (misaligned(x) || misaligned(packed) || misaligned(out.y) || misaligned(workspace)) return W4A16_EALIGN;
     const int nblocks = pad_cols(N) / kBlockCols;
     const int mt = (M + 15) / 16;
     Plan pl = choose_plan(M, N, K);
@@ -1283,7 +1386,31 @@ int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, 
         if (!workspace) return W4A16_EWORKSPACE;
         if (workspace_bytes < kTicketBytes + partial_bytes(mt, nblocks, pl)) return W4A16_EWORKSPACE;
     }
-    return dispatch(mt, pl, x, packed, y, M, N, K, workspace, (hipStream_t)stream);
+    return dispatch(mt, pl, x, packed, out, M, N, K, workspace, (hipStream_t)stream);
+}
+
+int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, int G,
+               void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gemm_entry(x, packed, Out{(_Float16 *)y, nullptr, kEpiNone}, M, N, K, G, workspace, workspace_bytes, stream);
+}
+
+int w4a16_gemm_fused(const void *x, const void *packed, void *y, int M, int N, int K, int G, int epilogue,
+                     const void *residual, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (epilogue != W4A16_EPI_NONE && epilogue != W4A16_EPI_RESIDUAL && epilogue != W4A16_EPI_SILU_MUL)
+        return W4A16_EINVAL;
+    if (epilogue == W4A16_EPI_RESIDUAL) {
+        if (!residual) return W4A16_ENULL;
+        if (misaligned(residual)) return W4A16_EALIGN;
+    } else if (residual) {
+        return W4A16_EINVAL;
+    }
+    if (epilogue == W4A16_EPI_SILU_MUL && (N <= 0 || N % 32 != 0)) return W4A16_EINVAL;
+    static_assert(W4A16_EPI_NONE == kEpiNone && W4A16_EPI_RESIDUAL == kEpiResidual && W4A16_EPI_SILU_MUL == kEpiSiluMul,
+                  "public and internal epilogue codes agree");
+    return gemm_entry(x, packed, Out{(_Float16 *)y, (const _Float16 *)residual, epilogue}, M, N, K, G, workspace,
+                      workspace_bytes, stream);
 }
 
 }  // extern "C"

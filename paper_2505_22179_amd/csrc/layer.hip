@@ -1,0 +1,115 @@
+// rms_norm and rope_append: the small element-wise steps of a decoder layer that sit between the
+// linears and the attention.  Contracts in include/w4a16.h.
+#include "internal.h"
+
+namespace w4 {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+
+constexpr int kNormThreads = 256;
+constexpr int kNormChunks = 8;   // 16-byte chunks a thread can hold: K <= 256 * 8 * 8 = 16384
+
+// one workgroup per row: the row stays in registers between the sum of squares and the scaling
+__global__ __launch_bounds__(kNormThreads) void rms_norm_kernel(const _Float16 *__restrict__ x,
+                                                                const _Float16 *__restrict__ gamma,
+                                                                _Float16 *__restrict__ y, int K, float eps)
+{
+    __shared__ float wave_sum[kNormThreads / 64];
+    const int tid = threadIdx.x, m = blockIdx.x;
+    const int chunks = K >> 3;
+    const half8 *xr = reinterpret_cast<const half8 *>(x + (size_t)m * K);
+    half8 v[kNormChunks];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < kNormChunks; ++i) {
+        const int ch = tid + kNormThreads * i;
+        if (ch < chunks) {
+            v[i] = xr[ch];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss = fmaf((float)v[i][e], (float)v[i][e], ss);
+        }
+    }
+    // fixed-order sum: butterfly inside the wavefront, then the four wavefront sums in order
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if ((tid & 63) == 0) wave_sum[tid >> 6] = ss;
+    __syncthreads();
+    float total = 0.f;
+#pragma unroll
+    for (int w = 0; w < kNormThreads / 64; ++w) total += wave_sum[w];
+    const float r = 1.0f / sqrtf(total / (float)K + eps);
+    const half8 *gr = reinterpret_cast<const half8 *>(gamma);
+    half8 *yr = reinterpret_cast<half8 *>(y + (size_t)m * K);
+#pragma unroll
+    for (int i = 0; i < kNormChunks; ++i) {
+        const int ch = tid + kNormThreads * i;
+        if (ch < chunks) {
+            const half8 g = gr[ch];
+            half8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (_Float16)((float)v[i][e] * r * (float)g[e]);
+            yr[ch] = o;
+        }
+    }
+}
+
+// grid (M, Hq + 2 Hkv); thread i of a workgroup owns the element pair (i, i + D/2) of one head
+__global__ void rope_append_kernel(const _Float16 *__restrict__ qkv, const int32_t *__restrict__ pos,
+                                   const float *__restrict__ cos_t, const float *__restrict__ sin_t, int n_pos,
+                                   _Float16 *__restrict__ q, _Float16 *__restrict__ k_cache,
+                                   _Float16 *__restrict__ v_cache, int P, int Hq, int Hkv, int D)
+{
+    const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x, h = D >> 1;
+    if (i >= h) return;
+    const _Float16 *src = qkv + ((size_t)m * (Hq + 2 * Hkv) + head) * D;
+    const float lo = (float)src[i], hi = (float)src[i + h];
+    if (head >= Hq + Hkv) {   // value head: plain copy into the cache
+        _Float16 *dst = v_cache + ((size_t)(P + m) * Hkv + (head - Hq - Hkv)) * D;
+        dst[i] = src[i];
+        dst[i + h] = src[i + h];
+        return;
+    }
+    const int p = pos[m];
+    if (p < 0 || p >= n_pos) return;   // no table entry: this row's q and k are left untouched
+    const float c = cos_t[(size_t)p * h + i], s = sin_t[(size_t)p * h + i];
+    _Float16 *dst = head < Hq ? q + ((size_t)m * Hq + head) * D : k_cache + ((size_t)(P + m) * Hkv + (head - Hq)) * D;
+    dst[i] = (_Float16)fmaf(lo, c, -hi * s);
+    dst[i + h] = (_Float16)fmaf(hi, c, lo * s);
+}
+
+}  // namespace w4
+
+using namespace w4;
+
+extern "C" {
+
+int rms_norm(const void *x, const void *gamma, void *y, int M, int K, float eps, void *stream)
+{
+    if (M < 1 || K < 8 || K % 8 != 0 || !(eps >= 0.f)) return W4A16_EINVAL;
+    if (M > 65535) return W4A16_EUNSUP;
+    if (K > kNormThreads * kNormChunks * 8) return W4A16_EUNSUP;
+    if (!x || !gamma || !y) return W4A16_ENULL;
+    if (misaligned(x) || misaligned(gamma) || misaligned(y)) return W4A16_EALIGN;
+    hipLaunchKernelGGL(rms_norm_kernel, dim3((unsigned)M), dim3(kNormThreads), 0, (hipStream_t)stream,
+                       (const _Float16 *)x, (const _Float16 *)gamma, (_Float16 *)y, K, eps);
+    return launch_status();
+}
+
+int rope_append(const void *qkv, const int32_t *pos, const float *cos_table, const float *sin_table, int n_pos,
+                void *q, void *k_cache, void *v_cache, int M, int P, int Hq, int Hkv, int D, void *stream)
+{
+    if (M < 1 || P < 0 || Hq < 1 || Hkv < 1 || D < 2 || D % 2 != 0 || n_pos < 1) return W4A16_EINVAL;
+    if (M > 65535 || Hq + 2 * Hkv > 65535 || D > 2048) return W4A16_EUNSUP;
+    if (!qkv || !pos || !cos_table || !sin_table || !q || !k_cache || !v_cache) return W4A16_ENULL;
+    if (misaligned(qkv) || misaligned(q) || misaligned(k_cache) || misaligned(v_cache)) return W4A16_EALIGN;
+    if ((reinterpret_cast<uintptr_t>(pos) & 3u) || (reinterpret_cast<uintptr_t>(cos_table) & 3u) ||
+        (reinterpret_cast<uintptr_t>(sin_table) & 3u))
+        return W4A16_EALIGN;
+    const int threads = ((D / 2) + 63) / 64 * 64;
+    hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)M, (unsigned)(Hq + 2 * Hkv)), dim3(threads), 0,
+                       (hipStream_t)stream, (const _Float16 *)qkv, pos, cos_table, sin_table, n_pos, (_Float16 *)q,
+                       (_Float16 *)k_cache, (_Float16 *)v_cache, P, Hq, Hkv, D);
+    return launch_status();
+}
+
+}  // extern "C"

@@ -23,11 +23,21 @@ __device__ __forceinline__ uint32_t permute_fields_to_canonical(uint32_t packed)
     return out;
 }
 
+// canonical column held at packed column n (n < N): n itself, or -- paired layout -- the tiles of
+// the two halves of the weight alternate: packed tile 2j is tile j of columns 0..N/2-1, packed tile
+// 2j+1 is tile j of columns N/2..N-1
+__device__ __forceinline__ int source_column(int n, int N, int paired)
+{
+    if (!paired) return n;
+    const int tile = n >> 4;
+    return (tile & 1) * (N >> 1) + (tile >> 1) * 16 + (n & 15);
+}
+
 // one thread per (record, tile, lane): writes the lane's 16 bytes of codes; threads with t == 0
 // and r == 0 also write the record's scales and zero-points for their column index c.
 __global__ void pack_kernel(const uint32_t *__restrict__ qweight, const uint16_t *__restrict__ scales,
                             const uint32_t *__restrict__ qzeros, uint8_t *__restrict__ packed,
-                            int N, int K, long long total)
+                            int N, int K, long long total, int paired)
 {
     long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
@@ -41,18 +51,19 @@ __global__ void pack_kernel(const uint32_t *__restrict__ qweight, const uint16_t
     int n = nb * kBlockCols + t * 16 + c;
     uint8_t *base = packed + record_offset(nb, g, groups);
     uint4 w = make_uint4(0, 0, 0, 0);
+    const int src = n < N ? source_column(n, N, paired) : 0;
     if (n < N) {
         uint32_t v[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             int kw = g * 16 + j * 4 + r;  // canonical word row: rows 8*kw .. 8*kw+7
-            v[j] = permute_fields_to_packed(qweight[(size_t)kw * N + n]);
+            v[j] = permute_fields_to_packed(qweight[(size_t)kw * N + src]);
         }
         w = make_uint4(v[0], v[1], v[2], v[3]);
     }
     *reinterpret_cast<uint4 *>(base + t * 1024 + lane * 16) = w;
     if (r == 0) {
-        uint16_t s = (n < N) ? scales[(size_t)g * N + n] : (uint16_t)0;
+        uint16_t s = (n < N) ? scales[(size_t)g * N + src] : (uint16_t)0;
         *reinterpret_cast<uint16_t *>(base + kScalesOff + c * 16 + t * 2) = s;
         if (t == 0) {
             uint32_t zw = 0;
@@ -60,7 +71,10 @@ __global__ void pack_kernel(const uint32_t *__restrict__ qweight, const uint16_t
             for (int tt = 0; tt < 8; ++tt) {
                 int nn = nb * kBlockCols + tt * 16 + c;
                 uint32_t z = 0;
-                if (nn < N) z = (qzeros[(size_t)g * (N / 8) + (nn >> 3)] >> (4 * (nn & 7))) & 0xFu;
+                if (nn < N) {
+                    const int ns = source_column(nn, N, paired);
+                    z = (qzeros[(size_t)g * (N / 8) + (ns >> 3)] >> (4 * (ns & 7))) & 0xFu;
+                }
                 zw |= z << (4 * tt);
             }
             *reinterpret_cast<uint32_t *>(base + kZerosOff + c * 4) = zw;
@@ -233,18 +247,31 @@ int w4a16_read_probe(const void *buf, size_t bytes, void *sink, void *stream)
     return launch_status();
 }
 
-int w4a16_pack(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
-               int N, int K, int G, void *stream)
+static int pack_entry(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
+                      int N, int K, int G, void *stream, int paired)
 {
     int rc = check_weight_shape(N, K, G);
     if (rc != W4A16_OK) return rc;
+    if (paired && N % 32 != 0) return W4A16_EINVAL;
     if (!qweight || !scales || !qzeros || !packed) return W4A16_ENULL;
     if (misaligned(qweight) || misaligned(scales) || misaligned(qzeros) || misaligned(packed)) return W4A16_EALIGN;
     long long total = (long long)(pad_cols(N) / kBlockCols) * (K / kGroup) * 512;
     hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
                        (const uint32_t *)qweight, (const uint16_t *)scales, (const uint32_t *)qzeros,
-                       (uint8_t *)packed, N, K, total);
+                       (uint8_t *)packed, N, K, total, paired);
     return launch_status();
+}
+
+int w4a16_pack(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
+               int N, int K, int G, void *stream)
+{
+    return pack_entry(qweight, scales, qzeros, packed, N, K, G, stream, 0);
+}
+
+int w4a16_pack_gate_up(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
+                       int N, int K, int G, void *stream)
+{
+    return pack_entry(qweight, scales, qzeros, packed, N, K, G, stream, 1);
 }
 
 int w4a16_unpack(const void *packed, int32_t *qweight, void *scales, int32_t *qzeros,

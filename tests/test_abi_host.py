@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared():
     text = open(os.path.join(ROOT, "include", "w4a16.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b((?:w4a16|tree)_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:w4a16|tree|rms|rope)_\w+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported():
@@ -118,3 +118,33 @@ def test_tree_accept_rejects_bad_arguments_before_the_gpu():
     assert L.tree_accept(*args(result=0x1002)) == -3   # 4-byte alignment of the integer buffers
     assert L.tree_accept(*args(k=0x2008)) == -3        # 16-byte alignment of the cache
     assert L.tree_accept(*args(Hkv=1, D=4)) == -4      # rows that are not a multiple of 16 bytes
+
+
+def test_layer_glue_validation_happens_before_any_gpu_call():
+    lib = B.load()
+    a = 0x1000
+    EINVAL, ENULL, EALIGN, EUNSUP = -1, -2, -3, -4
+    f = lib.w4a16_gemm_fused
+    assert f(a, a, a, 1, 4096, 4096, 128, 3, None, a, 1 << 30, None) == EINVAL       # unknown epilogue
+    assert f(a, a, a, 1, 4096, 4096, 128, 1, None, a, 1 << 30, None) == ENULL        # residual missing
+    assert f(a, a, a, 1, 4096, 4096, 128, 1, a + 8, a, 1 << 30, None) == EALIGN
+    assert f(a, a, a, 1, 4096, 4096, 128, 0, a, a, 1 << 30, None) == EINVAL          # residual without the epilogue
+    assert f(a, a, a, 1, 4112, 4096, 128, 2, None, a, 1 << 30, None) == EINVAL       # gate/up halves need N % 32 == 0
+    assert f(a, a, a, 65, 4096, 4096, 128, 2, None, a, 1 << 30, None) == EUNSUP
+    assert lib.w4a16_pack_gate_up(a, a, a, a, 4112, 4096, 128, None) == EINVAL
+    assert lib.w4a16_pack_gate_up(a, a, None, a, 4096, 4096, 128, None) == ENULL
+    n = lib.rms_norm
+    assert n(a, a, a, 0, 4096, 1e-5, None) == EINVAL
+    assert n(a, a, a, 1, 4100, 1e-5, None) == EINVAL
+    assert n(a, a, a, 1, 4096, -1.0, None) == EINVAL
+    assert n(a, a, a, 1, 32768, 1e-5, None) == EUNSUP
+    assert n(a, None, a, 1, 4096, 1e-5, None) == ENULL
+    assert n(a, a, a + 4, 1, 4096, 1e-5, None) == EALIGN
+    r = lib.rope_append
+    assert r(a, a, a, a, 64, a, a, a, 0, 10, 8, 2, 128, None) == EINVAL              # M = 0
+    assert r(a, a, a, a, 64, a, a, a, 4, -1, 8, 2, 128, None) == EINVAL              # P < 0
+    assert r(a, a, a, a, 64, a, a, a, 4, 10, 8, 2, 127, None) == EINVAL              # odd head size
+    assert r(a, a, a, a, 0, a, a, a, 4, 10, 8, 2, 128, None) == EINVAL               # empty tables
+    assert r(a, None, a, a, 64, a, a, a, 4, 10, 8, 2, 128, None) == ENULL
+    assert r(a, a + 2, a, a, 64, a, a, a, 4, 10, 8, 2, 128, None) == EALIGN
+    assert r(a, a, a, a, 64, a + 8, a, a, 4, 10, 8, 2, 128, None) == EALIGN
