@@ -52,12 +52,13 @@ class Layer:
         self.copies = copies
         self.packed = []   # [copy][gemm]
         first = []
-        for (_, K, N) in shapes:
+        for (name, K, N) in shapes:
             qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (K // 8, N), dtype=torch.int32, device="cuda", generator=gen)
             sc = (torch.rand((K // G, N), device="cuda", generator=gen) * 9e-3 + 1e-3).to(torch.float16)
             qz = torch.randint(-2 ** 31, 2 ** 31 - 1, (K // G, N // 8), dtype=torch.int32, device="cuda", generator=gen)
             p = torch.empty(B.w4a16_packed_bytes(N, K, G), dtype=torch.uint8, device="cuda")
-            B.w4a16_pack(qw, sc, qz, p, N, K, G)
+            # gate_up in the paired tile order the fused SiLU-gate epilogue reads (same bytes, same cost for the plain GEMM)
+            (B.w4a16_pack_gate_up if name == "gate_up" else B.w4a16_pack)(qw, sc, qz, p, N, K, G)
             first.append(p)
             del qw, sc, qz
         self.packed.append(first)
@@ -96,6 +97,53 @@ class Layer:
             if self.packed[c][gi] is None:
                 self.packed[c][gi] = self.packed[0][gi].clone()
         return need
+
+
+class DecoderLayer:
+    """One whole decoder layer of the target model on M draft-tree tokens over a P-token prefix, chained
+    from the library's entry points: norm, qkv, rotary + K/V append, tree attention, o_proj + residual,
+    norm, gate/up with the SiLU gate, down + residual (8 kernels launches plus the split-K / merge passes)."""
+
+    def __init__(self, layer: "Layer", M: int, P: int, kv_copies: int, Hq: int = 64, Hkv: int = 8, D: int = 128):
+        self.L, self.M, self.P, self.Hq, self.Hkv, self.D = layer, M, P, Hq, Hkv, D
+        (_, H, Nqkv), _, (_, _, Ngu), _ = layer.shapes
+        assert Nqkv == (Hq + 2 * Hkv) * D and H == Hq * D
+        self.H, self.Nqkv, self.Ngu = H, Nqkv, Ngu
+        f16 = lambda *shape: torch.empty(shape, dtype=torch.float16, device="cuda")
+        self.h = torch.from_numpy(I.make_hidden(4242 + M, M, H)).cuda()
+        self.g1 = torch.from_numpy(I.make_gamma(4243, H)).cuda()
+        self.g2 = torch.from_numpy(I.make_gamma(4244, H)).cuda()
+        self.n1, self.qkv, self.q, self.att = f16(M, H), f16(M, Nqkv), f16(M, Hq, D), f16(M, Hq, D)
+        self.h1, self.n2, self.act, self.h2 = f16(M, H), f16(M, H), f16(M, Ngu // 2), f16(M, H)
+        if M > 1:
+            parent, _, mask = I.make_tree(I.seed_for(5, 0) + 7, M, 6, 4)
+        else:
+            parent, mask = np.array([-1]), np.ones((1, 1), dtype=np.uint8)
+        self.mask = torch.from_numpy(mask).cuda()
+        self.pos = torch.from_numpy(I.tree_positions(parent, P)).cuda()
+        cos, sin = I.make_rope_tables(P + 64, D)
+        self.cos, self.sin, self.n_pos = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda(), P + 64
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(77)
+        k0 = torch.randn((P + M, Hkv, D), device="cuda", generator=gen).to(torch.float16)
+        v0 = torch.randn((P + M, Hkv, D), device="cuda", generator=gen).to(torch.float16)
+        self.k = [k0] + [k0.clone() for _ in range(kv_copies - 1)]
+        self.v = [v0] + [v0.clone() for _ in range(kv_copies - 1)]
+        self.aws = B.new_workspace(B.tree_verify_attn_workspace_bytes(M, P, Hq, Hkv, D))
+        self.scale = 1.0 / float(np.sqrt(D))
+
+    def step(self, c: int):
+        L, M, P, Hq, Hkv, D, H = self.L, self.M, self.P, self.Hq, self.Hkv, self.D, self.H
+        w = L.packed[c % L.copies]
+        k, v = self.k[c % len(self.k)], self.v[c % len(self.v)]
+        B.rms_norm(self.h, self.g1, self.n1, M, H, 1e-5)
+        B.w4a16_gemm(self.n1, w[0], self.qkv, M, self.Nqkv, H, G, L.ws)
+        B.rope_append(self.qkv, self.pos, self.cos, self.sin, self.n_pos, self.q, k, v, M, P, Hq, Hkv, D)
+        B.tree_verify_attn(self.q, k, v, self.mask, self.att, M, P, Hq, Hkv, D, self.scale, self.aws)
+        B.w4a16_gemm_fused(self.att, w[1], self.h1, M, H, H, G, B.EPI_RESIDUAL, self.h, L.ws)
+        B.rms_norm(self.h1, self.g2, self.n2, M, H, 1e-5)
+        B.w4a16_gemm_fused(self.n2, w[2], self.act, M, self.Ngu, H, G, B.EPI_SILU_MUL, None, L.ws)
+        B.w4a16_gemm_fused(self.act, w[3], self.h2, M, H, self.Ngu // 2, G, B.EPI_RESIDUAL, self.h1, L.ws)
 
 
 def time_steps(fn, steps: int, warmup: int, use_graph: bool, copies: int):
@@ -280,7 +328,19 @@ def main():
         extra["tree_verify_step_M60"] = {"attn_us": ms_attn * 1e3, "step_us": ms_tree * 1e3,
                                          "accept_and_compact_us": ms_acc * 1e3, "accepted_nodes": int(d_res[0].item())}
         log(f"tree-verify: attn {ms_attn * 1e3:.1f} us, step {ms_tree * 1e3:.1f} us")
-        del big, ks, vs
+        del ks, vs
+        # whole decoder layer (norms, rotary + append, attention, fused epilogues) as one graph per step:
+        # T_t = the layer at M = 1, T_v(n) = the layer on an n-token draft tree, prefix 2048
+        dl = {}
+        for M in (1, 8, 32, 48, 60, 64):
+            layer = DecoderLayer(big, M, 2048, kv_copies=48)
+            ms = time_steps(layer.step, args.steps, args.warmup, use_graph, 48)   # 48 = lcm-friendly with the 3 weight copies
+            dl[M] = ms
+            log(f"70B decoder layer M={M}: {ms * 1e3:.1f} us")
+            del layer
+        extra["llama3_70b_decoder_layer_P2048"] = {
+            str(M): {"us_per_layer": ms * 1e3, "ratio_vs_M1": ms / dl[1], "ms_per_80_layers": ms * 80} for M, ms in dl.items()}
+        del big
         torch.cuda.empty_cache()
         small = Layer(I.LLAMA3_8B, 6, seed=8)   # 6 x 113 MB: never re-read within 512 MB
         s8 = {}

@@ -58,7 +58,9 @@ const char *w4a16_strerror(int code);
  * wavefront owns that many quantisation groups and requests all of their weights up front; needs
  * K / 128 == split_k * waves_per_wg * flat_groups); a combination that is not compiled, or that
  * does not fit the shape, makes w4a16_gemm return W4A16_EUNSUP,
- * "attn_splits" (0 = heuristic, else the number of key ranges per head in tree_verify_attn).
+ * "attn_splits" (0 = heuristic, else the number of key ranges per row tile in tree_verify_attn),
+ * "attn_pack" (0 = the query heads that share a KV head share one 64-row tile whenever
+ * M * Hq/Hkv <= 64, 1 = one tile per query head always).
  * Returns W4A16_EINVAL for an unknown name or an out-of-range value.  Not thread-safe. */
 int w4a16_set_param(const char *name, int value);
 int w4a16_get_param(const char *name);

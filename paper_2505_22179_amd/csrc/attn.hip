@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ k, const _Float16 *__restrict__ v,
     const uint8_t *__restrict__ mask, _Float16 *__restrict__ out, float *__restrict__ part_o,
     float *__restrict__ part_ml, int M, int P, int Hq, int Hkv,
-    float scale_log2e, int nsplit, int bq, int brem)
+    float scale_log2e, int nsplit, int bq, int brem, int rep)
 {
     extern __shared__ float4v smem4[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -63,16 +63,25 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     // its K/V rows are fetched into one L2 instead of all eight.
     int lid = blockIdx.x;
     if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int h = lid / nsplit, sp = lid % nsplit;
-    const int kvh = h / (Hq / Hkv);
+    // A workgroup's 64-row tile holds the M rows of one query head (rep == 0), or -- when they fit --
+    // the M rows of all rep query heads that share a KV head (tile row j * M + m = head j of the
+    // group, query row m): few-row calls then read K and V once per KV head instead of once per head.
+    const int unit = lid / nsplit, sp = lid % nsplit;
+    const int kvh = rep ? unit : unit / (Hq / Hkv);
+    const int R = rep ? M * rep : M;   // valid rows of the tile
     const int T = P + M;
     // key steps of this split: bq = nblk / nsplit each, the first brem = nblk % nsplit one more (host-computed)
     const int b0 = sp * bq + (sp < brem ? sp : brem), b1 = b0 + bq + (sp < brem ? 1 : 0);
     const size_t kv_stride = (size_t)Hkv * kHeadDim;
 
-    int row[4];   // rows >= M repeat row M-1 and are never stored
+    int row[4], head[4];   // query row and head of tile row 16 rt + c; tile rows >= R repeat row R-1 and are never stored
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) row[rt] = min(rt * 16 + c, M - 1);
+    for (int rt = 0; rt < 4; ++rt) {
+        const int rho = min(rt * 16 + c, R - 1);
+        const int j = rep ? rho / M : 0;
+        row[rt] = rho - j * M;
+        head[rt] = rep ? unit * rep + j : unit;
+    }
     // Tree mask as one 64-bit word per query row (bit j = draft key j visible), built once by the
     // workgroups whose key range reaches the draft keys: a byte load per key inside the step loop
     // would put some thirty dependent memory round trips on the critical path of the last steps.
@@ -91,7 +100,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            qf[rt][j] = *reinterpret_cast<const half8v *>(q + ((size_t)row[rt] * Hq + h) * kHeadDim + 32 * j + 8 * r);
+            qf[rt][j] = *reinterpret_cast<const half8v *>(q + ((size_t)row[rt] * Hq + head[rt]) * kHeadDim + 32 * j + 8 * r);
 
     float4v o[8][4];
 #pragma unroll
@@ -286,17 +295,17 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
             for (int w2 = 0; w2 < 4; ++w2) val += wgt[w2] * xq[(w2 * 32 + dt * 4 + rt) * 64 + lane];
             val *= inv;
             // row 16 rt + c, head-dim elements 16 dt + 4r .. + 3: four consecutive outputs
-            if (orow < M) {
+            if (orow < R) {
                 if (last) {
                     typedef _Float16 half4v __attribute__((ext_vector_type(4)));
                     half4v hv = {(_Float16)val[0], (_Float16)val[1], (_Float16)val[2], (_Float16)val[3]};
-                    *reinterpret_cast<half4v *>(out + ((size_t)orow * Hq + h) * kHeadDim + dt * 16 + 4 * r) = hv;
+                    *reinterpret_cast<half4v *>(out + ((size_t)row[rt] * Hq + head[rt]) * kHeadDim + dt * 16 + 4 * r) = hv;
                 } else {
                     *reinterpret_cast<float4v *>(po + orow * kHeadDim + dt * 16 + 4 * r) = val;
                 }
             }
         }
-        if (!last && wave == 0 && r == 0 && orow < M) {
+        if (!last && wave == 0 && r == 0 && orow < R) {
             // partial state of this key range: a second kernel merges the ranges (the kernel boundary
             // makes them visible, at no fence cost)
             pml[orow * 2] = m_all;
@@ -310,14 +319,17 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
 template <int NS>
 __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const float *__restrict__ part_o,
                                                               const float *__restrict__ part_ml,
-                                                              _Float16 *__restrict__ out, int M, int Hq, int nsplit)
+                                                              _Float16 *__restrict__ out, int M, int Hq, int nsplit,
+                                                              int rep)
 {
     const int idx = blockIdx.x * 256 + threadIdx.x;   // over M * Hq * 32 quads
     if (idx >= M * Hq * (kHeadDim / 4)) return;
-    const int d4 = idx % (kHeadDim / 4), h = (idx / (kHeadDim / 4)) % Hq, row = idx / (kHeadDim / 4) / Hq;
+    const int d4 = idx % (kHeadDim / 4), h = (idx / (kHeadDim / 4)) % Hq, qrow = idx / (kHeadDim / 4) / Hq;
     const float NEG_INF = -__builtin_inff();
-    const float *hml = part_ml + (size_t)h * nsplit * kRowsPad * 2;
-    const float4v *ho = reinterpret_cast<const float4v *>(part_o + (size_t)h * nsplit * kRowsPad * kHeadDim);
+    // where the first kernel left this (row, head): tile `unit`, tile row `row` (see tree_attn_kernel)
+    const int unit = rep ? h / rep : h, row = rep ? (h % rep) * M + qrow : qrow;
+    const float *hml = part_ml + (size_t)unit * nsplit * kRowsPad * 2;
+    const float4v *ho = reinterpret_cast<const float4v *>(part_o + (size_t)unit * nsplit * kRowsPad * kHeadDim);
     float ms[NS], ls[NS];
     float4v os[NS];
 #pragma unroll
@@ -345,7 +357,7 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const float *__res
     const float inv = 1.f / den;
     typedef _Float16 half4v __attribute__((ext_vector_type(4)));
     half4v hv = {(_Float16)(num[0] * inv), (_Float16)(num[1] * inv), (_Float16)(num[2] * inv), (_Float16)(num[3] * inv)};
-    *reinterpret_cast<half4v *>(out + ((size_t)row * Hq + h) * kHeadDim + d4 * 4) = hv;
+    *reinterpret_cast<half4v *>(out + ((size_t)qrow * Hq + h) * kHeadDim + d4 * 4) = hv;
 }
 
 // Greedy acceptance of a verified draft tree, then compaction of the accepted K/V rows.
@@ -401,10 +413,17 @@ __global__ __launch_bounds__(256) void tree_accept_kernel(const int32_t *__restr
     }
 }
 
-static int attn_splits(int M, int P, int Hq)
+// query heads per 64-row tile: Hq / Hkv when the rows of a whole KV group fit (and the knob allows), else 0
+static int attn_rep(int M, int Hq, int Hkv)
+{
+    const int rep = Hq / Hkv;
+    return (params().attn_pack != 1 && rep > 1 && M * rep <= kRowsPad) ? rep : 0;
+}
+
+static int attn_splits(int M, int P, int units)
 {
     int nblk = (P + M + kKeyBlock - 1) / kKeyBlock;
-    int want = params().attn_splits > 0 ? params().attn_splits : (256 + Hq - 1) / Hq;   // about one workgroup per compute unit
+    int want = params().attn_splits > 0 ? params().attn_splits : (256 + units - 1) / units;   // about one workgroup per compute unit
     if (want > nblk) want = nblk;
     if (want > kMaxSplits) want = kMaxSplits;
     return want < 1 ? 1 : want;
@@ -440,11 +459,13 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
     if (rc != W4A16_OK) return rc;
     if (!q || !k || !v || !mask || !out) return W4A16_ENULL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace)) return W4A16_EALIGN;
-    const int ns = attn_splits(M, P, Hq);
-    const size_t need = kTicketBytes + (size_t)Hq * ns * kRowsPad * (kHeadDim + 2) * sizeof(float);
+    const int rep = attn_rep(M, Hq, Hkv);
+    const int units = rep ? Hkv : Hq;
+    const int ns = attn_splits(M, P, units);
+    const size_t need = kTicketBytes + (size_t)units * ns * kRowsPad * (kHeadDim + 2) * sizeof(float);
     if (ns > 1 && (!workspace || workspace_bytes < need)) return W4A16_EWORKSPACE;
     float *part_o = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
-    float *part_ml = part_o + (size_t)Hq * ns * kRowsPad * kHeadDim;
+    float *part_ml = part_o + (size_t)units * ns * kRowsPad * kHeadDim;
     const float scale_log2e = scale * 1.4426950408889634f;
     const int nblk = (P + M + kKeyBlock - 1) / kKeyBlock;
     static bool lds_ok = false;   // LDS above 64 KB needs an opt-in, once
@@ -454,21 +475,21 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
             return W4A16_EHIP;
         lds_ok = true;
     }
-    hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)(Hq * ns)), dim3(kAttnThreads), kAttnLdsBytes, (hipStream_t)stream,
+    hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)(units * ns)), dim3(kAttnThreads), kAttnLdsBytes, (hipStream_t)stream,
                        (const _Float16 *)q, (const _Float16 *)k, (const _Float16 *)v, mask, (_Float16 *)out,
-                       part_o, part_ml, M, P, Hq, Hkv, scale_log2e, ns, nblk / ns, nblk % ns);
+                       part_o, part_ml, M, P, Hq, Hkv, scale_log2e, ns, nblk / ns, nblk % ns, rep);
     if (ns > 1) {
         const int quads = M * Hq * (kHeadDim / 4);
         const dim3 grid((unsigned)((quads + 255) / 256));
         if (ns <= 4)
             hipLaunchKernelGGL(tree_attn_merge_kernel<4>, grid, dim3(256), 0, (hipStream_t)stream, (const float *)part_o,
-                               (const float *)part_ml, (_Float16 *)out, M, Hq, ns);
+                               (const float *)part_ml, (_Float16 *)out, M, Hq, ns, rep);
         else if (ns <= 8)
             hipLaunchKernelGGL(tree_attn_merge_kernel<8>, grid, dim3(256), 0, (hipStream_t)stream, (const float *)part_o,
-                               (const float *)part_ml, (_Float16 *)out, M, Hq, ns);
+                               (const float *)part_ml, (_Float16 *)out, M, Hq, ns, rep);
         else
             hipLaunchKernelGGL(tree_attn_merge_kernel<kMaxSplits>, grid, dim3(256), 0, (hipStream_t)stream,
-                               (const float *)part_o, (const float *)part_ml, (_Float16 *)out, M, Hq, ns);
+                               (const float *)part_o, (const float *)part_ml, (_Float16 *)out, M, Hq, ns, rep);
     }
     return launch_status();
 }

@@ -16,6 +16,7 @@ DEV = "cuda"
 def _reset_knobs():
     yield
     B.w4a16_set_param("attn_splits", 0)
+    B.w4a16_set_param("attn_pack", 0)
 
 
 def run_attn(a: I.AttnInputs, ws=None):
@@ -50,6 +51,10 @@ CASES = [
     (1, 0, 8, 1, "identity"),        # a single key
     (33, 31, 8, 2, "identity"),
     (48, 5, 4, 1, "random"),
+    (8, 1000, 64, 8, "random"),      # 8 rows x 8 heads of a KV group fill one 64-row tile exactly
+    (5, 70, 24, 3, "random"),        # 40 of 64 tile rows in use, three KV heads
+    (16, 333, 16, 4, "chain"),       # 4 heads x 16 rows
+    (3, 2, 12, 2, "chain"),          # fewer keys than one step
 ]
 
 
@@ -59,9 +64,11 @@ def test_attn_parity(M, P, Hq, Hkv, tree):
     depth = 6 if M > 6 else max(M - 1, 0)
     a = I.make_attn(8000 + M + P + Hq, M, P, Hq, Hkv, 128, tree=tree, depth=depth)
     ref64, _ = R.tree_verify_attn(a.q, a.k, a.v, a.mask, a.scale)
-    for splits in (0, 1, 3):
-        B.w4a16_set_param("attn_splits", splits)
-        stats = check(run_attn(a), ref64, f"M={M} P={P} {tree} splits={splits}")
+    for pack in ((0, 1) if M * (Hq // Hkv) <= 64 and Hq > Hkv else (0,)):   # shared tile per KV group, and without
+        B.w4a16_set_param("attn_pack", pack)
+        for splits in (0, 1, 3, 16):
+            B.w4a16_set_param("attn_splits", splits)
+            stats = check(run_attn(a), ref64, f"M={M} P={P} {tree} splits={splits} pack={pack}")
     print("   ", stats, flush=True)
 
 
