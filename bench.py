@@ -240,6 +240,8 @@ def main():
     ap.add_argument("--quick", action="store_true", help="headline only (used under the profiler)")
     ap.add_argument("--quick-m", type=int, default=1,
                     help="with --quick: run at this M instead of 1 (profiler runs at other token counts; not the headline)")
+    ap.add_argument("--decoder-layer-only", type=int, default=0, metavar="M",
+                    help="time only the whole decoder layer at this M (profiler runs; prints that one figure)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -252,6 +254,12 @@ def main():
 
     big = Layer(I.LLAMA3_70B, args.copies, seed=70)
     log("70B layer packed")
+    if args.decoder_layer_only:
+        M = args.decoder_layer_only
+        layer = DecoderLayer(big, M, 2048, kv_copies=12)
+        ms = time_steps(layer.step, args.steps, args.warmup, use_graph, 12)
+        print(json.dumps({"metric": "us per Llama-3-70B decoder layer (prefix 2048)", "M": M, "value": ms * 1e3, "unit": "us"}))
+        return
     sweep = {}
     quick_ms = (args.quick_m,)
     for M in (quick_ms if args.quick else I.M_SWEEP_70B):

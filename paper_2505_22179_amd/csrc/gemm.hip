@@ -367,19 +367,23 @@ __device__ __forceinline__ KRange k_range(int ks, int gq, int grem)
     return {begin, begin + gq + (ks < grem ? 1 : 0)};
 }
 
-// coherent-at-device-scope accesses for the split-K partials: they bypass the per-XCD L2's
-// non-coherent lines one access at a time, so no whole-cache write-back or invalidate is needed
-__device__ __forceinline__ void store_partial(float *p, float4v v)
+// Coherent-at-device-scope 16-byte accesses for the split-K partials of the last-arriver mode: they
+// bypass the per-XCD L2's non-coherent lines one access at a time, so no whole-cache write-back or
+// invalidate is needed.  The partials of one column unit are addressed through a buffer descriptor
+// (wavefront-uniform base) and the index of the 16-byte quad.
+typedef __amdgpu_buffer_rsrc_t PartialBuffer;
+constexpr int kDeviceScope = 16;   // cache-policy bit sc1
+__device__ __forceinline__ PartialBuffer partial_buffer(const float *base)
 {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) __hip_atomic_store(p + i, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0, 0x7FFFFFFF, 0x00020000);
 }
-__device__ __forceinline__ float4v load_partial(const float *p)
+__device__ __forceinline__ void store_partial(PartialBuffer b, int quad, float4v v)
 {
-    float4v v;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = __hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return v;
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), b, quad * 16, 0, kDeviceScope);
+}
+__device__ __forceinline__ float4v load_partial(PartialBuffer b, int quad)
+{
+    return __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(b, quad * 16, 0, kDeviceScope));
 }
 
 // Epilogue shared by the K-split kernels: the NW wavefronts' accumulators are summed through LDS
@@ -449,24 +453,24 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
         return;
     }
     // the last workgroup of this column unit to arrive sums all S partials in split order
+    const PartialBuffer all = partial_buffer(partial + (size_t)unit * S * E4 * 4);
 #pragma unroll
     for (int q = 0; q < Q; ++q)
         if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
-            store_partial(mine + (size_t)(tid + kThreads * q) * 4, sum[q]);
+            store_partial(all, ks * E4 + tid + kThreads * q, sum[q]);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partials have reached device scope
     __syncthreads();
     if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_sh != (uint32_t)(S - 1)) return;
-    const float *all = partial + (size_t)unit * S * E4 * 4;
     if (y.epi == kEpiSiluMul) {   // uniform
         for (int idx = tid; idx < E4 / 2; idx += kThreads) {
             const int e4 = gate_quad<MT>(idx);
             if (quad_row<MT>(e4) >= M) continue;
             float4v g = (float4v){0.f, 0.f, 0.f, 0.f}, u = g;
             for (int s = 0; s < S; ++s) {
-                g += load_partial(all + ((size_t)s * E4 + e4) * 4);
-                u += load_partial(all + ((size_t)s * E4 + e4 + 64 * MT) * 4);
+                g += load_partial(all, s * E4 + e4);
+                u += load_partial(all, s * E4 + e4 + 64 * MT);
             }
             store_gated<MT>(y, g, u, e4, first_col, M, N);
         }
@@ -479,7 +483,7 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
 #pragma unroll
         for (int q = 0; q < Q; ++q)
             if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
-                sum[q] += load_partial(all + ((size_t)s * E4 + tid + kThreads * q) * 4);
+                sum[q] += load_partial(all, s * E4 + tid + kThreads * q);
     }
 #pragma unroll
     for (int q = 0; q < Q; ++q)
@@ -868,9 +872,11 @@ __device__ __forceinline__ void compute_group_lean(const u32x4 (&a)[MT][4], Quan
 template <int MT, int TW, int KS, int DEPTH>
 __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
     const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, const Out y,
-    float *__restrict__ partial, int M, int N, int K, int groups, int S, int gq, int grem)
+    float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused,
+    int gq, int grem)
 {
     extern __shared__ float4v lds4[];
+    __shared__ uint32_t ticket_sh;
     constexpr int R = 4 * TW * MT;                 // accumulator registers per lane
     constexpr int E4 = R * 16;                     // float4 results per wavefront
     constexpr int kBufQuads = KS * MT * 4 * 64;    // 16-byte fragments of one step's x tiles
@@ -988,29 +994,74 @@ __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
 #pragma unroll
             for (int k4 = 0; k4 < 4; ++k4) mine_lds[((t * MT + mt) * 4 + k4) * 64 + lane] = acc[t][mt][k4];
     __syncthreads();
-    if (!active) return;
     const int first_col = nb * kBlockCols + t0 * 16;
-    if (S == 1 && y.epi == kEpiSiluMul) {   // uniform
+    if (S == 1) {
+        if (!active) return;
+        if (y.epi == kEpiSiluMul) {   // uniform
+            for (int idx = kset * 64 + lane; idx < E4 / 2; idx += 64 * KS) {
+                const int e4 = gate_quad<MT>(idx);
+                float4v g = out4[colq * E4 + e4], u = out4[colq * E4 + e4 + 64 * MT];
+#pragma unroll
+                for (int s = 1; s < KS; ++s) {
+                    g += out4[(s * 4 + colq) * E4 + e4];
+                    u += out4[(s * 4 + colq) * E4 + e4 + 64 * MT];
+                }
+                store_gated<MT>(y, g, u, e4, first_col, M, N);
+            }
+            return;
+        }
+        for (int q = kset; q < E4 / 64; q += KS) {
+            const int e4 = lane + 64 * q;
+            float4v v = out4[colq * E4 + e4];
+#pragma unroll
+            for (int s = 1; s < KS; ++s) v += out4[(s * 4 + colq) * E4 + e4];
+            store_quad<MT>(y, v, e4, first_col, M, N);
+        }
+        return;
+    }
+    // K split across workgroups: this workgroup's sums go to the workspace.  Two-kernel mode ends
+    // here; otherwise they are published at device scope and the last workgroup of the column unit
+    // to take a ticket adds the S partials in split order and stores the result.
+    float *mine_part = partial + ((size_t)unit * S + ks) * E4 * 4;
+    const PartialBuffer all = partial_buffer(partial + (size_t)unit * S * E4 * 4);
+    if (active) {
+        for (int q = kset; q < E4 / 64; q += KS) {
+            const int e4 = lane + 64 * q;
+            if (quad_row<MT>(e4) >= M) continue;
+            float4v v = out4[colq * E4 + e4];
+#pragma unroll
+            for (int s = 1; s < KS; ++s) v += out4[(s * 4 + colq) * E4 + e4];
+            if (fused) store_partial(all, ks * E4 + e4, v);
+            else reinterpret_cast<float4v *>(mine_part)[e4] = v;
+        }
+    }
+    if (!fused) return;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partials have reached device scope
+    __syncthreads();
+    if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[wg_unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (ticket_sh != (uint32_t)(S - 1)) return;
+    if (tid == 0) __hip_atomic_store(&tickets[wg_unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!active) return;
+    if (y.epi == kEpiSiluMul) {   // uniform
         for (int idx = kset * 64 + lane; idx < E4 / 2; idx += 64 * KS) {
             const int e4 = gate_quad<MT>(idx);
-            float4v g = out4[colq * E4 + e4], u = out4[colq * E4 + e4 + 64 * MT];
-#pragma unroll
-            for (int s = 1; s < KS; ++s) {
-                g += out4[(s * 4 + colq) * E4 + e4];
-                u += out4[(s * 4 + colq) * E4 + e4 + 64 * MT];
+            if (quad_row<MT>(e4) >= M) continue;
+            float4v g = (float4v){0.f, 0.f, 0.f, 0.f}, u = g;
+            for (int s = 0; s < S; ++s) {
+                g += load_partial(all, s * E4 + e4);
+                u += load_partial(all, s * E4 + e4 + 64 * MT);
             }
             store_gated<MT>(y, g, u, e4, first_col, M, N);
         }
         return;
     }
-    float4v *part4 = reinterpret_cast<float4v *>(partial) + ((size_t)unit * S + ks) * E4;
     for (int q = kset; q < E4 / 64; q += KS) {
         const int e4 = lane + 64 * q;
-        float4v v = out4[colq * E4 + e4];
-#pragma unroll
-        for (int s = 1; s < KS; ++s) v += out4[(s * 4 + colq) * E4 + e4];
-        if (S == 1) store_quad<MT>(y, v, e4, first_col, M, N);
-        else if (quad_row<MT>(e4) < M) part4[e4] = v;
+        if (quad_row<MT>(e4) >= M) continue;
+        float4v v = (float4v){0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < S; ++s) v += load_partial(all, s * E4 + e4);
+        store_quad<MT>(y, v, e4, first_col, M, N);
     }
 }
 
@@ -1165,7 +1216,7 @@ static Plan choose_plan(int M, int N, int K)
         const int tw = p.tiles_per_wave ? p.tiles_per_wave : 4, depth = p.prefetch_depth ? p.prefetch_depth : 2;
         int s = p.split_k > 0 ? p.split_k : 1;
         if (s > groups) s = groups;
-        if (variant_exists(mt, tw, 0, depth, p.k_sets)) best = {tw, 0, depth, s, 0, p.k_sets, 0};
+        if (variant_exists(mt, tw, 0, depth, p.k_sets)) best = {tw, 0, depth, s, p.fused_reduce == 1, p.k_sets, 0};
         return best;
     }
     if (best.tw == 0 && free_choice && mt > 1) {
@@ -1266,8 +1317,8 @@ static int launch_ns(const void *x, const void *packed, const Out &y, int M, int
 }
 
 template <int MT, int TW, int KS, int DEPTH>
-static int launch_cs(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, void *workspace,
-                     hipStream_t stream)
+static int launch_cs(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, int fused,
+                     void *workspace, hipStream_t stream)
 {
     static bool lds_ok = false;
     const size_t lds_bytes = (size_t)KS * TW * MT * 4096;   // 4*KS wavefronts' results; the x tiles (KS * MT * 8 KB) fit inside
@@ -1279,11 +1330,12 @@ static int launch_cs(const void *x, const void *packed, const Out &y, int M, int
         lds_ok = true;
     }
     const int groups = K / kGroup, units = pad_cols(N) / 16 / TW;
+    uint32_t *tickets = reinterpret_cast<uint32_t *>(workspace);
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
     hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH>), dim3((unsigned)S, (unsigned)((units + 3) / 4)), dim3(256 * KS),
-                       lds_bytes, stream, (const _Float16 *)x, (const uint8_t *)packed, y, partial, M, N, K,
-                       groups, S, groups / S, groups % S);
-    if (S > 1)
+                       lds_bytes, stream, (const _Float16 *)x, (const uint8_t *)packed, y, partial, tickets, M, N, K,
+                       groups, S, fused, groups / S, groups % S);
+    if (S > 1 && !fused)
         hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
                            (const float *)partial, y, M, N, S);
     return launch_status();
@@ -1330,7 +1382,7 @@ static int dispatch(int mt, const Plan &pl, const void *x, const void *packed, c
 #undef F
 #define Z(MT_, TW_, KS_, D_)                                                       \
     if (mt == MT_ && pl.ks == KS_ && pl.tw == TW_ && pl.depth == D_)               \
-        return launch_cs<MT_, TW_, KS_, D_>(x, packed, y, M, N, K, pl.S, workspace, stream);
+        return launch_cs<MT_, TW_, KS_, D_>(x, packed, y, M, N, K, pl.S, pl.fused, workspace, stream);
     if (pl.ks > 0) {
         W4_CS_VARIANTS(Z)
         return W4A16_EUNSUP;

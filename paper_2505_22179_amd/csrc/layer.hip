@@ -6,10 +6,11 @@ namespace w4 {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
-constexpr int kNormThreads = 256;
-constexpr int kNormChunks = 8;   // 16-byte chunks a thread can hold: K <= 256 * 8 * 8 = 16384
+constexpr int kNormThreads = 1024;
+constexpr int kNormChunks = 2;   // 16-byte chunks a thread can hold: K <= 1024 * 2 * 8 = 16384
 
-// one workgroup per row: the row stays in registers between the sum of squares and the scaling
+// one workgroup per row: the row stays in registers between the sum of squares and the scaling;
+// the norm weights are requested together with the row, so one memory round trip covers both
 __global__ __launch_bounds__(kNormThreads) void rms_norm_kernel(const _Float16 *__restrict__ x,
                                                                 const _Float16 *__restrict__ gamma,
                                                                 _Float16 *__restrict__ y, int K, float eps)
@@ -18,18 +19,25 @@ __global__ __launch_bounds__(kNormThreads) void rms_norm_kernel(const _Float16 *
     const int tid = threadIdx.x, m = blockIdx.x;
     const int chunks = K >> 3;
     const half8 *xr = reinterpret_cast<const half8 *>(x + (size_t)m * K);
-    half8 v[kNormChunks];
-    float ss = 0.f;
+    const half8 *gr = reinterpret_cast<const half8 *>(gamma);
+    half8 v[kNormChunks], g[kNormChunks];
 #pragma unroll
     for (int i = 0; i < kNormChunks; ++i) {
         const int ch = tid + kNormThreads * i;
         if (ch < chunks) {
             v[i] = xr[ch];
+            g[i] = gr[ch];
+        }
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < kNormChunks; ++i) {
+        if (tid + kNormThreads * i < chunks) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) ss = fmaf((float)v[i][e], (float)v[i][e], ss);
         }
     }
-    // fixed-order sum: butterfly inside the wavefront, then the four wavefront sums in order
+    // fixed-order sum: butterfly inside the wavefront, then the wavefront sums in order
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
     if ((tid & 63) == 0) wave_sum[tid >> 6] = ss;
@@ -38,43 +46,48 @@ __global__ __launch_bounds__(kNormThreads) void rms_norm_kernel(const _Float16 *
 #pragma unroll
     for (int w = 0; w < kNormThreads / 64; ++w) total += wave_sum[w];
     const float r = 1.0f / sqrtf(total / (float)K + eps);
-    const half8 *gr = reinterpret_cast<const half8 *>(gamma);
     half8 *yr = reinterpret_cast<half8 *>(y + (size_t)m * K);
 #pragma unroll
     for (int i = 0; i < kNormChunks; ++i) {
         const int ch = tid + kNormThreads * i;
         if (ch < chunks) {
-            const half8 g = gr[ch];
             half8 o;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (_Float16)((float)v[i][e] * r * (float)g[e]);
+            for (int e = 0; e < 8; ++e) o[e] = (_Float16)((float)v[i][e] * r * (float)g[i][e]);
             yr[ch] = o;
         }
     }
 }
 
-// grid (M, Hq + 2 Hkv); thread i of a workgroup owns the element pair (i, i + D/2) of one head
-__global__ void rope_append_kernel(const _Float16 *__restrict__ qkv, const int32_t *__restrict__ pos,
-                                   const float *__restrict__ cos_t, const float *__restrict__ sin_t, int n_pos,
-                                   _Float16 *__restrict__ q, _Float16 *__restrict__ k_cache,
-                                   _Float16 *__restrict__ v_cache, int P, int Hq, int Hkv, int D)
+// one workgroup per row: thread t owns the element pair (i, i + D/2), i = t % (D/2), of the heads
+// t / (D/2), t / (D/2) + heads_per_pass, ...; its table entry is fetched once and serves every head
+constexpr int kRopeThreads = 1024;
+__global__ __launch_bounds__(kRopeThreads) void rope_append_kernel(
+    const _Float16 *__restrict__ qkv, const int32_t *__restrict__ pos, const float *__restrict__ cos_t,
+    const float *__restrict__ sin_t, int n_pos, _Float16 *__restrict__ q, _Float16 *__restrict__ k_cache,
+    _Float16 *__restrict__ v_cache, int P, int Hq, int Hkv, int D)
 {
-    const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x, h = D >> 1;
-    if (i >= h) return;
-    const _Float16 *src = qkv + ((size_t)m * (Hq + 2 * Hkv) + head) * D;
-    const float lo = (float)src[i], hi = (float)src[i + h];
-    if (head >= Hq + Hkv) {   // value head: plain copy into the cache
-        _Float16 *dst = v_cache + ((size_t)(P + m) * Hkv + (head - Hq - Hkv)) * D;
-        dst[i] = src[i];
-        dst[i + h] = src[i + h];
-        return;
-    }
+    const int m = blockIdx.x, h = D >> 1;
+    const int heads_per_pass = kRopeThreads / h;
+    const int i = threadIdx.x % h, slot = threadIdx.x / h;
+    if (slot >= heads_per_pass) return;
+    const int heads = Hq + 2 * Hkv;
     const int p = pos[m];
-    if (p < 0 || p >= n_pos) return;   // no table entry: this row's q and k are left untouched
-    const float c = cos_t[(size_t)p * h + i], s = sin_t[(size_t)p * h + i];
-    _Float16 *dst = head < Hq ? q + ((size_t)m * Hq + head) * D : k_cache + ((size_t)(P + m) * Hkv + (head - Hq)) * D;
-    dst[i] = (_Float16)fmaf(lo, c, -hi * s);
-    dst[i + h] = (_Float16)fmaf(hi, c, lo * s);
+    const bool in_table = p >= 0 && p < n_pos;   // otherwise this row's q and k are left untouched
+    const float c = in_table ? cos_t[(size_t)p * h + i] : 0.f, s = in_table ? sin_t[(size_t)p * h + i] : 0.f;
+    for (int head = slot; head < heads; head += heads_per_pass) {
+        const _Float16 *src = qkv + ((size_t)m * heads + head) * D;
+        if (head >= Hq + Hkv) {   // value head: plain copy into the cache
+            _Float16 *dst = v_cache + ((size_t)(P + m) * Hkv + (head - Hq - Hkv)) * D;
+            dst[i] = src[i];
+            dst[i + h] = src[i + h];
+        } else if (in_table) {
+            const float lo = (float)src[i], hi = (float)src[i + h];
+            _Float16 *dst = head < Hq ? q + ((size_t)m * Hq + head) * D : k_cache + ((size_t)(P + m) * Hkv + (head - Hq)) * D;
+            dst[i] = (_Float16)fmaf(lo, c, -hi * s);
+            dst[i + h] = (_Float16)fmaf(hi, c, lo * s);
+        }
+    }
 }
 
 }  // namespace w4
@@ -99,14 +112,13 @@ int rope_append(const void *qkv, const int32_t *pos, const float *cos_table, con
                 void *q, void *k_cache, void *v_cache, int M, int P, int Hq, int Hkv, int D, void *stream)
 {
     if (M < 1 || P < 0 || Hq < 1 || Hkv < 1 || D < 2 || D % 2 != 0 || n_pos < 1) return W4A16_EINVAL;
-    if (M > 65535 || Hq + 2 * Hkv > 65535 || D > 2048) return W4A16_EUNSUP;
+    if (M > 65535 || D > 2 * kRopeThreads) return W4A16_EUNSUP;
     if (!qkv || !pos || !cos_table || !sin_table || !q || !k_cache || !v_cache) return W4A16_ENULL;
     if (misaligned(qkv) || misaligned(q) || misaligned(k_cache) || misaligned(v_cache)) return W4A16_EALIGN;
     if ((reinterpret_cast<uintptr_t>(pos) & 3u) || (reinterpret_cast<uintptr_t>(cos_table) & 3u) ||
         (reinterpret_cast<uintptr_t>(sin_table) & 3u))
         return W4A16_EALIGN;
-    const int threads = ((D / 2) + 63) / 64 * 64;
-    hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)M, (unsigned)(Hq + 2 * Hkv)), dim3(threads), 0,
+    hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)M), dim3(kRopeThreads), 0,
                        (hipStream_t)stream, (const _Float16 *)qkv, pos, cos_table, sin_table, n_pos, (_Float16 *)q,
                        (_Float16 *)k_cache, (_Float16 *)v_cache, P, Hq, Hkv, D);
     return launch_status();

@@ -87,7 +87,8 @@ def candidates(N: int, K: int, M: int):
                         wgs = ((N // 16) // tw + 3) // 4 * S
                         if wgs < 160 or wgs > 2048 or S * ks * 2 > K // G:
                             continue
-                        yield (tw, 0, depth, S, 0, ks, 0)
+                        for fused in ((0,) if S == 1 else (0, 1)):
+                            yield (tw, 0, depth, S, fused, ks, 0)
     for tw in (8, 4, 2):
         for nw in (1, 4, 8, 16):   # 1 = column-split workgroup sharing x through LDS
             for depth in (1, 2, 4):

@@ -121,8 +121,10 @@ def test_parity_high_occupancy(M, K, N, big_ws):
         if variant[0] == 4 and variant[1] == 2 and M > 32:
             continue   # compiled for at most two row tiles
         set_cs_variant(*variant)
-        check_gemm(run_gemm(inp, packed, big_ws), y32, f"M={M} K={K} N={N} (tw, ks, depth, split)={variant}")
-        assert np.array_equal(run_gemm(ex, ex_packed, big_ws).view(np.uint16), ex16.view(np.uint16)), variant
+        for fused in ((0, 1) if variant[3] > 1 else (0,)):   # K splits summed by a second kernel, or by the last workgroup to arrive
+            B.w4a16_set_param("fused_reduce", fused)
+            check_gemm(run_gemm(inp, packed, big_ws), y32, f"M={M} K={K} N={N} (tw, ks, depth, split)={variant} fused={fused}")
+            assert np.array_equal(run_gemm(ex, ex_packed, big_ws).view(np.uint16), ex16.view(np.uint16)), (variant, fused)
 
 
 # all-loads-up-front kernel, M <= 4 only: (tiles_per_wave, waves_per_wg, flat_groups, split_k, fused_reduce);
