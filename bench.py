@@ -146,6 +146,38 @@ class DecoderLayer:
         B.w4a16_gemm_fused(self.act, w[3], self.h2, M, H, self.Ngu // 2, G, B.EPI_RESIDUAL, self.h1, L.ws)
 
 
+# Expected accepted length tau(n, d) of EAGLE-2 on the W4A16 Llama-3-70B target, read off the paper's
+# figure "Accepted Length (70B, A100)" (W4A16 series; tree sizes n with d = 3, 4, 5, 6 draft passes).
+PAPER_TAU_70B_W4A16 = {24: (3, 3.283), 32: (4, 3.630), 40: (5, 3.819), 48: (6, 3.926)}
+# the same figure group's verification-to-decoding time ratio on an A100, for comparison
+PAPER_RATIO_70B_W4A16_A100 = {24: 1.262, 32: 1.287, 40: 1.555, 48: 1.580}
+
+
+def eq1_projection(layer_ms: dict, read_GBps: float) -> dict:
+    """The paper's speedup model (Eq. 1), T_sd/T_t = (d T_d/T_t + T_v(n)/T_t) / tau(n, d), fed with
+    this GPU's measured decoder-layer times for T_v(n)/T_t and the paper's tau.  The draft model is
+    not built here: its time is ESTIMATED as the bytes one pass of an EAGLE-2 draft has to stream (one
+    fp16 decoder layer of the target's shape, the 2H->H fusion layer and the fp16 LM head) at the
+    plain-read rate measured above, and the target's own fp16 LM head is added to both T_t and T_v.
+    A projection for context, not a measurement of speculative decoding."""
+    H, V, layers = 8192, 128256, 80
+    layer_params = sum(K * N for (_, K, N) in I.LLAMA3_70B)
+    lm_head_ms = V * H * 2 / (read_GBps * 1e6)
+    draft_ms = (layer_params * 2 + 2 * H * H * 2) / (read_GBps * 1e6) + lm_head_ms
+    t_t = layer_ms[1] * layers + lm_head_ms
+    out = {"inputs": {"tau": "paper, figure 'Accepted Length (70B, A100)', W4A16 series",
+                      "T_v_over_T_t": "measured here: 80 x decoder layer (prefix 2048) + estimated fp16 LM head",
+                      "T_d": "estimated from bytes at the measured plain-read rate, not measured",
+                      "T_t_ms": t_t, "T_d_ms_estimated": draft_ms, "lm_head_ms_estimated": lm_head_ms}}
+    for n, (d, tau) in PAPER_TAU_70B_W4A16.items():
+        t_v = layer_ms[n] * layers + lm_head_ms
+        out[str(n)] = {"d": d, "tau_paper": tau, "T_v_over_T_t": t_v / t_t,
+                       "T_v_over_T_t_paper_A100": PAPER_RATIO_70B_W4A16_A100[n],
+                       "speedup_over_own_autoregressive_no_draft_cost": tau / (t_v / t_t),
+                       "speedup_over_own_autoregressive_estimated_draft": tau / (d * draft_ms / t_t + t_v / t_t)}
+    return out
+
+
 def time_steps(fn, steps: int, warmup: int, use_graph: bool, copies: int):
     """fn(copy_index) enqueues one step.  Warm up, then time exactly `steps` steps between two
     events on the launch stream.  With graphs, `copies` consecutive steps form one HIP graph (so the
@@ -340,7 +372,7 @@ def main():
         # whole decoder layer (norms, rotary + append, attention, fused epilogues) as one graph per step:
         # T_t = the layer at M = 1, T_v(n) = the layer on an n-token draft tree, prefix 2048
         dl = {}
-        for M in (1, 8, 32, 48, 60, 64):
+        for M in (1, 7, 8, 24, 32, 40, 48, 60, 64):
             layer = DecoderLayer(big, M, 2048, kv_copies=48)
             ms = time_steps(layer.step, args.steps, args.warmup, use_graph, 48)   # 48 = lcm-friendly with the 3 weight copies
             dl[M] = ms
@@ -348,6 +380,7 @@ def main():
             del layer
         extra["llama3_70b_decoder_layer_P2048"] = {
             str(M): {"us_per_layer": ms * 1e3, "ratio_vs_M1": ms / dl[1], "ms_per_80_layers": ms * 80} for M, ms in dl.items()}
+        extra["eq1_projection_70b"] = eq1_projection(dl, plain["gate_up"]["GBps"])
         del big
         torch.cuda.empty_cache()
         small = Layer(I.LLAMA3_8B, 6, seed=8)   # 6 x 113 MB: never re-read within 512 MB
