@@ -18,6 +18,10 @@ append): plain numpy in fp64 at the end of this file; pinned in tests/test_oracl
 closed forms, one-hot inputs that reduce the linear to a table lookup, rotation invariants and the
 torch library routines.
 
+Draft-side LM head with log-softmax and top-k: numpy fp64 at the end of this file; pinned in
+tests/test_oracle_lm_head.py (one-hot rows, planted winners, probabilities that sum to one, ties,
+torch's log_softmax / topk).
+
 Pin status.  The paper prints no worked numerical example for any of these operations, so beyond the
 pins in tests/test_oracle_*.py (nibble-order fixtures, round trips, closed forms, exact rational
 brute force, numpy/torch library cross-checks, structural invariants) the numerics are unpinned
@@ -279,3 +283,28 @@ def rope_append(qkv, pos, cos, sin, k_cache, v_cache, P: int, Hq: int, Hkv: int,
     k2[P:P + M] = k.astype(np.float16)
     v2[P:P + M] = qkv.reshape(M, Hq + 2 * Hkv, D)[:, Hq + Hkv:]
     return q, q.astype(np.float16), k2, v2
+
+
+# ---------------------------------------------------------------------------------------------
+# draft side: fp16 language-model head, log-softmax and top-k (paper section 2.1: the draft model
+# uses the target's LM head and expands its beam search by the softmax output; section 3.1: the
+# draft stays in fp16 because LM head and softmax are its bottleneck and are not quantisable)
+
+
+def lm_head_topk(x, W, top_k: int):
+    """x fp16 [M, K] (draft hidden states), W fp16 [V, K] (LM-head weight, one row per token).
+    logits[m, v] = sum_k x[m, k] W[v, k];  logprob = logits - log(sum_v exp(logits)), per row.
+    Returns (logits64 [M, V], idx int64 [M, top_k], logprob64 [M, top_k]): per row the top_k tokens by
+    logit, largest first, equal logits in ascending token order, with their log-probabilities."""
+    x64 = np.asarray(x).astype(np.float64)
+    W64 = np.asarray(W).astype(np.float64)
+    logits = x64 @ W64.T
+    mx = logits.max(axis=1, keepdims=True)
+    lse = mx[:, 0] + np.log(np.exp(logits - mx).sum(axis=1))
+    M, V = logits.shape
+    idx = np.empty((M, top_k), dtype=np.int64)
+    for m in range(M):
+        order = sorted(range(V), key=lambda v: (-logits[m, v], v))   # plain definition of the order
+        idx[m] = order[:top_k]
+    lp = np.take_along_axis(logits, idx, axis=1) - lse[:, None]
+    return logits, idx, lp

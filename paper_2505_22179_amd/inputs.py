@@ -240,3 +240,13 @@ def tree_positions(parent: np.ndarray, P: int) -> np.ndarray:
     for i in range(1, n):
         depth[i] = depth[int(parent[i])] + 1
     return (P + depth).astype(np.int32)
+
+
+def make_lm_head(seed: int, M: int, K: int, V: int, w_std: float = 0.02):
+    """Draft hidden states x fp16 [M, K] ~ N(0, 1) and an LM-head weight W fp16 [V, K] ~ N(0, w_std^2)
+    (stand-ins for an EAGLE-2 draft layer's output and Llama-3's output embedding): logits of spread
+    sqrt(K) * w_std."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((M, K), dtype=np.float32).astype(np.float16)
+    W = (rng.standard_normal((V, K), dtype=np.float32) * np.float32(w_std)).astype(np.float16)
+    return x, W
