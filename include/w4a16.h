@@ -198,6 +198,34 @@ int rms_norm(const void *x, const void *gamma, void *y, int M, int K, float eps,
 int rope_append(const void *qkv, const int32_t *pos, const float *cos_table, const float *sin_table, int n_pos,
                 void *q, void *k_cache, void *v_cache, int M, int P, int Hq, int Hkv, int D, void *stream);
 
+/* Size in bytes of the packed LM-head weight for a V-token vocabulary and hidden size K (the
+ * vocabulary is padded to a multiple of 16 inside the buffer).  0 if the shape is not supported. */
+size_t lm_head_packed_bytes(int V, int K);
+
+/* Re-lay an fp16 LM-head weight W [V, K] (row-major, one row per token) into the streaming layout
+ * lm_head_topk reads: 16-token tiles whose 16x32 blocks are stored in matrix-instruction operand
+ * order, one contiguous run per tile.  Offline, once per weight.  Requires K % 128 == 0;
+ * `packed` receives lm_head_packed_bytes(V, K) bytes. */
+int lm_head_pack(const void *W, void *packed, int V, int K, void *stream);
+
+/* Scratch lm_head_topk needs for these sizes (per-chunk softmax statistics and top-k candidates). */
+size_t lm_head_workspace_bytes(int M, int V, int K, int top_k);
+
+/* Draft-side language-model head with log-softmax and top-k (paper section 2.1: the draft model uses
+ * the target's LM head and grows its beam-search tree from the softmax output; section 3.1: the draft
+ * stays in fp16 because this head and its softmax dominate drafting and cannot be quantised).
+ *   x        fp16 [M, K]   draft hidden states, 1 <= M <= 16
+ *   packed   the LM-head weight W fp16 [V, K] as laid out by lm_head_pack
+ *   logits   fp32 [M, V]   out: logits[m, v] = sum_k x[m, k] W[v, k], fp32 accumulation
+ *   top_idx  int32 [M, top_k], top_logprob fp32 [M, top_k]   out: per row the top_k tokens by logit,
+ *            largest first, equal logits in ascending token order, with
+ *            logprob = logit - log(sum_v exp(logit[m, v]))
+ * x, packed, logits, workspace 16-byte aligned; top_idx, top_logprob 4-byte aligned.  Requires
+ * K % 128 == 0, 1 <= top_k <= min(V, 64), V <= 262144 and ceil(V / 512) * top_k <= 8192.  `workspace` holds
+ * lm_head_workspace_bytes(M, V, K, top_k) bytes and needs no initialisation.  Deterministic. */
+int lm_head_topk(const void *x, const void *packed, int M, int V, int K, int top_k, float *logits, int32_t *top_idx,
+                 float *top_logprob, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

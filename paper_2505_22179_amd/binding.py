@@ -16,7 +16,8 @@ EXPORTS = (
     "w4a16_version", "w4a16_strerror", "w4a16_set_param", "w4a16_get_param", "w4a16_packed_bytes",
     "w4a16_workspace_bytes", "w4a16_workspace_init", "w4a16_pack", "w4a16_unpack", "w4a16_dequant",
     "w4a16_gemm", "w4a16_gemm_fused", "w4a16_pack_gate_up", "w4a16_read_probe", "tree_verify_attn_workspace_bytes",
-    "tree_verify_attn", "tree_accept", "rms_norm", "rope_append",
+    "tree_verify_attn", "tree_accept", "rms_norm", "rope_append", "lm_head_workspace_bytes", "lm_head_topk",
+    "lm_head_packed_bytes", "lm_head_pack",
 )
 
 EPI_NONE, EPI_RESIDUAL, EPI_SILU_MUL = 0, 1, 2
@@ -61,6 +62,12 @@ def load() -> ctypes.CDLL:
     L.w4a16_pack_gate_up.argtypes = [vp, vp, vp, vp, i, i, i, vp]
     L.rms_norm.argtypes = [vp, vp, vp, i, i, ctypes.c_float, vp]
     L.rope_append.argtypes = [vp, vp, vp, vp, i, vp, vp, vp, i, i, i, i, i, vp]
+    L.lm_head_packed_bytes.restype = sz
+    L.lm_head_packed_bytes.argtypes = [i, i]
+    L.lm_head_pack.argtypes = [vp, vp, i, i, vp]
+    L.lm_head_workspace_bytes.restype = sz
+    L.lm_head_workspace_bytes.argtypes = [i, i, i, i]
+    L.lm_head_topk.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -154,6 +161,24 @@ def rope_append(qkv, pos, cos_table, sin_table, n_pos: int, q, k_cache, v_cache,
                 D: int) -> None:
     _check(load().rope_append(_ptr(qkv), _ptr(pos), _ptr(cos_table), _ptr(sin_table), n_pos, _ptr(q), _ptr(k_cache),
                               _ptr(v_cache), M, P, Hq, Hkv, D, _stream()), "rope_append")
+
+
+def lm_head_workspace_bytes(M: int, V: int, K: int, top_k: int) -> int:
+    return int(load().lm_head_workspace_bytes(M, V, K, top_k))
+
+
+def lm_head_packed_bytes(V: int, K: int) -> int:
+    return int(load().lm_head_packed_bytes(V, K))
+
+
+def lm_head_pack(W, packed, V: int, K: int) -> None:
+    _check(load().lm_head_pack(_ptr(W), _ptr(packed), V, K, _stream()), "lm_head_pack")
+
+
+def lm_head_topk(x, packed, M: int, V: int, K: int, top_k: int, logits, top_idx, top_logprob, workspace) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().lm_head_topk(_ptr(x), _ptr(packed), M, V, K, top_k, _ptr(logits), _ptr(top_idx), _ptr(top_logprob),
+                               _ptr(workspace), nbytes, _stream()), "lm_head_topk")
 
 
 def w4a16_read_probe(buf, nbytes: int, sink) -> None:

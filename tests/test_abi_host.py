@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared():
     text = open(os.path.join(ROOT, "include", "w4a16.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b((?:w4a16|tree|rms|rope)_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:w4a16|tree|rms|rope|lm_head)_\w+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported():
@@ -148,3 +148,29 @@ def test_layer_glue_validation_happens_before_any_gpu_call():
     assert r(a, None, a, a, 64, a, a, a, 4, 10, 8, 2, 128, None) == ENULL
     assert r(a, a + 2, a, a, 64, a, a, a, 4, 10, 8, 2, 128, None) == EALIGN
     assert r(a, a, a, a, 64, a + 8, a, a, 4, 10, 8, 2, 128, None) == EALIGN
+
+
+def test_lm_head_validation_happens_before_any_gpu_call():
+    lib = B.load()
+    a = 0x1000
+    EINVAL, ENULL, EALIGN, EUNSUP, EWS = -1, -2, -3, -4, -5
+    f = lib.lm_head_topk
+    assert f(a, a, 0, 1000, 4096, 10, a, a, a, a, 1 << 30, None) == EINVAL        # M = 0
+    assert f(a, a, 17, 1000, 4096, 10, a, a, a, a, 1 << 30, None) == EUNSUP       # more than one row tile
+    assert f(a, a, 4, 1000, 4000, 10, a, a, a, a, 1 << 30, None) == EINVAL        # K % 128
+    assert f(a, a, 4, 8, 4096, 10, a, a, a, a, 1 << 30, None) == EINVAL           # top_k > V
+    assert f(a, a, 4, 1000, 4096, 65, a, a, a, a, 1 << 30, None) == EUNSUP
+    assert f(a, a, 4, 128256, 4096, 64, a, a, a, a, 1 << 30, None) == EUNSUP      # too many candidates to merge
+    assert f(a, a, 4, 300000, 4096, 4, a, a, a, a, 1 << 30, None) == EUNSUP        # too many chunks
+    assert f(a, None, 4, 1000, 4096, 10, a, a, a, a, 1 << 30, None) == ENULL
+    assert f(a, a, 4, 1000, 4096, 10, a, a + 2, a, a, 1 << 30, None) == EALIGN
+    assert f(a, a, 4, 1000, 4096, 10, a, a, a, None, 0, None) == EWS
+    assert f(a, a, 4, 1000, 4096, 10, a, a, a, a, 16, None) == EWS
+    assert B.lm_head_packed_bytes(128256, 4096) == 128256 * 4096 * 2
+    assert B.lm_head_packed_bytes(1001, 128) == 1008 * 128 * 2           # padded to whole 16-token tiles
+    assert B.lm_head_packed_bytes(1000, 100) == 0
+    assert lib.lm_head_pack(a, a, 1000, 100, None) == EINVAL
+    assert lib.lm_head_pack(None, a, 1000, 128, None) == ENULL
+    assert lib.lm_head_pack(a, a + 4, 1000, 128, None) == EALIGN
+    assert B.lm_head_workspace_bytes(10, 128256, 4096, 10) > 0
+    assert B.lm_head_workspace_bytes(17, 128256, 4096, 10) == 0
