@@ -178,6 +178,41 @@ def eq1_projection(layer_ms: dict, read_GBps: float) -> dict:
     return out
 
 
+def lm_head_leg(args, use_graph: bool) -> dict:
+    """Draft side: fp16 LM head of the Llama-3 vocabulary + log-softmax + top-10, for the draft models of
+    the 8B (K = 4096) and 70B (K = 8192) targets; each weight (1.05 / 2.1 GB) exceeds the last-level cache."""
+    lm = {}
+    V, top_k = 128256, 10
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    for K in (4096, 8192):
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(4096 + K)
+        Ws = []
+        for _ in range(2):
+            raw = (torch.randn((V, K), device="cuda", generator=gen) * 0.02).to(torch.float16)
+            pk = torch.empty(B.lm_head_packed_bytes(V, K), dtype=torch.uint8, device="cuda")
+            B.lm_head_pack(raw, pk, V, K)
+            Ws.append(pk)
+            del raw
+        nbytes = V * K * 2
+        steps, warm = min(args.steps, 60), min(args.warmup, 6)
+        ms_read = time_steps(lambda c: B.w4a16_read_probe(Ws[c], nbytes, sink), steps, warm, use_graph, 2)
+        lm[str(K)] = {"weight_bytes": nbytes, "plain_read_us": ms_read * 1e3, "plain_read_GBps": nbytes / ms_read / 1e6}
+        for M in (1, 10):
+            x = torch.randn((M, K), device="cuda", generator=gen).to(torch.float16)
+            logits = torch.empty((M, V), dtype=torch.float32, device="cuda")
+            ti = torch.empty((M, top_k), dtype=torch.int32, device="cuda")
+            tp = torch.empty((M, top_k), dtype=torch.float32, device="cuda")
+            lws = torch.empty(B.lm_head_workspace_bytes(M, V, K, top_k), dtype=torch.uint8, device="cuda")
+            ms = time_steps(lambda c: B.lm_head_topk(x, Ws[c], M, V, K, top_k, logits, ti, tp, lws), steps, warm, use_graph, 2)
+            lm[str(K)][f"M{M}"] = {"us": ms * 1e3, "weight_GBps": nbytes / ms / 1e6,
+                                   "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBPS}
+            log(f"LM head K={K} M={M}: {ms * 1e3:.1f} us  {nbytes / ms / 1e6:.0f} GB/s (plain read {ms_read * 1e3:.1f} us)")
+        del Ws
+        torch.cuda.empty_cache()
+    return lm
+
+
 def time_steps(fn, steps: int, warmup: int, use_graph: bool, copies: int):
     """fn(copy_index) enqueues one step.  Warm up, then time exactly `steps` steps between two
     events on the launch stream.  With graphs, `copies` consecutive steps form one HIP graph (so the
@@ -272,6 +307,7 @@ def main():
     ap.add_argument("--quick", action="store_true", help="headline only (used under the profiler)")
     ap.add_argument("--quick-m", type=int, default=1,
                     help="with --quick: run at this M instead of 1 (profiler runs at other token counts; not the headline)")
+    ap.add_argument("--lm-head-only", action="store_true", help="time only the draft-side LM head (profiler runs)")
     ap.add_argument("--decoder-layer-only", type=int, default=0, metavar="M",
                     help="time only the whole decoder layer at this M (profiler runs; prints that one figure)")
     args = ap.parse_args()
@@ -284,6 +320,9 @@ def main():
     dev = torch.cuda.get_device_name(0)
     log(f"device: {dev}")
 
+    if args.lm_head_only:
+        print(json.dumps({"metric": "draft-side fp16 LM head + top-10, V = 128256", "lm_head_topk_V128256": lm_head_leg(args, use_graph)}))
+        return
     big = Layer(I.LLAMA3_70B, args.copies, seed=70)
     log("70B layer packed")
     if args.decoder_layer_only:
@@ -383,36 +422,7 @@ def main():
         extra["eq1_projection_70b"] = eq1_projection(dl, plain["gate_up"]["GBps"])
         del big
         torch.cuda.empty_cache()
-        # draft side: fp16 LM head of the Llama-3 vocabulary + log-softmax + top-10, for the 8B (K = 4096) and
-        # 70B (K = 8192) targets' draft models; each weight (1.05 / 2.1 GB) is larger than the last-level cache
-        lm = {}
-        V, top_k = 128256, 10
-        for K in (4096, 8192):
-            gen = torch.Generator(device="cuda")
-            gen.manual_seed(4096 + K)
-            Ws = []
-            for _ in range(2):
-                raw = (torch.randn((V, K), device="cuda", generator=gen) * 0.02).to(torch.float16)
-                pk = torch.empty(B.lm_head_packed_bytes(V, K), dtype=torch.uint8, device="cuda")
-                B.lm_head_pack(raw, pk, V, K)
-                Ws.append(pk)
-                del raw
-            nbytes = V * K * 2
-            ms_read = time_steps(lambda c: B.w4a16_read_probe(Ws[c], nbytes, sink), 60, 6, use_graph, 2)
-            lm[str(K)] = {"weight_bytes": nbytes, "plain_read_us": ms_read * 1e3, "plain_read_GBps": nbytes / ms_read / 1e6}
-            for M in (1, 10):
-                x = torch.randn((M, K), device="cuda", generator=gen).to(torch.float16)
-                logits = torch.empty((M, V), dtype=torch.float32, device="cuda")
-                ti = torch.empty((M, top_k), dtype=torch.int32, device="cuda")
-                tp = torch.empty((M, top_k), dtype=torch.float32, device="cuda")
-                lws = torch.empty(B.lm_head_workspace_bytes(M, V, K, top_k), dtype=torch.uint8, device="cuda")
-                ms = time_steps(lambda c: B.lm_head_topk(x, Ws[c], M, V, K, top_k, logits, ti, tp, lws), 60, 6, use_graph, 2)
-                lm[str(K)][f"M{M}"] = {"us": ms * 1e3, "weight_GBps": nbytes / ms / 1e6,
-                                       "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBPS}
-                log(f"LM head K={K} M={M}: {ms * 1e3:.1f} us  {nbytes / ms / 1e6:.0f} GB/s (plain read {ms_read * 1e3:.1f} us)")
-            del Ws
-            torch.cuda.empty_cache()
-        extra["lm_head_topk_V128256"] = lm
+        extra["lm_head_topk_V128256"] = lm_head_leg(args, use_graph)
         small = Layer(I.LLAMA3_8B, 6, seed=8)   # 6 x 113 MB: never re-read within 512 MB
         s8 = {}
         for M in I.M_SWEEP_8B:
