@@ -1120,6 +1120,9 @@ struct Plan {
                  // K / 128 == S * nw * ng exactly)
 };
 
+// measured rows are keyed by a row bucket: 0 for M <= 8 (plain decoding and sequence verification), else
+// the number of 16-row tiles (1 = M 9..16, 2 = 17..32, ...)
+static int row_bucket(int M) { return M <= 8 ? 0 : (M + 15) / 16; }
 struct TunedRow { int N, K, mt, tw, nw, depth, S, fused, ks; };
 static const TunedRow kTuned[] = {
 #include "tuned_plans.inc"
@@ -1209,7 +1212,7 @@ static Plan choose_plan(int M, int N, int K)
                 return pl;
             }
         for (const TunedRow &r : kTuned)
-            if (r.N == N && r.K == K && r.mt == mt && variant_exists(mt, r.tw, r.nw, r.depth, r.ks))
+            if (r.N == N && r.K == K && r.mt == row_bucket(M) && variant_exists(mt, r.tw, r.nw, r.depth, r.ks))
                 best = {r.tw, r.nw, r.depth, r.S, r.fused, r.ks, 0};
     }
     if (p.k_sets > 0) {   // forced: the high-occupancy column-split variant

@@ -1,6 +1,6 @@
 """Launch-shape tuner for w4a16_gemm (needs a GPU).
 
-For every (layer shape, M bucket of 16 rows) it times each compiled kernel variant -- tiles per
+For every (layer shape, row bucket: M <= 8, 9..16, 17..32, ...) it times each compiled kernel variant -- tiles per
 wavefront, wavefronts per workgroup, prefetch depth, K splits, fused or two-kernel reduction --
 through the library's ablation knobs (for M > 16 also the high-occupancy column-split variant and its K sets), on weights rotated through more than 512 MB so the
 last-level cache never serves them, and writes the winners as rows of csrc/tuned_plans.inc.  The
@@ -116,16 +116,19 @@ def tune_shape(name: str, K: int, N: int, Ms, ws, log):
     wb = weight_bytes(K, N)
     copies = max(3, int(700e6 // wb) + 1)
     packs = make_packed(K, N, copies)
-    per_bucket = collections.defaultdict(list)   # mt -> list of {plan: us}
+    per_bucket = collections.defaultdict(list)   # row bucket (0: M <= 8, else 16-row tiles) -> list of {plan: us}
     flat_runs = []                               # M <= FLAT_MAX_M: ({flat plan: us}, best non-flat us)
     for M in Ms:
         x = torch.randn((M, K), device="cuda").to(torch.float16)
         y = torch.empty((M, N), dtype=torch.float16, device="cuda")
         res = {}
+        # the many-row kernels are bound by instruction issue and follow the clock, which sags under
+        # sustained load: time them over a longer stretch than the memory-bound few-row kernels
+        min_us = 1500.0 if M <= 16 else 12000.0
         for plan in candidates(N, K, M):
             set_knobs(plan)
             try:
-                res[plan] = time_graph(lambda c: B.w4a16_gemm(x, packs[c], y, M, N, K, G, ws), copies)
+                res[plan] = time_graph(lambda c: B.w4a16_gemm(x, packs[c], y, M, N, K, G, ws), copies, min_us)
             except B.W4A16Error:
                 continue   # variant not compiled for this M
         best = min(res.values())
@@ -144,7 +147,7 @@ def tune_shape(name: str, K: int, N: int, Ms, ws, log):
         top = sorted(res.items(), key=lambda kv: kv[1])[:4]
         log(f"{name} K={K} N={N} M={M}: ideal {wb / 8e6:.1f} us | " +
             " ".join(f"[tw{p[0]} {'ks%d' % p[5] if p[5] else 'nw%d' % p[1]} d{p[2]} S{p[3]}{'f' if p[4] else 'k'} {us:.1f}us]" for p, us in top))
-        per_bucket[(M + 15) // 16].append({p: us / best for p, us in res.items()})
+        per_bucket[0 if M <= 8 else (M + 15) // 16].append({p: us / best for p, us in res.items()})
     set_knobs((0, 0, 0, 0, 2, 0, 0))
     rows = []
     for mt, runs in sorted(per_bucket.items()):
@@ -172,7 +175,7 @@ def main() -> None:
     ap.add_argument("--out", required=True)
     ap.add_argument("--flat-out", default=None, help="rows for csrc/tuned_flat.inc (default: <out>.flat)")
     ap.add_argument("--shapes", default="70b,8b")
-    ap.add_argument("--M", default="1,4,8,16,32,48,64")
+    ap.add_argument("--M", default="1,4,8,12,16,32,48,64")
     args = ap.parse_args()
     Ms = [int(m) for m in args.M.split(",")]
     ws = B.new_workspace(1 << 30)
@@ -188,7 +191,7 @@ def main() -> None:
             flat_rows += f
     with open(args.out, "w") as f:
         f.write("// Tuned launch shapes, written by `python -m paper_2505_22179_amd.tune` on an MI355X.\n")
-        f.write("// {N, K, row tiles, tiles per wavefront, wavefronts per workgroup, prefetch depth, K splits, fused reduce, K sets}\n")
+        f.write("// {N, K, row bucket (0: M <= 8, else 16-row tiles), tiles per wavefront, wavefronts per workgroup, prefetch depth, K splits, fused reduce, K sets}\n")
         for r in rows:
             f.write("{" + ", ".join(str(v) for v in r) + "},\n")
     flat_out = args.flat_out or args.out + ".flat"
