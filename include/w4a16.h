@@ -54,7 +54,9 @@ const char *w4a16_strerror(int code);
  * heuristic, else 1, 2 or 4 groups of codes in flight per wavefront), "k_sets" (0 = heuristic, else
  * 1, 2 or 3: forces the M > 16 variant whose workgroup has 4 * k_sets wavefronts, four column
  * quarters times k_sets interleaved sets of quantisation groups; waves_per_wg is then ignored and
- * fused_reduce = 2 means the second kernel), "flat_groups" (0 = heuristic, else 4, 7 or 8: forces the M <= 4 variant in which a
+ * fused_reduce = 2 means the second kernel), "even_split" (with k_sets: 1 deals the (column unit, group)
+ * pairs in equal runs to one workgroup per compute unit instead of splitting K into split_k equal parts
+ * per unit; the runs that share a unit are summed by the last to arrive), "flat_groups" (0 = heuristic, else 4, 7 or 8: forces the M <= 4 variant in which a
  * wavefront owns that many quantisation groups and requests all of their weights up front; needs
  * K / 128 == split_k * waves_per_wg * flat_groups); a combination that is not compiled, or that
  * does not fit the shape, makes w4a16_gemm return W4A16_EUNSUP,

@@ -869,14 +869,19 @@ __device__ __forceinline__ void compute_group_lean(const u32x4 (&a)[MT][4], Quan
 // colq and on every KS-th quantisation group starting at kset, so KS wavefronts share each SIMD.
 // Per step the workgroup parks the x fragments of KS consecutive groups in LDS (operand order,
 // double-buffered, one barrier per step); the KS partial sums of a column meet in LDS at the end.
+// One (column unit, group range) segment of the kernel below: groups g_begin .. g_end-1 of workgroup
+// unit wg_unit.  nslots == 1: the segment is the unit's whole K and its sums are stored.  Otherwise it
+// is contributor `slot` of `nslots` (ascending group ranges) and its sums go to the workspace, slot
+// stride `sstride` per wavefront unit; in last-arriver mode (fused) the contributor that takes the
+// last ticket adds all of them in slot order and stores.  Every wavefront of the workgroup passes the
+// same barriers whatever it returns through.
 template <int MT, int TW, int KS, int DEPTH>
-__global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
-    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, const Out y,
-    float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused,
-    int gq, int grem)
+__device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed,
+                                           const Out &y, float *__restrict__ partial, uint32_t *__restrict__ tickets,
+                                           float4v *lds4, uint32_t &ticket_sh, int M, int N, int K, int groups,
+                                           int wg_unit, int g_begin, int g_end, int nslots, int slot, int sstride,
+                                           int fused)
 {
-    extern __shared__ float4v lds4[];
-    __shared__ uint32_t ticket_sh;
     constexpr int R = 4 * TW * MT;                 // accumulator registers per lane
     constexpr int E4 = R * 16;                     // float4 results per wavefront
     constexpr int kBufQuads = KS * MT * 4 * 64;    // 16-byte fragments of one step's x tiles
@@ -886,14 +891,12 @@ __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int colq = wave & 3, kset = wave >> 2;
     const int r = lane >> 4, c = lane & 15;
-    const int wg_unit = blockIdx.y, ks = blockIdx.x;   // grid = (S, workgroup units)
     const int unit = wg_unit * 4 + colq;
     const int tiles_total = pad_cols(N) / 16;
     const bool active = unit * TW < tiles_total;   // a ragged last workgroup has idle column quarters
     const int tile_first = active ? unit * TW : 0;
     const int nb = tile_first >> 3, t0 = tile_first & 7;
-    const KRange kr = k_range(ks, gq, grem);
-    const int g_begin = kr.begin, g_end = kr.end;
+    const int S = nslots, ks = slot;
     const int n = g_end - g_begin;
     const int steps = (n + KS - 1) / KS;           // workgroup-uniform
     const int full = n / KS;                       // steps in which every k set has a group
@@ -1022,8 +1025,8 @@ __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
     // K split across workgroups: this workgroup's sums go to the workspace.  Two-kernel mode ends
     // here; otherwise they are published at device scope and the last workgroup of the column unit
     // to take a ticket adds the S partials in split order and stores the result.
-    float *mine_part = partial + ((size_t)unit * S + ks) * E4 * 4;
-    const PartialBuffer all = partial_buffer(partial + (size_t)unit * S * E4 * 4);
+    float *mine_part = partial + ((size_t)unit * sstride + ks) * E4 * 4;
+    const PartialBuffer all = partial_buffer(partial + (size_t)unit * sstride * E4 * 4);
     if (active) {
         for (int q = kset; q < E4 / 64; q += KS) {
             const int e4 = lane + 64 * q;
@@ -1062,6 +1065,41 @@ __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
         float4v v = (float4v){0.f, 0.f, 0.f, 0.f};
         for (int s = 0; s < S; ++s) v += load_partial(all, s * E4 + e4);
         store_quad<MT>(y, v, e4, first_col, M, N);
+    }
+}
+
+// Two ways to share the work.  Classic (per == 0): grid = (S, workgroup units), workgroup (ks, u) takes
+// K split ks of unit u.  Even split (per > 0): the (unit, group) pairs, unit-major, are dealt out in
+// runs of `per` to a 1-D grid, so every workgroup gets the same number of groups even when the units
+// alone do not fill the chip; a run that crosses a unit boundary is handled as two segments, and a
+// unit shared by several runs is summed by its last arriver.
+template <int MT, int TW, int KS, int DEPTH>
+__global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
+    const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, const Out y,
+    float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused,
+    int gq, int grem, int per, int wg_units)
+{
+    extern __shared__ float4v lds4[];
+    __shared__ uint32_t ticket_sh;
+    if (per == 0) {
+        const KRange kr = k_range(blockIdx.x, gq, grem);
+        cs_segment<MT, TW, KS, DEPTH>(x, packed, y, partial, tickets, lds4, ticket_sh, M, N, K, groups, blockIdx.y,
+                                      kr.begin, kr.end, S, blockIdx.x, S, fused);
+        return;
+    }
+    const int total = wg_units * groups;
+    int item = blockIdx.x * per;
+    const int end = min(item + per, total);
+    bool again = false;
+    while (item < end) {   // uniform over the workgroup
+        const int u = item / groups, g0 = item - u * groups;
+        const int g1 = min(groups, g0 + (end - item));
+        const int first = (u * groups) / per, last = ((u + 1) * groups - 1) / per;   // runs that touch unit u
+        if (again) __syncthreads();   // the previous segment's epilogue has left LDS
+        cs_segment<MT, TW, KS, DEPTH>(x, packed, y, partial, tickets, lds4, ticket_sh, M, N, K, groups, u, g0, g1,
+                                      last - first + 1, (int)blockIdx.x - first, S, 1);
+        item += g1 - g0;
+        again = true;
     }
 }
 
@@ -1219,6 +1257,7 @@ static Plan choose_plan(int M, int N, int K)
         const int tw = p.tiles_per_wave ? p.tiles_per_wave : 4, depth = p.prefetch_depth ? p.prefetch_depth : 2;
         int s = p.split_k > 0 ? p.split_k : 1;
         if (s > groups) s = groups;
+        if (p.even_split) s = 0;
         if (variant_exists(mt, tw, 0, depth, p.k_sets)) best = {tw, 0, depth, s, p.fused_reduce == 1, p.k_sets, 0};
         return best;
     }
@@ -1264,10 +1303,30 @@ static Plan choose_plan(int M, int N, int K)
     return best;   // tw == 0: the knobs name a variant that is not compiled
 }
 
-static size_t partial_bytes(int mt, int nblocks, const Plan &pl)
+// Even split of the column-split kernel's (workgroup unit, group) pairs over the compute units:
+// run length, number of runs (= workgroups) and the largest number of runs that touch one unit.
+constexpr int kComputeUnits = 256;
+struct EvenSplit { int per, runs, max_slots; };
+static EvenSplit even_split(int wg_units, int groups)
+{
+    const long long total = (long long)wg_units * groups;
+    EvenSplit e;
+    e.per = (int)((total + kComputeUnits - 1) / kComputeUnits);
+    e.runs = (int)((total + e.per - 1) / e.per);
+    e.max_slots = 1;
+    for (int u = 0; u < wg_units; ++u) {
+        const int first = (int)(((long long)u * groups) / e.per), last = (int)((((long long)u + 1) * groups - 1) / e.per);
+        if (last - first + 1 > e.max_slots) e.max_slots = last - first + 1;
+    }
+    return e;
+}
+
+// plan.S == 0 asks for that even split (column-split kernels only); otherwise S is the number of K splits
+static size_t partial_bytes(int mt, int nblocks, const Plan &pl, int groups)
 {
     const size_t units = (size_t)nblocks * kTiles / pl.tw;
-    return pl.S > 1 ? units * pl.S * (4 * pl.tw * mt * 64) * sizeof(float) : 0;
+    const int slots = pl.S == 0 ? even_split((int)((units + 3) / 4), groups).max_slots : pl.S;
+    return slots > 1 ? units * slots * (4 * pl.tw * mt * 64) * sizeof(float) : 0;
 }
 
 template <int MT, int TW, int NW, int DEPTH>
@@ -1335,9 +1394,16 @@ static int launch_cs(const void *x, const void *packed, const Out &y, int M, int
     const int groups = K / kGroup, units = pad_cols(N) / 16 / TW;
     uint32_t *tickets = reinterpret_cast<uint32_t *>(workspace);
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
+    if (S == 0) {   // even split of (unit, group) pairs over the compute units, summed by last arrivers
+        const EvenSplit e = even_split((units + 3) / 4, groups);
+        hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH>), dim3((unsigned)e.runs), dim3(256 * KS), lds_bytes, stream,
+                           (const _Float16 *)x, (const uint8_t *)packed, y, partial, tickets, M, N, K, groups,
+                           e.max_slots, 1, 0, 0, e.per, (units + 3) / 4);
+        return launch_status();
+    }
     hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH>), dim3((unsigned)S, (unsigned)((units + 3) / 4)), dim3(256 * KS),
                        lds_bytes, stream, (const _Float16 *)x, (const uint8_t *)packed, y, partial, tickets, M, N, K,
-                       groups, S, fused, groups / S, groups % S);
+                       groups, S, fused, groups / S, groups % S, 0, 0);
     if (S > 1 && !fused)
         hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
                            (const float *)partial, y, M, N, S);
@@ -1417,7 +1483,7 @@ size_t w4a16_workspace_bytes(int M_max, int N, int K, int G)
     size_t need = 0;
     for (int m = 1; m <= M_max; ++m) {   // the plan depends on M only through a few thresholds: cheap enough
         const Plan pl = choose_plan(m, N, K);
-        size_t b = pl.tw ? partial_bytes((m + 15) / 16, nblocks, pl) : 0;
+        size_t b = pl.tw ? partial_bytes((m + 15) / 16, nblocks, pl, K / kGroup) : 0;
         if (b > need) need = b;
     }
     return kTicketBytes + need;
@@ -1436,10 +1502,11 @@ static int gemm_entry(const void *x, const void *packed, const Out &out, int M, 
     const int mt = (M + 15) / 16;
     Plan pl = choose_plan(M, N, K);
     if (pl.tw == 0) return W4A16_EUNSUP;
-    if (pl.S > 1 && nblocks * kTiles / pl.tw > kMaxTickets) pl.S = 1;
-    if (pl.S > 1) {
-        if (!workspace) return W4A16_EWORKSPACE;
-        if (workspace_bytes < kTicketBytes + partial_bytes(mt, nblocks, pl)) return W4A16_EWORKSPACE;
+    if (pl.S != 1 && nblocks * kTiles / pl.tw > kMaxTickets) pl.S = 1;
+    if (pl.S != 1) {
+        const size_t need = partial_bytes(mt, nblocks, pl, K / kGroup);
+        if (need > 0 && !workspace) return W4A16_EWORKSPACE;
+        if (need > 0 && workspace_bytes < kTicketBytes + need) return W4A16_EWORKSPACE;
     }
     return dispatch(mt, pl, x, packed, out, M, N, K, workspace, (hipStream_t)stream);
 }

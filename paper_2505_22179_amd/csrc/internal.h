@@ -33,6 +33,7 @@ struct Params {
     int waves_per_wg = 0;     // 0 = heuristic, else 4, 8 or 16
     int prefetch_depth = 0;   // 0 = heuristic, else 1, 2, 3 or 4
     int k_sets = 0;           // 0 = heuristic, else 1..3: force the high-occupancy column-split kernel
+    int even_split = 0;       // 1 with k_sets: deal (unit, group) pairs evenly to one workgroup per compute unit
     int flat_groups = 0;      // 0 = heuristic, else 4, 7 or 8: force the all-loads-up-front kernel (M <= 4)
 };
 Params &params();

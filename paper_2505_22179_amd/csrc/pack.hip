@@ -200,6 +200,7 @@ static int *param_slot(const char *name)
     if (!strcmp(name, "waves_per_wg")) return &p.waves_per_wg;
     if (!strcmp(name, "prefetch_depth")) return &p.prefetch_depth;
     if (!strcmp(name, "k_sets")) return &p.k_sets;
+    if (!strcmp(name, "even_split")) return &p.even_split;
     if (!strcmp(name, "flat_groups")) return &p.flat_groups;
     return nullptr;
 }

@@ -23,6 +23,8 @@ from . import inputs as I
 
 G = 128
 KNOBS = ("tiles_per_wave", "waves_per_wg", "prefetch_depth", "split_k", "fused_reduce", "k_sets", "flat_groups")
+# a plan's split_k field of 0 together with k_sets > 0 means the even split of the column-split kernel
+# (not among the candidates: it lost to the plain K split on every Llama-3 shape, by 3 to 60 %)
 FLAT_MAX_M = 4   # the all-loads-up-front variant stages at most this many rows
 
 
@@ -76,6 +78,7 @@ def time_graph(fn, copies: int, min_us: float = 1500.0) -> float:
 def set_knobs(values) -> None:
     for k, v in zip(KNOBS, values):
         B.w4a16_set_param(k, v)
+    B.w4a16_set_param("even_split", 1 if (values[5] > 0 and values[3] == 0) else 0)
 
 
 def candidates(N: int, K: int, M: int):

@@ -24,7 +24,7 @@ def big_ws():
 @pytest.fixture(autouse=True)
 def _reset_knobs():
     yield
-    for k in ("split_k", "tiles_per_wave", "waves_per_wg", "prefetch_depth", "k_sets", "flat_groups"):
+    for k in ("split_k", "tiles_per_wave", "waves_per_wg", "prefetch_depth", "k_sets", "flat_groups", "even_split"):
         B.w4a16_set_param(k, 0)
     B.w4a16_set_param("fused_reduce", 2)
 
@@ -125,6 +125,11 @@ def test_parity_high_occupancy(M, K, N, big_ws):
             B.w4a16_set_param("fused_reduce", fused)
             check_gemm(run_gemm(inp, packed, big_ws), y32, f"M={M} K={K} N={N} (tw, ks, depth, split)={variant} fused={fused}")
             assert np.array_equal(run_gemm(ex, ex_packed, big_ws).view(np.uint16), ex16.view(np.uint16)), (variant, fused)
+        # (unit, group) pairs dealt evenly to one workgroup per compute unit: runs cross unit boundaries
+        B.w4a16_set_param("even_split", 1)
+        check_gemm(run_gemm(inp, packed, big_ws), y32, f"M={M} K={K} N={N} (tw, ks, depth)={variant[:3]} even split")
+        assert np.array_equal(run_gemm(ex, ex_packed, big_ws).view(np.uint16), ex16.view(np.uint16)), (variant, "even split")
+        B.w4a16_set_param("even_split", 0)
 
 
 # all-loads-up-front kernel, M <= 4 only: (tiles_per_wave, waves_per_wg, flat_groups, split_k, fused_reduce);
@@ -157,6 +162,24 @@ def test_parity_flat(M, N, big_ws):
     with pytest.raises(B.W4A16Error) as e:
         run_gemm(inp, B.pack_from_numpy(inp), big_ws)
     assert e.value.code == -4
+
+
+@pytest.mark.parametrize("M,K,N", [(64, 8192, 7168), (33, 4096, 14336 + 128), (48, 1024, 57344)])
+def test_parity_even_split_many_units(M, K, N, big_ws):
+    """more workgroup units than compute units, or not a multiple of them: every run crosses a unit
+    boundary somewhere, units have one, two or three contributors"""
+    print(f"gemm parity (even split) M={M} K={K} N={N}", flush=True)
+    inp = I.make_linear(6400 + M + K + N, M, K, N)
+    packed = B.pack_from_numpy(inp)
+    y32, _, _ = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, 128, want64=False)
+    for tw, ks, depth in ((4, 2, 1), (2, 2, 1), (4, 1, 2)):
+        if tw == 4 and ks == 2 and M > 32 and depth == 2:
+            continue
+        set_cs_variant(tw, ks, depth, 0)
+        B.w4a16_set_param("even_split", 1)
+        first = run_gemm(inp, packed, big_ws)
+        check_gemm(first, y32, f"M={M} K={K} N={N} even split (tw, ks, depth)={(tw, ks, depth)}")
+        assert np.array_equal(run_gemm(inp, packed, big_ws).view(np.uint16), first.view(np.uint16)), "not deterministic"
 
 
 def test_uncompiled_variant_is_reported():

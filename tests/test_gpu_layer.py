@@ -30,14 +30,14 @@ def big_ws():
 @pytest.fixture(autouse=True)
 def _reset_knobs():
     yield
-    for k in ("split_k", "tiles_per_wave", "waves_per_wg", "prefetch_depth", "k_sets", "flat_groups"):
+    for k in ("split_k", "tiles_per_wave", "waves_per_wg", "prefetch_depth", "k_sets", "flat_groups", "even_split"):
         B.w4a16_set_param(k, 0)
     B.w4a16_set_param("fused_reduce", 2)
 
 
-def set_knobs(tw=0, nw=0, depth=0, split=0, fused=2, ks=0, ng=0):
+def set_knobs(tw=0, nw=0, depth=0, split=0, fused=2, ks=0, ng=0, even=0):
     for k, v in (("tiles_per_wave", tw), ("waves_per_wg", nw), ("prefetch_depth", depth), ("split_k", split),
-                 ("fused_reduce", fused), ("k_sets", ks), ("flat_groups", ng)):
+                 ("fused_reduce", fused), ("k_sets", ks), ("flat_groups", ng), ("even_split", even)):
         B.w4a16_set_param(k, v)
 
 
@@ -89,7 +89,8 @@ def kernel_families(M):
     if M > 16:
         fam += [("column split S=1", dict(tw=4, nw=1, depth=1, split=1)), ("column split S=3", dict(tw=8, nw=1, depth=1, split=3)),
                 ("high occupancy S=1", dict(tw=2, ks=2, depth=2, split=1)), ("high occupancy S=2", dict(tw=4, ks=1, depth=2, split=2)),
-                ("high occupancy last-arriver", dict(tw=2, ks=2, depth=2, split=3, fused=1))]
+                ("high occupancy last-arriver", dict(tw=2, ks=2, depth=2, split=3, fused=1)),
+                ("high occupancy even split", dict(tw=2, ks=1, depth=2, even=1))]
     return fam
 
 
