@@ -355,3 +355,37 @@ def test_decoder_layer_chain(big_ws):
     rel = np.linalg.norm(h2.astype(np.float64) - o_h2) / np.linalg.norm(o_h2)
     print(f"decoder layer chain: relative Frobenius error of the layer output {rel:.3g}", flush=True)
     assert rel <= 3e-3
+
+
+# ---- full-size shapes in the launch configuration the benchmark times --------------------------------
+
+@pytest.mark.parametrize("M", [1, 8, 60])
+def test_fused_epilogues_full_size_sampled_columns(M):
+    """Llama-3-70B gate_up with the gate and down with the residual, default launch plans; the oracle
+    recomputes sampled output columns (all rows) from the same canonical tensors"""
+    from tests.parity import column_subproblem
+    print(f"fused epilogues full size M={M}", flush=True)
+    rng = np.random.default_rng(9900 + M)
+    # gate_up: output column n needs weight columns n (gate) and I + n (up)
+    _, K, N = I.LLAMA3_70B[2]
+    half = N // 2
+    inp = I.make_linear(I.seed_for(4, 2) + 50, M, K, N)
+    ws = B.new_workspace(B.w4a16_workspace_bytes(M, N, K))
+    got = run_fused(inp, B.pack_from_numpy(inp, gate_up=True), ws, B.EPI_SILU_MUL)
+    blocks = rng.choice(half // 8, size=16, replace=False)
+    cols = np.sort((blocks[:, None] * 8 + np.arange(8)[None, :]).ravel())
+    qw, sc, qz = column_subproblem(inp, np.concatenate([cols, half + cols]))
+    want, _ = R.w4a16_gemm_silu_mul(inp.x, qw, sc, qz)
+    check_gemm(got[:, cols], want, f"gate_up with gate, M={M}")
+    del inp, got
+    # down + residual, in place
+    _, K, N = I.LLAMA3_70B[3]
+    inp = I.make_linear(I.seed_for(4, 3) + 50, M, K, N)
+    res = I.make_hidden(9950 + M, M, N, 0)
+    ws = B.new_workspace(B.w4a16_workspace_bytes(M, N, K))
+    got = run_fused(inp, B.pack_from_numpy(inp), ws, B.EPI_RESIDUAL, res, in_place=True)
+    blocks = rng.choice(N // 8, size=32, replace=False)
+    cols = np.sort((blocks[:, None] * 8 + np.arange(8)[None, :]).ravel())
+    qw, sc, qz = column_subproblem(inp, cols)
+    want, _ = R.w4a16_gemm_residual(inp.x, qw, sc, qz, res[:, cols])
+    check_gemm(got[:, cols], want, f"down + residual, M={M}")
