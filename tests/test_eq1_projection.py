@@ -1,0 +1,29 @@
+"""Host check of the benchmark's Eq. (1) projection: the paper's speed-up model
+T_sd / T_t = (d T_d / T_t + T_v(n) / T_t) / tau(n, d) evaluated by hand on made-up layer times."""
+import bench
+
+
+def test_projection_formula_by_hand():
+    layer_ms = {1: 0.100, 24: 0.130, 32: 0.140, 40: 0.160, 48: 0.170}     # ms per decoder layer
+    read_GBps = 6000.0
+    out = bench.eq1_projection(layer_ms, read_GBps)
+    H, V = 8192, 128256
+    lm_head_ms = V * H * 2 / (read_GBps * 1e6)
+    layer_params = 8192 * 10240 + 8192 * 8192 + 8192 * 57344 + 28672 * 8192
+    draft_ms = (layer_params * 2 + 2 * H * H * 2) / (read_GBps * 1e6) + lm_head_ms
+    t_t = 80 * 0.100 + lm_head_ms
+    assert abs(out["inputs"]["T_t_ms"] - t_t) < 1e-12 and abs(out["inputs"]["T_d_ms_estimated"] - draft_ms) < 1e-12
+    for n, (d, tau) in bench.PAPER_TAU_70B_W4A16.items():
+        ratio = (80 * layer_ms[n] + lm_head_ms) / t_t
+        row = out[str(n)]
+        assert row["d"] == d and row["tau_paper"] == tau
+        assert abs(row["T_v_over_T_t"] - ratio) < 1e-12
+        assert abs(row["speedup_over_own_autoregressive_no_draft_cost"] - tau / ratio) < 1e-12
+        # Eq. (1): expected latency per token relative to plain decoding, inverted into a speed-up
+        rel_latency = (d * draft_ms / t_t + ratio) / tau
+        assert abs(row["speedup_over_own_autoregressive_estimated_draft"] - 1.0 / rel_latency) < 1e-12
+    # the paper's figure: accepted length grows with the tree, so does the A100 verification ratio
+    taus = [bench.PAPER_TAU_70B_W4A16[n][1] for n in (24, 32, 40, 48)]
+    assert taus == sorted(taus) and all(3.2 < t < 4.0 for t in taus)
+    ratios = [bench.PAPER_RATIO_70B_W4A16_A100[n] for n in (24, 32, 40, 48)]
+    assert ratios == sorted(ratios) and ratios[-1] == 1.58
