@@ -6,7 +6,7 @@ through the library's ablation knobs (for M > 16 also the high-occupancy column-
 last-level cache never serves them, and writes the winners as rows of csrc/tuned_plans.inc.  The
 library falls back to a generic rule for shapes that have no row.
 
-    python -m paper_2505_22179_amd.tune --out gpurun_out/tuned_plans.inc [--shapes 70b,8b]
+    python -m paper_2505_22179_amd.tune --out tuned_plans.inc [--flat-out tuned_flat.inc] [--shapes 70b,8b]
 
 Rebuild the library after copying the outputs over csrc/tuned_plans.inc and csrc/tuned_flat.inc.
 """
