@@ -18,9 +18,10 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kHeadDim = 128;
 constexpr int kKeyBlock = 32;
-constexpr int kAttnThreads = 256;
 constexpr int kRowsPad = 64;
-constexpr int kAttnLdsBytes = 4 * 136 * 64 * 4;   // four exchange slots (they cover the four 8 KB V tiles)
+// LDS of a workgroup of 4 * RG wavefronts with RT row tiles each: one exchange slot per wavefront
+// (8 * RT accumulator quads + 2 * RT state values per lane); the slots cover the 8 KB V tiles
+constexpr int attn_lds_bytes(int rt, int rg) { return 4 * rg * (8 * rt * 4 + 2 * rt) * 64 * 4; }
 constexpr int kMaxSplits = 16;   // key ranges per head (the merge keeps one value per range in registers)
 
 __device__ __forceinline__ float xor_max(float v, int lane_mask)
@@ -30,12 +31,16 @@ __device__ __forceinline__ float xor_max(float v, int lane_mask)
 
 constexpr float kLowest = -1.0e30f;   // "no key seen yet": finite, so differences of two of them are 0, not NaN
 
-// One workgroup = one query head x one contiguous range of 32-key steps.  The four wavefronts split
-// the KEYS, not the rows: wavefront w takes steps w, w + 4, ... of the range and carries, for all
-// (up to 64) query rows, its own online-softmax state -- running maximum, running sum and an
+// One workgroup = one 64-row tile (a query head, or the heads of a KV group) x one contiguous range
+// of 32-key steps.  Its 4 * RG wavefronts are RG row groups of four: the four wavefronts of a row
+// group split the KEYS -- wavefront kw takes steps kw, kw + 4, ... of the range -- and each carries,
+// for the RT * 16 rows of its group, its own online-softmax state -- running maximum, running sum and an
 // unnormalised output tile -- so K and V rows are fetched once per workgroup (no wavefront re-reads
 // another's keys), the main loop has no workgroup barrier, and the four states meet once, at the
-// end, through LDS.
+// end, through LDS.  RT = 4, RG = 1: one wavefront per SIMD holds all 64 rows.  RT = 2, RG = 2: two
+// wavefronts per SIMD with 32 rows each (half the accumulator and Q registers, K/V fragments fetched
+// twice from L2): one wavefront's dependent softmax chain hides behind the other's matrix work.
+// RT = 2, RG = 1: tiles of at most 32 rows; two such workgroups fit a compute unit.
 //
 // Per step a lane's registers hold, for row tile rt (rows 16 rt + c) and lane (r, c):
 //   S^T = K . Q^T     sa[rt][i], sb[rt][i]: keys 4r + i of the step's two 16-key tiles, row 16 rt + c
@@ -48,7 +53,8 @@ constexpr float kLowest = -1.0e30f;   // "no key seen yet": finite, so differenc
 // from a per-wavefront LDS tile vt[d][32 keys in slot order], written as 8-byte units of four keys
 // and read as one 16-byte load per dt; 16-byte chunks are XOR-swizzled by bits of d against bank
 // conflicts.  The same wavefront writes and reads the tile: LDS keeps its program order.
-__global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
+template <int RT, int RG>
+__global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ k, const _Float16 *__restrict__ v,
     const uint8_t *__restrict__ mask, _Float16 *__restrict__ out, float *__restrict__ part_o,
     float *__restrict__ part_ml, int M, int P, int Hq, int Hkv,
@@ -57,6 +63,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     extern __shared__ float4v smem4[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kw = wave & 3, rg = wave >> 2;   // key wavefront inside the row group, row group
     const int r = lane >> 4, c = lane & 15;
     // Workgroups are dealt to the eight XCDs round-robin by index, and each XCD has its own L2.
     // Renumber so that the workgroups of one KV head (consecutive logical ids) share an XCD and
@@ -74,10 +81,10 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     const int b0 = sp * bq + (sp < brem ? sp : brem), b1 = b0 + bq + (sp < brem ? 1 : 0);
     const size_t kv_stride = (size_t)Hkv * kHeadDim;
 
-    int row[4], head[4];   // query row and head of tile row 16 rt + c; tile rows >= R repeat row R-1 and are never stored
+    int row[RT], head[RT];   // query row and head of tile row 16 (rg RT + rt) + c; tile rows >= R repeat row R-1 and are never stored
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
-        const int rho = min(rt * 16 + c, R - 1);
+    for (int rt = 0; rt < RT; ++rt) {
+        const int rho = min((rg * RT + rt) * 16 + c, R - 1);
         const int j = rep ? rho / M : 0;
         row[rt] = rho - j * M;
         head[rt] = rep ? unit * rep + j : unit;
@@ -86,30 +93,32 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
     // workgroups whose key range reaches the draft keys: a byte load per key inside the step loop
     // would put some thirty dependent memory round trips on the critical path of the last steps.
     __shared__ uint64_t row_bits[kRowsPad];
-    uint64_t mbits[4] = {0, 0, 0, 0};
+    uint64_t mbits[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) mbits[rt] = 0;
     const bool reaches_draft = b1 * kKeyBlock > P;   // uniform over the workgroup
     uint8_t mask_byte[16];   // requested first, used after the Q, K and V requests: the oldest loads
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int mrow = wave * 16 + i;
+        const int mrow = wave * 16 + i;   // wavefronts 0..3 cover the 64 rows
         mask_byte[i] = (reaches_draft && mrow < M && lane < M) ? mask[(size_t)mrow * M + lane] : 0;
     }
     // Q^T fragments (second operand of S^T): lane (r, c) holds q[row, h, 32 j + 8 r .. +7]
-    half8v qf[4][4];
+    half8v qf[RT][4];
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt)
+    for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             qf[rt][j] = *reinterpret_cast<const half8v *>(q + ((size_t)row[rt] * Hq + head[rt]) * kHeadDim + 32 * j + 8 * r);
 
-    float4v o[8][4];
+    float4v o[8][RT];
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt) o[dt][rt] = (float4v){0.f, 0.f, 0.f, 0.f};
-    float m_run[4], l_run[4];   // l_run: this lane's share (its keys 4r + i) of the row's sum
+        for (int rt = 0; rt < RT; ++rt) o[dt][rt] = (float4v){0.f, 0.f, 0.f, 0.f};
+    float m_run[RT], l_run[RT];   // l_run: this lane's share (its keys 4r + i) of the row's sum
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
+    for (int rt = 0; rt < RT; ++rt) {
         m_run[rt] = kLowest;
         l_run[rt] = 0.f;
     }
@@ -163,25 +172,25 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
         park_v(vr);
         load_v(next, vr);
         __builtin_amdgcn_sched_barrier(0);
-        float4v sa[4], sb[4];
+        float4v sa[RT], sb[RT];
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt) {
+        for (int rt = 0; rt < RT; ++rt) {
             sa[rt] = (float4v){0.f, 0.f, 0.f, 0.f};
             sb[rt] = (float4v){0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int rt = 0; rt < 4; ++rt) {
+            for (int rt = 0; rt < RT; ++rt) {
                 sa[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[j], qf[rt][j], sa[rt], 0, 0, 0);
                 sb[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[j], qf[rt][j], sb[rt], 0, 0, 0);
             }
         load_k(next, fa, fb);
         __builtin_amdgcn_sched_barrier(0);
-        half8v pb[4];
+        half8v pb[RT];
         const bool prefix_only = key0 + kKeyBlock <= P;   // uniform: committed keys, all visible
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt) {
+        for (int rt = 0; rt < RT; ++rt) {
             float s[8];
             if (prefix_only) {
 #pragma unroll
@@ -223,13 +232,13 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
             const int chunk = r ^ ((d >> 1) & 3) ^ ((d >> 3) & 3);
             const half8v va = *reinterpret_cast<const half8v *>(vt + d * 64 + chunk * 16);
 #pragma unroll
-            for (int rt = 0; rt < 4; ++rt) o[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], o[dt][rt], 0, 0, 0);
+            for (int rt = 0; rt < RT; ++rt) o[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], o[dt][rt], 0, 0, 0);
         }
     };
 
     half8v ka[4], kb[4];
     u32x4 vr[2][4];
-    const int first = b0 + wave;
+    const int first = b0 + kw;
     if (first < b1) {
         load_k(first, ka, kb);
         load_v(first, vr);
@@ -238,63 +247,64 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const uint64_t bits = __ballot(mask_byte[i] != 0);
-            if (lane == 0) row_bits[wave * 16 + i] = bits;
+            if (lane == 0 && wave < 4) row_bits[wave * 16 + i] = bits;
         }
         __syncthreads();
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt) mbits[rt] = row_bits[row[rt]];
+        for (int rt = 0; rt < RT; ++rt) mbits[rt] = row_bits[row[rt]];
     }
     for (int step = first; step < b1; step += 4)
         step_fn(step, step + 4 < b1 ? step + 4 : step, ka, kb, vr);   // past the end: the same rows again, unused
 
     // a row's sum over this wavefront's keys: add the four lanes (r = 0..3) that share the row
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
+    for (int rt = 0; rt < RT; ++rt) {
         l_run[rt] += __shfl_xor(l_run[rt], 16, 64);
         l_run[rt] += __shfl_xor(l_run[rt], 32, 64);
     }
-    // The four wavefronts' states meet in LDS: each parks its whole state (32 accumulator quads and
-    // 8 state values per lane, lane-contiguous), and after one barrier wavefront w combines, in
-    // wavefront order, the head-dim tiles 2w and 2w + 1 of all four and stores them.
-    float4v *xq = smem4;                                                             // [4 slots][32 quads][64 lanes]
-    float *xs = reinterpret_cast<float *>(smem4 + 4 * 32 * 64);                      // [4 slots][8 values][64 lanes]
+    // The wavefronts' states meet in LDS: each parks its whole state (8 * RT accumulator quads and
+    // 2 * RT state values per lane, lane-contiguous), and after one barrier wavefront (rg, kw) combines, in
+    // wavefront order, the head-dim tiles 2 kw and 2 kw + 1 of the four key wavefronts of its row group.
+    constexpr int kQuads = 8 * RT;
+    float4v *xq = smem4;                                                             // [slots][8 RT quads][64 lanes]
+    float *xs = reinterpret_cast<float *>(smem4 + 4 * RG * kQuads * 64);             // [slots][2 RT values][64 lanes]
     __syncthreads();   // every wavefront has left its V tile: the exchange reuses that LDS
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-        for (int rt = 0; rt < 4; ++rt) xq[(wave * 32 + dt * 4 + rt) * 64 + lane] = o[dt][rt];
+        for (int rt = 0; rt < RT; ++rt) xq[(wave * kQuads + dt * RT + rt) * 64 + lane] = o[dt][rt];
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
-        xs[(wave * 8 + rt) * 64 + lane] = m_run[rt];
-        xs[(wave * 8 + 4 + rt) * 64 + lane] = l_run[rt];
+    for (int rt = 0; rt < RT; ++rt) {
+        xs[(wave * 2 * RT + rt) * 64 + lane] = m_run[rt];
+        xs[(wave * 2 * RT + RT + rt) * 64 + lane] = l_run[rt];
     }
     __syncthreads();
     const bool last = nsplit == 1;
     float *po = part_o + (size_t)lid * kRowsPad * kHeadDim;
     float *pml = part_ml + (size_t)lid * kRowsPad * 2;
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
+    for (int rt = 0; rt < RT; ++rt) {
         float ms[4], wgt[4], m_all = kLowest, l_all = 0.f;
 #pragma unroll
         for (int w2 = 0; w2 < 4; ++w2) {
-            ms[w2] = xs[(w2 * 8 + rt) * 64 + lane];
+            ms[w2] = xs[((rg * 4 + w2) * 2 * RT + rt) * 64 + lane];
             m_all = fmaxf(m_all, ms[w2]);
         }
 #pragma unroll
         for (int w2 = 0; w2 < 4; ++w2) {
             wgt[w2] = __builtin_amdgcn_exp2f(ms[w2] - m_all);
-            l_all += wgt[w2] * xs[(w2 * 8 + 4 + rt) * 64 + lane];
+            l_all += wgt[w2] * xs[((rg * 4 + w2) * 2 * RT + RT + rt) * 64 + lane];
         }
-        const int orow = rt * 16 + c;
+        const int orow = (rg * RT + rt) * 16 + c;
         const float inv = last ? 1.f / l_all : 1.f;
 #pragma unroll
         for (int dd = 0; dd < 2; ++dd) {
-            const int dt = 2 * wave + dd;
+            const int dt = 2 * kw + dd;
             float4v val = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int w2 = 0; w2 < 4; ++w2) val += wgt[w2] * xq[(w2 * 32 + dt * 4 + rt) * 64 + lane];
+            for (int w2 = 0; w2 < 4; ++w2) val += wgt[w2] * xq[((rg * 4 + w2) * kQuads + dt * RT + rt) * 64 + lane];
             val *= inv;
-            // row 16 rt + c, head-dim elements 16 dt + 4r .. + 3: four consecutive outputs
+            // tile row orow, head-dim elements 16 dt + 4r .. + 3: four consecutive outputs
             if (orow < R) {
                 if (last) {
                     typedef _Float16 half4v __attribute__((ext_vector_type(4)));
@@ -305,7 +315,7 @@ __global__ __launch_bounds__(kAttnThreads) void tree_attn_kernel(
                 }
             }
         }
-        if (!last && wave == 0 && r == 0 && orow < R) {
+        if (!last && kw == 0 && r == 0 && orow < R) {
             // partial state of this key range: a second kernel merges the ranges (the kernel boundary
             // makes them visible, at no fence cost)
             pml[orow * 2] = m_all;
@@ -429,6 +439,29 @@ static int attn_splits(int M, int P, int units)
     return want < 1 ? 1 : want;
 }
 
+template <int RT, int RG, typename... Args>
+static int launch_attn_variant(int grid, hipStream_t stream, Args... args)
+{
+    static bool lds_ok = false;   // LDS above 48 KB needs an opt-in, once per variant
+    constexpr int lds = attn_lds_bytes(RT, RG);
+    if (!lds_ok) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_kernel<RT, RG>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return W4A16_EHIP;
+        lds_ok = true;
+    }
+    hipLaunchKernelGGL((tree_attn_kernel<RT, RG>), dim3((unsigned)grid), dim3(256 * RG), lds, stream, args...);
+    return W4A16_OK;
+}
+
+template <typename... Args>
+static int launch_attn(int rt, int rgroups, int grid, hipStream_t stream, Args... args)
+{
+    if (rt == 4) return launch_attn_variant<4, 1>(grid, stream, args...);
+    if (rgroups == 2) return launch_attn_variant<2, 2>(grid, stream, args...);
+    return launch_attn_variant<2, 1>(grid, stream, args...);
+}
+
 static int check_attn(int M, int P, int Hq, int Hkv, int D)
 {
     if (M < 1 || P < 0 || Hq < 1 || Hkv < 1 || D < 1) return W4A16_EINVAL;
@@ -468,16 +501,16 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
     float *part_ml = part_o + (size_t)units * ns * kRowsPad * kHeadDim;
     const float scale_log2e = scale * 1.4426950408889634f;
     const int nblk = (P + M + kKeyBlock - 1) / kKeyBlock;
-    static bool lds_ok = false;   // LDS above 64 KB needs an opt-in, once
-    if (!lds_ok) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLdsBytes) != hipSuccess)
-            return W4A16_EHIP;
-        lds_ok = true;
-    }
-    hipLaunchKernelGGL(tree_attn_kernel, dim3((unsigned)(units * ns)), dim3(kAttnThreads), kAttnLdsBytes, (hipStream_t)stream,
-                       (const _Float16 *)q, (const _Float16 *)k, (const _Float16 *)v, mask, (_Float16 *)out,
-                       part_o, part_ml, M, P, Hq, Hkv, scale_log2e, ns, nblk / ns, nblk % ns, rep);
+    // row tiles per wavefront: tiles of at most 32 rows run with 2 (fewer registers, two workgroups per
+    // compute unit: measured 12-17 % faster); fuller tiles with 4, one wavefront per SIMD carrying all 64
+    // rows (two row groups of 32 rows re-fetch K/V fragments and measured 15-20 % slower)
+    const int rows = rep ? M * rep : M;
+    const int knob = params().attn_row_tiles;
+    const int rt = knob == 4 ? 4 : knob == 2 ? 2 : (rows <= 32 ? 2 : 4), rgroups = (rt == 2 && rows > 32) ? 2 : 1;
+    rc = launch_attn(rt, rgroups, units * ns, (hipStream_t)stream, (const _Float16 *)q, (const _Float16 *)k,
+                     (const _Float16 *)v, mask, (_Float16 *)out, part_o, part_ml, M, P, Hq, Hkv, scale_log2e, ns,
+                     nblk / ns, nblk % ns, rep);
+    if (rc != W4A16_OK) return rc;
     if (ns > 1) {
         const int quads = M * Hq * (kHeadDim / 4);
         const dim3 grid((unsigned)((quads + 255) / 256));

@@ -17,6 +17,7 @@ def _reset_knobs():
     yield
     B.w4a16_set_param("attn_splits", 0)
     B.w4a16_set_param("attn_pack", 0)
+    B.w4a16_set_param("attn_row_tiles", 0)
 
 
 def run_attn(a: I.AttnInputs, ws=None):
@@ -66,9 +67,11 @@ def test_attn_parity(M, P, Hq, Hkv, tree):
     ref64, _ = R.tree_verify_attn(a.q, a.k, a.v, a.mask, a.scale)
     for pack in ((0, 1) if M * (Hq // Hkv) <= 64 and Hq > Hkv else (0,)):   # shared tile per KV group, and without
         B.w4a16_set_param("attn_pack", pack)
-        for splits in (0, 1, 3, 16):
-            B.w4a16_set_param("attn_splits", splits)
-            stats = check(run_attn(a), ref64, f"M={M} P={P} {tree} splits={splits} pack={pack}")
+        for row_tiles in (0, 2, 4):   # by tile height; 32 rows per wavefront (one or two row groups); all 64
+            B.w4a16_set_param("attn_row_tiles", row_tiles)
+            for splits in (0, 1, 3, 16):
+                B.w4a16_set_param("attn_splits", splits)
+                stats = check(run_attn(a), ref64, f"M={M} P={P} {tree} splits={splits} pack={pack} row_tiles={row_tiles}")
     print("   ", stats, flush=True)
 
 
