@@ -146,35 +146,45 @@ class DecoderLayer:
         B.w4a16_gemm_fused(self.act, w[3], self.h2, M, H, self.Ngu // 2, G, B.EPI_RESIDUAL, self.h1, L.ws)
 
 
-# Expected accepted length tau(n, d) of EAGLE-2 on the W4A16 Llama-3-70B target, read off the paper's
-# figure "Accepted Length (70B, A100)" (W4A16 series; tree sizes n with d = 3, 4, 5, 6 draft passes).
+# Expected accepted length tau(n, d) of EAGLE-2 on the W4A16 targets, read off the paper's figures
+# "Accepted Length (70B, A100)" and "Accepted Length (8B, A100)" (W4A16 series; tree size n: (d draft
+# passes, tau)), and the same figure groups' verification-to-decoding time ratios on an A100.
 PAPER_TAU_70B_W4A16 = {24: (3, 3.283), 32: (4, 3.630), 40: (5, 3.819), 48: (6, 3.926)}
-# the same figure group's verification-to-decoding time ratio on an A100, for comparison
 PAPER_RATIO_70B_W4A16_A100 = {24: 1.262, 32: 1.287, 40: 1.555, 48: 1.580}
+PAPER_TAU_8B_W4A16 = {30: (3, 3.300), 40: (4, 3.669), 50: (5, 3.902), 60: (6, 4.046)}
+PAPER_RATIO_8B_W4A16_A100 = {30: 1.317, 40: 1.548, 50: 1.790, 60: 1.803}
 
 
-def eq1_projection(layer_ms: dict, read_GBps: float) -> dict:
+def eq1_projection(layer_ms: dict, read_GBps: float, *, shapes=None, n_layers: int = 80, tau=None, paper_ratio=None,
+                   lm_head_ms: float | None = None, draft_lm_head_ms: float | None = None) -> dict:
     """The paper's speedup model (Eq. 1), T_sd/T_t = (d T_d/T_t + T_v(n)/T_t) / tau(n, d), fed with
     this GPU's measured decoder-layer times for T_v(n)/T_t and the paper's tau.  The draft model is
     not built here: its time is ESTIMATED as the bytes one pass of an EAGLE-2 draft has to stream (one
-    fp16 decoder layer of the target's shape, the 2H->H fusion layer and the fp16 LM head) at the
-    plain-read rate measured above, and the target's own fp16 LM head is added to both T_t and T_v.
-    A projection for context, not a measurement of speculative decoding."""
-    H, V, layers = 8192, 128256, 80
-    layer_params = sum(K * N for (_, K, N) in I.LLAMA3_70B)
-    lm_head_ms = V * H * 2 / (read_GBps * 1e6)
-    draft_ms = (layer_params * 2 + 2 * H * H * 2) / (read_GBps * 1e6) + lm_head_ms
-    t_t = layer_ms[1] * layers + lm_head_ms
-    out = {"inputs": {"tau": "paper, figure 'Accepted Length (70B, A100)', W4A16 series",
-                      "T_v_over_T_t": "measured here: 80 x decoder layer (prefix 2048) + estimated fp16 LM head",
-                      "T_d": "estimated from bytes at the measured plain-read rate, not measured",
-                      "T_t_ms": t_t, "T_d_ms_estimated": draft_ms, "lm_head_ms_estimated": lm_head_ms}}
-    for n, (d, tau) in PAPER_TAU_70B_W4A16.items():
-        t_v = layer_ms[n] * layers + lm_head_ms
-        out[str(n)] = {"d": d, "tau_paper": tau, "T_v_over_T_t": t_v / t_t,
-                       "T_v_over_T_t_paper_A100": PAPER_RATIO_70B_W4A16_A100[n],
-                       "speedup_over_own_autoregressive_no_draft_cost": tau / (t_v / t_t),
-                       "speedup_over_own_autoregressive_estimated_draft": tau / (d * draft_ms / t_t + t_v / t_t)}
+    fp16 decoder layer of the target's shape and the 2H->H fusion layer) at the plain-read rate
+    measured above, plus the fp16 LM head -- measured with lm_head_topk when given (draft_lm_head_ms
+    for the draft's beam, lm_head_ms for the target's own head, added to both T_t and T_v), else
+    estimated from its bytes too.  A projection for context, not a measurement of speculative decoding."""
+    shapes = I.LLAMA3_70B if shapes is None else shapes
+    tau = PAPER_TAU_70B_W4A16 if tau is None else tau
+    paper_ratio = PAPER_RATIO_70B_W4A16_A100 if paper_ratio is None else paper_ratio
+    H, V = shapes[0][1], 128256
+    layer_params = sum(K * N for (_, K, N) in shapes)
+    head_by_bytes = V * H * 2 / (read_GBps * 1e6)
+    lm_t = head_by_bytes if lm_head_ms is None else lm_head_ms
+    lm_d = head_by_bytes if draft_lm_head_ms is None else draft_lm_head_ms
+    draft_ms = (layer_params * 2 + 2 * H * H * 2) / (read_GBps * 1e6) + lm_d
+    t_t = layer_ms[1] * n_layers + lm_t
+    out = {"inputs": {"tau": "paper, figures 'Accepted Length (70B / 8B, A100)', W4A16 series",
+                      "T_v_over_T_t": f"measured here: {n_layers} x decoder layer (prefix 2048) + fp16 LM head",
+                      "T_d": "fp16 draft layer estimated from bytes at the measured plain-read rate, not measured",
+                      "lm_head": "measured (lm_head_topk)" if lm_head_ms is not None else "estimated from bytes",
+                      "T_t_ms": t_t, "T_d_ms_estimated": draft_ms, "lm_head_ms": lm_t}}
+    for n, (d, ta) in tau.items():
+        t_v = layer_ms[n] * n_layers + lm_t
+        out[str(n)] = {"d": d, "tau_paper": ta, "T_v_over_T_t": t_v / t_t,
+                       "T_v_over_T_t_paper_A100": paper_ratio[n],
+                       "speedup_over_own_autoregressive_no_draft_cost": ta / (t_v / t_t),
+                       "speedup_over_own_autoregressive_estimated_draft": ta / (d * draft_ms / t_t + t_v / t_t)}
     return out
 
 
@@ -419,16 +429,32 @@ def main():
             del layer
         extra["llama3_70b_decoder_layer_P2048"] = {
             str(M): {"us_per_layer": ms * 1e3, "ratio_vs_M1": ms / dl[1], "ms_per_80_layers": ms * 80} for M, ms in dl.items()}
-        extra["eq1_projection_70b"] = eq1_projection(dl, plain["gate_up"]["GBps"])
         del big
         torch.cuda.empty_cache()
-        extra["lm_head_topk_V128256"] = lm_head_leg(args, use_graph)
+        lm = lm_head_leg(args, use_graph)
+        extra["lm_head_topk_V128256"] = lm
+        read_rate = plain["gate_up"]["GBps"]
+        extra["eq1_projection_70b"] = eq1_projection(dl, read_rate, lm_head_ms=lm["8192"]["M1"]["us"] * 1e-3,
+                                                     draft_lm_head_ms=lm["8192"]["M10"]["us"] * 1e-3)
         small = Layer(I.LLAMA3_8B, 6, seed=8)   # 6 x 113 MB: never re-read within 512 MB
         s8 = {}
         for M in I.M_SWEEP_8B:
             ms = time_steps(lambda c, M=M: small.step(M, c), args.steps, args.warmup, use_graph, 6)
             s8[M] = ms
             log(f"8B M={M}: {ms * 1e3:.1f} us/layer  {small.bytes / ms / 1e6:.0f} GB/s")
+        dl8 = {}
+        for M in (1, 8, 30, 40, 50, 60):
+            layer = DecoderLayer(small, M, 2048, kv_copies=48, Hq=32, Hkv=8, D=128)
+            ms = time_steps(layer.step, args.steps, args.warmup, use_graph, 48)
+            dl8[M] = ms
+            log(f"8B decoder layer M={M}: {ms * 1e3:.1f} us")
+            del layer
+        extra["llama3_8b_decoder_layer_P2048"] = {
+            str(M): {"us_per_layer": ms * 1e3, "ratio_vs_M1": ms / dl8[1], "ms_per_32_layers": ms * 32} for M, ms in dl8.items()}
+        extra["eq1_projection_8b"] = eq1_projection(dl8, read_rate, shapes=I.LLAMA3_8B, n_layers=32, tau=PAPER_TAU_8B_W4A16,
+                                                    paper_ratio=PAPER_RATIO_8B_W4A16_A100,
+                                                    lm_head_ms=lm["4096"]["M1"]["us"] * 1e-3,
+                                                    draft_lm_head_ms=lm["4096"]["M10"]["us"] * 1e-3)
         extra["llama3_8b_layer"] = {str(M): {"us_per_layer": ms * 1e3, "weight_GBps": small.bytes / ms / 1e6,
                                             "ratio_vs_M1": ms / s8[1]} for M, ms in s8.items()}
         bytes70 = sum(weight_bytes(K, N) for (_, K, N) in I.LLAMA3_70B)

@@ -13,6 +13,7 @@ def test_projection_formula_by_hand():
     draft_ms = (layer_params * 2 + 2 * H * H * 2) / (read_GBps * 1e6) + lm_head_ms
     t_t = 80 * 0.100 + lm_head_ms
     assert abs(out["inputs"]["T_t_ms"] - t_t) < 1e-12 and abs(out["inputs"]["T_d_ms_estimated"] - draft_ms) < 1e-12
+    assert out["inputs"]["lm_head"] == "estimated from bytes"
     for n, (d, tau) in bench.PAPER_TAU_70B_W4A16.items():
         ratio = (80 * layer_ms[n] + lm_head_ms) / t_t
         row = out[str(n)]
@@ -27,3 +28,18 @@ def test_projection_formula_by_hand():
     assert taus == sorted(taus) and all(3.2 < t < 4.0 for t in taus)
     ratios = [bench.PAPER_RATIO_70B_W4A16_A100[n] for n in (24, 32, 40, 48)]
     assert ratios == sorted(ratios) and ratios[-1] == 1.58
+
+
+def test_projection_with_measured_heads_and_the_8b_tables():
+    from paper_2505_22179_amd import inputs as I
+    layer_ms = {1: 0.040, 30: 0.050, 40: 0.060, 50: 0.066, 60: 0.070}
+    out = bench.eq1_projection(layer_ms, 6500.0, shapes=I.LLAMA3_8B, n_layers=32, tau=bench.PAPER_TAU_8B_W4A16,
+                               paper_ratio=bench.PAPER_RATIO_8B_W4A16_A100, lm_head_ms=0.175, draft_lm_head_ms=0.200)
+    t_t = 32 * 0.040 + 0.175
+    layer_params = 4096 * 6144 + 4096 * 4096 + 4096 * 28672 + 14336 * 4096
+    draft_ms = (layer_params * 2 + 2 * 4096 * 4096 * 2) / (6500.0 * 1e6) + 0.200
+    assert abs(out["inputs"]["T_t_ms"] - t_t) < 1e-12 and abs(out["inputs"]["T_d_ms_estimated"] - draft_ms) < 1e-12
+    row = out["60"]
+    ratio = (32 * 0.070 + 0.175) / t_t
+    assert row["d"] == 6 and abs(row["T_v_over_T_t"] - ratio) < 1e-12 and row["T_v_over_T_t_paper_A100"] == 1.803
+    assert abs(row["speedup_over_own_autoregressive_estimated_draft"] - 4.046 / (6 * draft_ms / t_t + ratio)) < 1e-12
