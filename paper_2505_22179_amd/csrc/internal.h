@@ -29,6 +29,7 @@ struct Params {
     int fused_reduce = 2;  // 0 = second kernel, 1 = last workgroup, 2 = per-shape choice
     int attn_splits = 0;   // 0 = heuristic
     int attn_row_tiles = 0;   // 0 = by tile height, 2 = 32 query rows per wavefront (two row groups for taller tiles), 4 = 64 rows
+    int lm_tiles = 0;         // 0 = by M, else 1 or 2 vocabulary tiles per wavefront in lm_head_topk
     int attn_pack = 0;     // 0 = the query heads of a KV group share a row tile when they fit, 1 = never
     int tiles_per_wave = 0;   // 0 = heuristic, else 2, 4 or 8
     int waves_per_wg = 0;     // 0 = heuristic, else 4, 8 or 16

@@ -39,10 +39,11 @@ __global__ void lm_head_pack_kernel(const _Float16 *__restrict__ W, u32x4 *__res
 // Logits.  A wavefront owns one vocabulary tile (16 tokens = the rows of the MFMA result, the up to 16
 // hidden-state rows its columns) and streams the tile's K / 32 blocks with a ring of kLmDepth macro
 // steps (4 blocks = 4 KB each) in flight; the x fragments (at most 16 x K fp16, L2-resident) are
-// re-read per tile.  Tiles lie K * 32 bytes apart, a power of two for the usual hidden sizes:
+// re-read per wavefront, which works on two neighbouring tiles at once so that each fragment serves
+// both.  Tiles lie K * 32 bytes apart, a power of two for the usual hidden sizes:
 // wavefronts that all walked k from 0 would ask the same few memory channels at any moment, so each
 // starts at macro step (tile mod steps) and wraps around.
-template <bool EVEN>
+template <bool EVEN, int TWL>
 __global__ __launch_bounds__(256) void lm_head_logits_kernel(const _Float16 *__restrict__ x,
                                                              const u32x4 *__restrict__ packed,
                                                              float *__restrict__ logits, int M, int V, int K, int tiles)
@@ -50,28 +51,36 @@ __global__ __launch_bounds__(256) void lm_head_logits_kernel(const _Float16 *__r
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane >> 4, c = lane & 15;
-    const int tile = blockIdx.x * 4 + wave;
-    if (tile >= tiles) return;   // no barrier in this kernel
+    const int tile0 = (blockIdx.x * 4 + wave) * TWL;   // TWL consecutive tiles share every x fragment
+    if (tile0 >= tiles) return;   // no barrier in this kernel
     const int steps = K / kLmStepK;
-    const u32x4 *wp = packed + (size_t)tile * (K / 32) * 64 + lane;
+    const u32x4 *wp[TWL];
+#pragma unroll
+    for (int t = 0; t < TWL; ++t)   // a tile past the end repeats the last one; its logits are not stored
+        wp[t] = packed + (size_t)min(tile0 + t, tiles - 1) * (K / 32) * 64 + lane;
     const u32x4 *xp = reinterpret_cast<const u32x4 *>(x + (size_t)min(c, M - 1) * K + 8 * r);
-    u32x4 w[kLmDepth][4], xf[kLmDepth][4];
-    const int rot = tile % steps;
+    u32x4 w[kLmDepth][TWL][4], xf[kLmDepth][4];
+    const int rot = (tile0 / TWL) % steps;
     auto load = [&](int s, int slot) {
         int sr = s + rot;              // uniform
         sr = sr >= steps ? sr - steps : sr;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            w[slot][j] = __builtin_nontemporal_load(wp + (sr * 4 + j) * 64);
+#pragma unroll
+            for (int t = 0; t < TWL; ++t) w[slot][t][j] = __builtin_nontemporal_load(wp[t] + (sr * 4 + j) * 64);
             xf[slot][j] = xp[(sr * 4 + j) * 4];
         }
     };
-    float4v acc = {0.f, 0.f, 0.f, 0.f};
+    float4v acc[TWL];
+#pragma unroll
+    for (int t = 0; t < TWL; ++t) acc[t] = (float4v){0.f, 0.f, 0.f, 0.f};
     auto compute = [&](int slot) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, w[slot][j]),
-                                                         __builtin_bit_cast(half8v, xf[slot][j]), acc, 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < TWL; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, w[slot][t][j]),
+                                                                __builtin_bit_cast(half8v, xf[slot][j]), acc[t], 0, 0, 0);
     };
     if constexpr (EVEN) {   // steps is a multiple of the ring depth: every load of the steady state is unconditional
 #pragma unroll
@@ -101,15 +110,18 @@ __global__ __launch_bounds__(256) void lm_head_logits_kernel(const _Float16 *__r
         }
     }
     // lane (r, c) holds the logits of tokens 16 tile + 4 r .. + 3 for hidden-state row c
-    const int v0 = tile * 16 + 4 * r;
-    if (c < M) {
-        float *dst = logits + (size_t)c * V + v0;
-        if ((V & 3) == 0 && v0 + 3 < V) {
-            *reinterpret_cast<float4v *>(dst) = acc;
-        } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (v0 + i < V) dst[i] = acc[i];
+    for (int t = 0; t < TWL; ++t) {
+        const int v0 = (tile0 + t) * 16 + 4 * r;
+        if (c < M && tile0 + t < tiles) {
+            float *dst = logits + (size_t)c * V + v0;
+            if ((V & 3) == 0 && v0 + 3 < V) {
+                *reinterpret_cast<float4v *>(dst) = acc[t];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (v0 + i < V) dst[i] = acc[t][i];
+            }
         }
     }
 }
@@ -377,13 +389,24 @@ int lm_head_topk(const void *x, const void *packed, int M, int V, int K, int top
         lds_ok = true;
     }
     hipStream_t s = (hipStream_t)stream;
-    const dim3 grid((unsigned)((tiles + 3) / 4));
-    if ((K / kLmStepK) % kLmDepth == 0)
-        hipLaunchKernelGGL(lm_head_logits_kernel<true>, grid, dim3(256), 0, s, (const _Float16 *)x, (const u32x4 *)packed,
-                           logits, M, V, K, tiles);
-    else
-        hipLaunchKernelGGL(lm_head_logits_kernel<false>, grid, dim3(256), 0, s, (const _Float16 *)x, (const u32x4 *)packed,
-                           logits, M, V, K, tiles);
+    const bool even = (K / kLmStepK) % kLmDepth == 0;
+    // tiles per wavefront: two halve the x-fragment traffic from L2, which matters once the hidden-state
+    // rows differ (M = 16: 240 -> 194 us at K = 4096); a single row is a broadcast and runs best with one
+    const int twl = params().lm_tiles > 0 ? params().lm_tiles : (M <= 4 ? 1 : 2);
+    const dim3 grid((unsigned)((tiles + 4 * twl - 1) / (4 * twl)));
+#define W4_LM_LAUNCH(EVEN_, TWL_)                                                                                       \
+    hipLaunchKernelGGL((lm_head_logits_kernel<EVEN_, TWL_>), grid, dim3(256), 0, s, (const _Float16 *)x,                \
+                       (const u32x4 *)packed, logits, M, V, K, tiles)
+    if (twl == 1) {
+        if (even) W4_LM_LAUNCH(true, 1);
+        else W4_LM_LAUNCH(false, 1);
+    } else if (twl == 2) {
+        if (even) W4_LM_LAUNCH(true, 2);
+        else W4_LM_LAUNCH(false, 2);
+    } else {
+        return W4A16_EUNSUP;
+    }
+#undef W4_LM_LAUNCH
     hipLaunchKernelGGL(lm_head_chunk_kernel, dim3((unsigned)((chunks + kLmThreads / 64 - 1) / (kLmThreads / 64)), (unsigned)M), dim3(kLmThreads), 0, s,
                        (const float *)logits, V, top_k, chunks, chunk_max, chunk_sum, cand_val, cand_idx);
     hipLaunchKernelGGL(lm_head_merge_kernel, dim3((unsigned)M), dim3(kLmThreads), (size_t)chunks * top_k * 8, s, (const float *)chunk_max,

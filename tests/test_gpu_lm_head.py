@@ -73,7 +73,12 @@ def check(x, W, top_k, what):
 def test_lm_head_parity(M, K, V, top_k):
     print(f"lm_head M={M} K={K} V={V} top_k={top_k}", flush=True)
     x, W = I.make_lm_head(9500 + M + K + V, M, K, V)
-    e = check(x, W, top_k, f"M={M} K={K} V={V} k={top_k}")
+    try:
+        for tiles_per_wave in (0, 1, 2):
+            B.w4a16_set_param("lm_tiles", tiles_per_wave)
+            e = check(x, W, top_k, f"M={M} K={K} V={V} k={top_k} tiles per wavefront {tiles_per_wave}")
+    finally:
+        B.w4a16_set_param("lm_tiles", 0)
     print(f"    logits max abs err {e:.3g}", flush=True)
 
 
