@@ -16,7 +16,10 @@
  *   - the return value is W4A16_OK or a negative W4A16_E* code; arguments are validated before any
  *     GPU call, so an invalid call enqueues nothing; nothing is printed, nothing aborts;
  *   - all pointers must be 16-byte aligned; buffers must not overlap;
- *   - the same inputs give bit-identical outputs on every call (no atomically ordered sums).
+ *   - the same inputs give bit-identical outputs on every call (no atomically ordered sums);
+ *   - one GPU per process: the library keeps a few process-wide one-time flags (kernel attributes
+ *     set on first use) and the ablation knobs; calls may be issued from any one host thread at a
+ *     time, on any stream of the current device.
  */
 #ifndef W4A16_H
 #define W4A16_H
