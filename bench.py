@@ -101,8 +101,9 @@ class Layer:
 
 class DecoderLayer:
     """One whole decoder layer of the target model on M draft-tree tokens over a P-token prefix, chained
-    from the library's entry points: norm, qkv, rotary + K/V append, tree attention, o_proj + residual,
-    norm, gate/up with the SiLU gate, down + residual (8 kernels launches plus the split-K / merge passes)."""
+    through w4a16_decoder_layer: norm, qkv, rotary + K/V append, tree attention, o_proj + residual, norm,
+    gate/up with the SiLU gate, down + residual (8 kernel launches plus the split-K / merge passes).  The
+    hidden state of a step is one of several kept per object and is updated in place."""
 
     def __init__(self, layer: "Layer", M: int, P: int, kv_copies: int, Hq: int = 64, Hkv: int = 8, D: int = 128):
         self.L, self.M, self.P, self.Hq, self.Hkv, self.D = layer, M, P, Hq, Hkv, D
@@ -114,7 +115,11 @@ class DecoderLayer:
         self.g1 = torch.from_numpy(I.make_gamma(4243, H)).cuda()
         self.g2 = torch.from_numpy(I.make_gamma(4244, H)).cuda()
         self.n1, self.qkv, self.q, self.att = f16(M, H), f16(M, Nqkv), f16(M, Hq, D), f16(M, Hq, D)
-        self.h1, self.n2, self.act, self.h2 = f16(M, H), f16(M, H), f16(M, Ngu // 2), f16(M, H)
+        self.act = f16(M, Ngu // 2)
+        # one hidden state per step of a replayed graph.  The layer updates it in place; both branches start
+        # with a norm, so every application adds a bounded update and the values stay far inside the fp16
+        # range over the few hundred applications of a benchmark run (no copy has to be timed)
+        self.h_work = [self.h.clone() for _ in range(kv_copies)]
         if M > 1:
             parent, _, mask = I.make_tree(I.seed_for(5, 0) + 7, M, 6, 4)
         else:
@@ -136,14 +141,10 @@ class DecoderLayer:
         L, M, P, Hq, Hkv, D, H = self.L, self.M, self.P, self.Hq, self.Hkv, self.D, self.H
         w = L.packed[c % L.copies]
         k, v = self.k[c % len(self.k)], self.v[c % len(self.v)]
-        B.rms_norm(self.h, self.g1, self.n1, M, H, 1e-5)
-        B.w4a16_gemm(self.n1, w[0], self.qkv, M, self.Nqkv, H, G, L.ws)
-        B.rope_append(self.qkv, self.pos, self.cos, self.sin, self.n_pos, self.q, k, v, M, P, Hq, Hkv, D)
-        B.tree_verify_attn(self.q, k, v, self.mask, self.att, M, P, Hq, Hkv, D, self.scale, self.aws)
-        B.w4a16_gemm_fused(self.att, w[1], self.h1, M, H, H, G, B.EPI_RESIDUAL, self.h, L.ws)
-        B.rms_norm(self.h1, self.g2, self.n2, M, H, 1e-5)
-        B.w4a16_gemm_fused(self.n2, w[2], self.act, M, self.Ngu, H, G, B.EPI_SILU_MUL, None, L.ws)
-        B.w4a16_gemm_fused(self.act, w[3], self.h2, M, H, self.Ngu // 2, G, B.EPI_RESIDUAL, self.h1, L.ws)
+        weights = B.layer_weights(w[0], w[1], w[2], w[3], self.g1, self.g2, H, Hq, Hkv, D, self.Ngu // 2, 1e-5)
+        scratch = B.layer_scratch(self.n1, self.qkv, self.q, self.att, self.act, L.ws, self.aws)
+        hs = self.h_work[c % len(self.h_work)]   # updated in place
+        B.w4a16_decoder_layer(weights, hs, M, P, self.pos, self.cos, self.sin, self.n_pos, self.mask, k, v, scratch)
 
 
 # Expected accepted length tau(n, d) of EAGLE-2 on the W4A16 targets, read off the paper's figures

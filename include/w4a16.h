@@ -206,6 +206,38 @@ int rms_norm(const void *x, const void *gamma, void *y, int M, int K, float eps,
 int rope_append(const void *qkv, const int32_t *pos, const float *cos_table, const float *sin_table, int n_pos,
                 void *q, void *k_cache, void *v_cache, int M, int P, int Hq, int Hkv, int D, void *stream);
 
+/* One decoder layer of a Llama-type target model on M token rows over a P-token prefix, enqueued as one
+ * call (paper section 2.1: a verification is one forward pass of the target over the draft tokens):
+ *   n = rms_norm(h, norm1_gamma);  qkv = n . Wqkv;  rope_append(qkv) -> q, cache rows P..P+M-1;
+ *   a = tree_verify_attn(q, cache, mask, scale 1/sqrt(head_dim));  h += a . Wo;
+ *   n = rms_norm(h, norm2_gamma);  h += (silu(n . Wgate) * (n . Wup)) . Wdown
+ * i.e. exactly rms_norm, w4a16_gemm, rope_append, tree_verify_attn and w4a16_gemm_fused (residual in
+ * place, SiLU gate) in this order on `stream`; arguments mean what they mean there.  h fp16 [M, hidden] is
+ * updated in place.  Weights: w4a16_pack outputs for qkv [hidden -> (n_q_heads + 2 n_kv_heads) head_dim],
+ * o [n_q_heads head_dim -> hidden] and down [ffn -> hidden]; a w4a16_pack_gate_up output for
+ * gate_up [hidden -> 2 ffn]; group size 128.  Scratch, all fp16 and 16-byte aligned, owned by the
+ * caller: norm [M, hidden], qkv [M, (n_q_heads + 2 n_kv_heads) head_dim], q and attn [M, n_q_heads,
+ * head_dim], act [M, ffn]; gemm_workspace sized for the largest of the four linears
+ * (w4a16_workspace_bytes) and attn_workspace (tree_verify_attn_workspace_bytes), both initialised with
+ * w4a16_workspace_init.  Returns the first error of the calls it makes; validation failures of the
+ * first call enqueue nothing, a failure further on leaves the earlier steps enqueued. */
+typedef struct {
+    const void *qkv_packed, *o_packed, *gate_up_packed, *down_packed;
+    const void *norm1_gamma, *norm2_gamma; /* fp16 [hidden] */
+    int hidden, n_q_heads, n_kv_heads, head_dim, ffn;
+    float eps;
+} w4a16_layer_weights;
+typedef struct {
+    void *norm, *qkv, *q, *attn, *act;
+    void *gemm_workspace;
+    size_t gemm_workspace_bytes;
+    void *attn_workspace;
+    size_t attn_workspace_bytes;
+} w4a16_layer_scratch;
+int w4a16_decoder_layer(const w4a16_layer_weights *w, void *h, int M, int P, const int32_t *pos,
+                        const float *cos_table, const float *sin_table, int n_pos, const uint8_t *mask,
+                        void *k_cache, void *v_cache, const w4a16_layer_scratch *s, void *stream);
+
 /* Size in bytes of the packed LM-head weight for a V-token vocabulary and hidden size K (the
  * vocabulary is padded to a multiple of 16 inside the buffer).  0 if the shape is not supported. */
 size_t lm_head_packed_bytes(int V, int K);

@@ -17,12 +17,27 @@ EXPORTS = (
     "w4a16_workspace_bytes", "w4a16_workspace_init", "w4a16_pack", "w4a16_unpack", "w4a16_dequant",
     "w4a16_gemm", "w4a16_gemm_fused", "w4a16_pack_gate_up", "w4a16_read_probe", "tree_verify_attn_workspace_bytes",
     "tree_verify_attn", "tree_accept", "rms_norm", "rope_append", "lm_head_workspace_bytes", "lm_head_topk",
-    "lm_head_packed_bytes", "lm_head_pack",
+    "lm_head_packed_bytes", "lm_head_pack", "w4a16_decoder_layer",
 )
 
 EPI_NONE, EPI_RESIDUAL, EPI_SILU_MUL = 0, 1, 2
 
 _lib = None
+
+
+class LayerWeights(ctypes.Structure):
+    """w4a16_layer_weights of include/w4a16.h"""
+    _fields_ = [("qkv_packed", ctypes.c_void_p), ("o_packed", ctypes.c_void_p), ("gate_up_packed", ctypes.c_void_p),
+                ("down_packed", ctypes.c_void_p), ("norm1_gamma", ctypes.c_void_p), ("norm2_gamma", ctypes.c_void_p),
+                ("hidden", ctypes.c_int), ("n_q_heads", ctypes.c_int), ("n_kv_heads", ctypes.c_int),
+                ("head_dim", ctypes.c_int), ("ffn", ctypes.c_int), ("eps", ctypes.c_float)]
+
+
+class LayerScratch(ctypes.Structure):
+    """w4a16_layer_scratch of include/w4a16.h"""
+    _fields_ = [("norm", ctypes.c_void_p), ("qkv", ctypes.c_void_p), ("q", ctypes.c_void_p), ("attn", ctypes.c_void_p),
+                ("act", ctypes.c_void_p), ("gemm_workspace", ctypes.c_void_p), ("gemm_workspace_bytes", ctypes.c_size_t),
+                ("attn_workspace", ctypes.c_void_p), ("attn_workspace_bytes", ctypes.c_size_t)]
 
 
 class W4A16Error(RuntimeError):
@@ -62,6 +77,8 @@ def load() -> ctypes.CDLL:
     L.w4a16_pack_gate_up.argtypes = [vp, vp, vp, vp, i, i, i, vp]
     L.rms_norm.argtypes = [vp, vp, vp, i, i, ctypes.c_float, vp]
     L.rope_append.argtypes = [vp, vp, vp, vp, i, vp, vp, vp, i, i, i, i, i, vp]
+    L.w4a16_decoder_layer.argtypes = [ctypes.POINTER(LayerWeights), vp, i, i, vp, vp, vp, i, vp, vp, vp,
+                                      ctypes.POINTER(LayerScratch), vp]
     L.lm_head_packed_bytes.restype = sz
     L.lm_head_packed_bytes.argtypes = [i, i]
     L.lm_head_pack.argtypes = [vp, vp, i, i, vp]
@@ -161,6 +178,25 @@ def rope_append(qkv, pos, cos_table, sin_table, n_pos: int, q, k_cache, v_cache,
                 D: int) -> None:
     _check(load().rope_append(_ptr(qkv), _ptr(pos), _ptr(cos_table), _ptr(sin_table), n_pos, _ptr(q), _ptr(k_cache),
                               _ptr(v_cache), M, P, Hq, Hkv, D, _stream()), "rope_append")
+
+
+def layer_weights(qkv_packed, o_packed, gate_up_packed, down_packed, norm1_gamma, norm2_gamma, hidden: int,
+                  n_q_heads: int, n_kv_heads: int, head_dim: int, ffn: int, eps: float) -> LayerWeights:
+    return LayerWeights(_ptr(qkv_packed), _ptr(o_packed), _ptr(gate_up_packed), _ptr(down_packed), _ptr(norm1_gamma),
+                        _ptr(norm2_gamma), hidden, n_q_heads, n_kv_heads, head_dim, ffn, float(eps))
+
+
+def layer_scratch(norm, qkv, q, attn, act, gemm_workspace, attn_workspace) -> LayerScratch:
+    nb = lambda t: 0 if t is None else t.numel() * t.element_size()
+    return LayerScratch(_ptr(norm), _ptr(qkv), _ptr(q), _ptr(attn), _ptr(act), _ptr(gemm_workspace), nb(gemm_workspace),
+                        _ptr(attn_workspace), nb(attn_workspace))
+
+
+def w4a16_decoder_layer(weights: LayerWeights, h, M: int, P: int, pos, cos_table, sin_table, n_pos: int, mask, k_cache,
+                        v_cache, scratch: LayerScratch) -> None:
+    _check(load().w4a16_decoder_layer(ctypes.byref(weights), _ptr(h), M, P, _ptr(pos), _ptr(cos_table), _ptr(sin_table),
+                                      n_pos, _ptr(mask), _ptr(k_cache), _ptr(v_cache), ctypes.byref(scratch), _stream()),
+           "w4a16_decoder_layer")
 
 
 def lm_head_workspace_bytes(M: int, V: int, K: int, top_k: int) -> int:

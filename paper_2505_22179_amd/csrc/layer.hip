@@ -125,3 +125,41 @@ int rope_append(const void *qkv, const int32_t *pos, const float *cos_table, con
 }
 
 }  // extern "C"
+
+// ---- one decoder layer as one call: host glue over the entry points above and in the other files ----
+
+extern "C" int w4a16_decoder_layer(const w4a16_layer_weights *w, void *h, int M, int P, const int32_t *pos,
+                                   const float *cos_table, const float *sin_table, int n_pos, const uint8_t *mask,
+                                   void *k_cache, void *v_cache, const w4a16_layer_scratch *s, void *stream)
+{
+    if (!w || !s) return W4A16_ENULL;
+    const int H = w->hidden, Hq = w->n_q_heads, Hkv = w->n_kv_heads, D = w->head_dim, F = w->ffn;
+    if (H < 1 || Hq < 1 || Hkv < 1 || D < 1 || F < 1 || M < 1 || P < 0) return W4A16_EINVAL;
+    if (!w->qkv_packed || !w->o_packed || !w->gate_up_packed || !w->down_packed || !w->norm1_gamma || !w->norm2_gamma)
+        return W4A16_ENULL;
+    if (!h || !s->norm || !s->qkv || !s->q || !s->attn || !s->act) return W4A16_ENULL;
+    const int Nqkv = (Hq + 2 * Hkv) * D;
+    const float scale = 1.0f / sqrtf((float)D);
+    int rc;
+    // attention block: h += Wo . attn(rope(Wqkv . norm(h)))
+    if ((rc = rms_norm(h, w->norm1_gamma, s->norm, M, H, w->eps, stream)) != W4A16_OK) return rc;
+    if ((rc = w4a16_gemm(s->norm, w->qkv_packed, s->qkv, M, Nqkv, H, kGroup, s->gemm_workspace, s->gemm_workspace_bytes,
+                         stream)) != W4A16_OK)
+        return rc;
+    if ((rc = rope_append(s->qkv, pos, cos_table, sin_table, n_pos, s->q, k_cache, v_cache, M, P, Hq, Hkv, D, stream)) !=
+        W4A16_OK)
+        return rc;
+    if ((rc = tree_verify_attn(s->q, k_cache, v_cache, mask, s->attn, M, P, Hq, Hkv, D, scale, s->attn_workspace,
+                               s->attn_workspace_bytes, stream)) != W4A16_OK)
+        return rc;
+    if ((rc = w4a16_gemm_fused(s->attn, w->o_packed, h, M, H, Hq * D, kGroup, W4A16_EPI_RESIDUAL, h, s->gemm_workspace,
+                               s->gemm_workspace_bytes, stream)) != W4A16_OK)
+        return rc;
+    // feed-forward block: h += Wdown . (silu(Wgate . n) * (Wup . n)),  n = norm(h)
+    if ((rc = rms_norm(h, w->norm2_gamma, s->norm, M, H, w->eps, stream)) != W4A16_OK) return rc;
+    if ((rc = w4a16_gemm_fused(s->norm, w->gate_up_packed, s->act, M, 2 * F, H, kGroup, W4A16_EPI_SILU_MUL, nullptr,
+                               s->gemm_workspace, s->gemm_workspace_bytes, stream)) != W4A16_OK)
+        return rc;
+    return w4a16_gemm_fused(s->act, w->down_packed, h, M, H, F, kGroup, W4A16_EPI_RESIDUAL, h, s->gemm_workspace,
+                            s->gemm_workspace_bytes, stream);
+}

@@ -174,3 +174,28 @@ def test_lm_head_validation_happens_before_any_gpu_call():
     assert lib.lm_head_pack(a, a + 4, 1000, 128, None) == EALIGN
     assert B.lm_head_workspace_bytes(10, 128256, 4096, 10) > 0
     assert B.lm_head_workspace_bytes(17, 128256, 4096, 10) == 0
+
+
+def test_decoder_layer_validation_happens_before_any_gpu_call():
+    import ctypes
+    lib = B.load()
+    a = 0x1000
+    EINVAL, ENULL = -1, -2
+    w = B.LayerWeights(a, a, a, a, a, a, 1024, 8, 2, 128, 2816, 1e-5)
+    s = B.LayerScratch(a, a, a, a, a, a, 1 << 20, a, 1 << 20)
+    f = lib.w4a16_decoder_layer
+    args = lambda ww, ss, h=a, M=4, P=10: (ww, h, M, P, a, a, a, 64, a, a, a, ss, None)
+    assert f(*args(None, ctypes.byref(s))) == ENULL
+    assert f(*args(ctypes.byref(w), None)) == ENULL
+    assert f(*args(ctypes.byref(w), ctypes.byref(s), h=None)) == ENULL
+    assert f(*args(ctypes.byref(w), ctypes.byref(s), M=0)) == EINVAL
+    assert f(*args(ctypes.byref(w), ctypes.byref(s), P=-1)) == EINVAL
+    bad = B.LayerWeights(a, a, None, a, a, a, 1024, 8, 2, 128, 2816, 1e-5)
+    assert f(*args(ctypes.byref(bad), ctypes.byref(s))) == ENULL
+    bad = B.LayerWeights(a, a, a, a, a, a, 1024, 0, 2, 128, 2816, 1e-5)
+    assert f(*args(ctypes.byref(bad), ctypes.byref(s))) == EINVAL
+    nos = B.LayerScratch(a, None, a, a, a, a, 1 << 20, a, 1 << 20)
+    assert f(*args(ctypes.byref(w), ctypes.byref(nos))) == ENULL
+    # the first step's own validation: hidden size the norm cannot take, before anything is enqueued
+    bad = B.LayerWeights(a, a, a, a, a, a, 1000 * 1024, 8, 2, 128, 2816, 1e-5)
+    assert f(*args(ctypes.byref(bad), ctypes.byref(s))) == -4

@@ -329,6 +329,19 @@ def test_decoder_layer_chain(big_ws):
         return tuple(host(t) for t in (n1, qkv, q, kd, vd, att, h1, n2, act, h2))
 
     n1, qkv, q, kd, vd, att, h1, n2, act, h2 = gpu_layer()
+
+    # the same layer as ONE call: every kernel is the same, so the hidden state and the cache must agree bit for bit
+    hd, kd1, vd1 = dev(h0), dev(kc), dev(vc)
+    g1d, g2d = dev(g1), dev(g2)
+    weights = B.layer_weights(packed["qkv"], packed["o"], packed["gate_up"], packed["down"], g1d, g2d, H, Hq, Hkv, D, Iff, 1e-5)
+    bufs = [f16(M, H), f16(M, (Hq + 2 * Hkv) * D), f16(M, Hq, D), f16(M, Hq, D), f16(M, Iff)]
+    aws = B.new_workspace(B.tree_verify_attn_workspace_bytes(M, P, Hq, Hkv, D))
+    scratch = B.layer_scratch(*bufs, big_ws, aws)
+    posd, cosd, sind, maskd = dev(pos), dev(cos), dev(sin), dev(mask)
+    B.w4a16_decoder_layer(weights, hd, M, P, posd, cosd, sind, P + 16, maskd, kd1, vd1, scratch)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(hd).view(np.uint16), h2.view(np.uint16)), "one-call layer differs from the chained calls"
+    assert np.array_equal(host(kd1).view(np.uint16), kd.view(np.uint16)) and np.array_equal(host(vd1).view(np.uint16), vd.view(np.uint16))
     # step by step, each oracle step on the GPU's input to that step
     close_to_rounded(n1, R.rms_norm(h0, g1, 1e-5)[0], "norm 1")
     check_gemm(qkv, R.w4a16_gemm(n1, *canon["qkv"])[1], "qkv")
