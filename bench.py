@@ -147,6 +147,89 @@ class DecoderLayer:
         B.w4a16_decoder_layer(weights, hs, M, P, self.pos, self.cos, self.sin, self.n_pos, self.mask, k, v, scratch)
 
 
+class Model:
+    """A whole target model on the device: n_layers decoder layers with their own packed weights (copies of
+    one synthetic layer: the addresses differ, which is all that matters to the memory system) and their
+    own K/V caches, a final norm and the fp16 LM head.  forward(M) enqueues one pass over M token rows:
+    plain decoding for M = 1, verification of an M-token draft tree otherwise."""
+
+    def __init__(self, shapes, n_layers: int, Hq: int, Hkv: int, D: int, P: int, seed: int, V: int = 128256, M_max: int = 64):
+        self.layers = Layer(shapes, n_layers, seed)
+        self.n_layers, self.Hq, self.Hkv, self.D, self.P, self.V = n_layers, Hq, Hkv, D, P, V
+        (_, H, Nqkv), _, (_, _, Ngu), _ = shapes
+        self.H, self.Nqkv, self.F = H, Nqkv, Ngu // 2
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(seed + 1)
+        f16 = lambda *shape: torch.empty(shape, dtype=torch.float16, device="cuda")
+        self.g = [torch.from_numpy(I.make_gamma(seed + 2 + i, H)).cuda() for i in range(3)]   # norm 1, norm 2, final
+        self.k = [torch.randn((P + M_max, Hkv, D), device="cuda", generator=gen).to(torch.float16) for _ in range(n_layers)]
+        self.v = [torch.randn((P + M_max, Hkv, D), device="cuda", generator=gen).to(torch.float16) for _ in range(n_layers)]
+        raw = (torch.randn((V, H), device="cuda", generator=gen) * 0.02).to(torch.float16)
+        self.head = torch.empty(B.lm_head_packed_bytes(V, H), dtype=torch.uint8, device="cuda")
+        B.lm_head_pack(raw, self.head, V, H)
+        del raw
+        cos, sin = I.make_rope_tables(P + 64, D)
+        self.cos, self.sin, self.n_pos = torch.from_numpy(cos).cuda(), torch.from_numpy(sin).cuda(), P + 64
+        self.bufs = {}
+        self.f16 = f16
+        self.bytes = self.layers.bytes * n_layers + V * H * 2
+
+    def buffers(self, M: int):
+        if M not in self.bufs:
+            f16, H = self.f16, self.H
+            if M > 1:
+                parent, _, mask = I.make_tree(I.seed_for(5, 0) + 7, M, 6, 4)
+            else:
+                parent, mask = np.array([-1]), np.ones((1, 1), dtype=np.uint8)
+            b = {"h0": torch.from_numpy(I.make_hidden(777 + M, M, H)).cuda(), "h": f16(M, H), "hn": f16(M, H),
+                 "mask": torch.from_numpy(mask).cuda(), "pos": torch.from_numpy(I.tree_positions(parent, self.P)).cuda(),
+                 "logits": torch.empty((M, self.V), dtype=torch.float32, device="cuda"),
+                 "top_idx": torch.empty((M, 1), dtype=torch.int32, device="cuda"),
+                 "top_lp": torch.empty((M, 1), dtype=torch.float32, device="cuda"),
+                 "aws": B.new_workspace(B.tree_verify_attn_workspace_bytes(M, self.P, self.Hq, self.Hkv, self.D)),
+                 "lws": torch.empty(B.lm_head_workspace_bytes(M, self.V, H, 1), dtype=torch.uint8, device="cuda")}
+            b["scratch"] = B.layer_scratch(f16(M, H), f16(M, self.Nqkv), f16(M, self.Hq, self.D), f16(M, self.Hq, self.D),
+                                           f16(M, self.F), self.layers.ws, b["aws"])
+            b["keep"] = []   # the scratch struct holds raw pointers: keep the tensors alive
+            self.bufs[M] = b
+        return self.bufs[M]
+
+    def forward(self, M: int):
+        b, L = self.buffers(M), self.layers
+        b["h"].copy_(b["h0"])   # the embedding lookup's stand-in: a fresh hidden state per pass
+        for l in range(self.n_layers):
+            w = L.packed[l]
+            weights = B.layer_weights(w[0], w[1], w[2], w[3], self.g[0], self.g[1], self.H, self.Hq, self.Hkv, self.D,
+                                      self.F, 1e-5)
+            B.w4a16_decoder_layer(weights, b["h"], M, self.P, b["pos"], self.cos, self.sin, self.n_pos, b["mask"],
+                                  self.k[l], self.v[l], b["scratch"])
+        B.rms_norm(b["h"], self.g[2], b["hn"], M, self.H, 1e-5)
+        # greedy target tokens of all M rows
+        B.lm_head_topk(b["hn"], self.head, M, self.V, self.H, 1, b["logits"], b["top_idx"], b["top_lp"], b["lws"])
+
+
+def model_leg(name: str, shapes, n_layers: int, Hq: int, Hkv: int, Ms, args, use_graph: bool) -> dict:
+    """One whole forward pass of the target per step (all layers with their own weights and caches, final
+    norm, LM head with greedy tokens): T_t at M = 1 and T_v(M) measured, not extrapolated from one layer."""
+    model = Model(shapes, n_layers, Hq, Hkv, 128, 2048, seed=1000 + n_layers)
+    out = {}
+    for M in Ms:
+        steps, warm = max(5, min(args.steps, 20)), 3
+        ms = time_steps(lambda c, M=M: model.forward(M), steps, warm, use_graph, 1)
+        out[str(M)] = {"ms_per_forward": ms}
+        log(f"{name} whole model M={M}: {ms:.3f} ms per forward pass")
+    t_t = out["1"]["ms_per_forward"]
+    for M in Ms:
+        out[str(M)]["ratio_vs_M1"] = out[str(M)]["ms_per_forward"] / t_t
+    out["plain_decoding_tokens_per_s"] = 1e3 / t_t
+    out["weight_GBps_at_M1"] = model.bytes / t_t / 1e6
+    out["note"] = (f"{n_layers} decoder layers + final norm + fp16 LM head (greedy tokens for all rows), prefix 2048, "
+                   "one HIP graph per pass")
+    del model
+    torch.cuda.empty_cache()
+    return out
+
+
 # Expected accepted length tau(n, d) of EAGLE-2 on the W4A16 targets, read off the paper's figures
 # "Accepted Length (70B, A100)" and "Accepted Length (8B, A100)" (W4A16 series; tree size n: (d draft
 # passes, tau)), and the same figure groups' verification-to-decoding time ratios on an A100.
@@ -157,14 +240,16 @@ PAPER_RATIO_8B_W4A16_A100 = {30: 1.317, 40: 1.548, 50: 1.790, 60: 1.803}
 
 
 def eq1_projection(layer_ms: dict, read_GBps: float, *, shapes=None, n_layers: int = 80, tau=None, paper_ratio=None,
-                   lm_head_ms: float | None = None, draft_lm_head_ms: float | None = None) -> dict:
+                   lm_head_ms: float | None = None, draft_lm_head_ms: float | None = None, model_ms: dict | None = None) -> dict:
     """The paper's speedup model (Eq. 1), T_sd/T_t = (d T_d/T_t + T_v(n)/T_t) / tau(n, d), fed with
     this GPU's measured decoder-layer times for T_v(n)/T_t and the paper's tau.  The draft model is
     not built here: its time is ESTIMATED as the bytes one pass of an EAGLE-2 draft has to stream (one
     fp16 decoder layer of the target's shape and the 2H->H fusion layer) at the plain-read rate
     measured above, plus the fp16 LM head -- measured with lm_head_topk when given (draft_lm_head_ms
     for the draft's beam, lm_head_ms for the target's own head, added to both T_t and T_v), else
-    estimated from its bytes too.  A projection for context, not a measurement of speculative decoding."""
+    estimated from its bytes too.  With model_ms (ms per whole forward pass by M, as measured by model_leg)
+    T_t and T_v(n) are those measured passes instead of n_layers x one layer + head.  A projection for
+    context, not a measurement of speculative decoding."""
     shapes = I.LLAMA3_70B if shapes is None else shapes
     tau = PAPER_TAU_70B_W4A16 if tau is None else tau
     paper_ratio = PAPER_RATIO_70B_W4A16_A100 if paper_ratio is None else paper_ratio
@@ -174,14 +259,15 @@ def eq1_projection(layer_ms: dict, read_GBps: float, *, shapes=None, n_layers: i
     lm_t = head_by_bytes if lm_head_ms is None else lm_head_ms
     lm_d = head_by_bytes if draft_lm_head_ms is None else draft_lm_head_ms
     draft_ms = (layer_params * 2 + 2 * H * H * 2) / (read_GBps * 1e6) + lm_d
-    t_t = layer_ms[1] * n_layers + lm_t
+    t_t = model_ms[1] if model_ms else layer_ms[1] * n_layers + lm_t
     out = {"inputs": {"tau": "paper, figures 'Accepted Length (70B / 8B, A100)', W4A16 series",
-                      "T_v_over_T_t": f"measured here: {n_layers} x decoder layer (prefix 2048) + fp16 LM head",
+                      "T_v_over_T_t": ("measured here: whole forward passes (all layers, final norm, LM head with greedy tokens)"
+                                       if model_ms else f"measured here: {n_layers} x decoder layer (prefix 2048) + fp16 LM head"),
                       "T_d": "fp16 draft layer estimated from bytes at the measured plain-read rate, not measured",
                       "lm_head": "measured (lm_head_topk)" if lm_head_ms is not None else "estimated from bytes",
                       "T_t_ms": t_t, "T_d_ms_estimated": draft_ms, "lm_head_ms": lm_t}}
     for n, (d, ta) in tau.items():
-        t_v = layer_ms[n] * n_layers + lm_t
+        t_v = model_ms[n] if model_ms else layer_ms[n] * n_layers + lm_t
         out[str(n)] = {"d": d, "tau_paper": ta, "T_v_over_T_t": t_v / t_t,
                        "T_v_over_T_t_paper_A100": paper_ratio[n],
                        "speedup_over_own_autoregressive_no_draft_cost": ta / (t_v / t_t),
@@ -209,7 +295,7 @@ def lm_head_leg(args, use_graph: bool) -> dict:
         steps, warm = min(args.steps, 60), min(args.warmup, 6)
         ms_read = time_steps(lambda c: B.w4a16_read_probe(Ws[c], nbytes, sink), steps, warm, use_graph, 2)
         lm[str(K)] = {"weight_bytes": nbytes, "plain_read_us": ms_read * 1e3, "plain_read_GBps": nbytes / ms_read / 1e6}
-        for M in (1, 10):
+        for M in (1, 10, 60):
             x = torch.randn((M, K), device="cuda", generator=gen).to(torch.float16)
             logits = torch.empty((M, V), dtype=torch.float32, device="cuda")
             ti = torch.empty((M, top_k), dtype=torch.int32, device="cuda")
@@ -435,8 +521,6 @@ def main():
         lm = lm_head_leg(args, use_graph)
         extra["lm_head_topk_V128256"] = lm
         read_rate = plain["gate_up"]["GBps"]
-        extra["eq1_projection_70b"] = eq1_projection(dl, read_rate, lm_head_ms=lm["8192"]["M1"]["us"] * 1e-3,
-                                                     draft_lm_head_ms=lm["8192"]["M10"]["us"] * 1e-3)
         small = Layer(I.LLAMA3_8B, 6, seed=8)   # 6 x 113 MB: never re-read within 512 MB
         s8 = {}
         for M in I.M_SWEEP_8B:
@@ -452,11 +536,20 @@ def main():
             del layer
         extra["llama3_8b_decoder_layer_P2048"] = {
             str(M): {"us_per_layer": ms * 1e3, "ratio_vs_M1": ms / dl8[1], "ms_per_32_layers": ms * 32} for M, ms in dl8.items()}
+        bytes8 = small.bytes
+        del small
+        torch.cuda.empty_cache()
+        m70 = model_leg("70B", I.LLAMA3_70B, 80, 64, 8, (1, 8, 24, 32, 40, 48, 60), args, use_graph)
+        m8 = model_leg("8B", I.LLAMA3_8B, 32, 32, 8, (1, 8, 30, 40, 50, 60), args, use_graph)
+        extra["llama3_70b_model_P2048"], extra["llama3_8b_model_P2048"] = m70, m8
+        by_m = lambda leg: {int(k): v["ms_per_forward"] for k, v in leg.items() if k.isdigit()}
+        extra["eq1_projection_70b"] = eq1_projection(dl, read_rate, lm_head_ms=lm["8192"]["M1"]["us"] * 1e-3,
+                                                     draft_lm_head_ms=lm["8192"]["M10"]["us"] * 1e-3, model_ms=by_m(m70))
         extra["eq1_projection_8b"] = eq1_projection(dl8, read_rate, shapes=I.LLAMA3_8B, n_layers=32, tau=PAPER_TAU_8B_W4A16,
                                                     paper_ratio=PAPER_RATIO_8B_W4A16_A100,
                                                     lm_head_ms=lm["4096"]["M1"]["us"] * 1e-3,
-                                                    draft_lm_head_ms=lm["4096"]["M10"]["us"] * 1e-3)
-        extra["llama3_8b_layer"] = {str(M): {"us_per_layer": ms * 1e3, "weight_GBps": small.bytes / ms / 1e6,
+                                                    draft_lm_head_ms=lm["4096"]["M10"]["us"] * 1e-3, model_ms=by_m(m8))
+        extra["llama3_8b_layer"] = {str(M): {"us_per_layer": ms * 1e3, "weight_GBps": bytes8 / ms / 1e6,
                                             "ratio_vs_M1": ms / s8[1]} for M, ms in s8.items()}
         bytes70 = sum(weight_bytes(K, N) for (_, K, N) in I.LLAMA3_70B)
         extra["llama3_70b_layer"] = {str(M): {"us_per_layer": ms * 1e3, "weight_GBps": bytes70 / ms / 1e6,

@@ -67,8 +67,8 @@ const char *w4a16_strerror(int code);
  * "attn_pack" (0 = the query heads that share a KV head share one 64-row tile whenever
  * M * Hq/Hkv <= 64, 1 = one tile per query head always), "attn_row_tiles" (0 = chosen by the
  * number of rows in a tile; 2 = a wavefront of tree_verify_attn carries 32 query rows, in two row groups
- * for taller tiles; 4 = 64 rows, one wavefront per SIMD), "lm_tiles" (0 = heuristic, else 1 or 2
- * vocabulary tiles per wavefront in lm_head_topk).
+ * for taller tiles; 4 = 64 rows, one wavefront per SIMD), "lm_tiles" (0 = heuristic, else 1, 2 or
+ * -- for more than 16 rows -- 4 vocabulary tiles per wavefront in lm_head_topk).
  * Returns W4A16_EINVAL for an unknown name or an out-of-range value.  Not thread-safe. */
 int w4a16_set_param(const char *name, int value);
 int w4a16_get_param(const char *name);
@@ -254,7 +254,8 @@ size_t lm_head_workspace_bytes(int M, int V, int K, int top_k);
 /* Draft-side language-model head with log-softmax and top-k (paper section 2.1: the draft model uses
  * the target's LM head and grows its beam-search tree from the softmax output; section 3.1: the draft
  * stays in fp16 because this head and its softmax dominate drafting and cannot be quantised).
- *   x        fp16 [M, K]   draft hidden states, 1 <= M <= 16
+ *   x        fp16 [M, K]   hidden states, 1 <= M <= 64 (a draft beam; or the rows of a verification pass,
+ *                          whose target tokens are the top-1 of the target model's own head)
  *   packed   the LM-head weight W fp16 [V, K] as laid out by lm_head_pack
  *   logits   fp32 [M, V]   out: logits[m, v] = sum_k x[m, k] W[v, k], fp32 accumulation
  *   top_idx  int32 [M, top_k], top_logprob fp32 [M, top_k]   out: per row the top_k tokens by logit,

@@ -43,7 +43,7 @@ __global__ void lm_head_pack_kernel(const _Float16 *__restrict__ W, u32x4 *__res
 // both.  Tiles lie K * 32 bytes apart, a power of two for the usual hidden sizes:
 // wavefronts that all walked k from 0 would ask the same few memory channels at any moment, so each
 // starts at macro step (tile mod steps) and wraps around.
-template <bool EVEN, int TWL>
+template <bool EVEN, int TWL, int MTL, int DEPTH>
 __global__ __launch_bounds__(256) void lm_head_logits_kernel(const _Float16 *__restrict__ x,
                                                              const u32x4 *__restrict__ packed,
                                                              float *__restrict__ logits, int M, int V, int K, int tiles)
@@ -58,8 +58,10 @@ __global__ __launch_bounds__(256) void lm_head_logits_kernel(const _Float16 *__r
 #pragma unroll
     for (int t = 0; t < TWL; ++t)   // a tile past the end repeats the last one; its logits are not stored
         wp[t] = packed + (size_t)min(tile0 + t, tiles - 1) * (K / 32) * 64 + lane;
-    const u32x4 *xp = reinterpret_cast<const u32x4 *>(x + (size_t)min(c, M - 1) * K + 8 * r);
-    u32x4 w[kLmDepth][TWL][4], xf[kLmDepth][4];
+    const u32x4 *xp[MTL];           // MTL row tiles of 16 hidden-state rows; rows >= M repeat row M-1, never stored
+#pragma unroll
+    for (int mt = 0; mt < MTL; ++mt) xp[mt] = reinterpret_cast<const u32x4 *>(x + (size_t)min(mt * 16 + c, M - 1) * K + 8 * r);
+    u32x4 w[DEPTH][TWL][4], xf[DEPTH][MTL][4];
     const int rot = (tile0 / TWL) % steps;
     auto load = [&](int s, int slot) {
         int sr = s + rot;              // uniform
@@ -68,62 +70,70 @@ __global__ __launch_bounds__(256) void lm_head_logits_kernel(const _Float16 *__r
         for (int j = 0; j < 4; ++j) {
 #pragma unroll
             for (int t = 0; t < TWL; ++t) w[slot][t][j] = __builtin_nontemporal_load(wp[t] + (sr * 4 + j) * 64);
-            xf[slot][j] = xp[(sr * 4 + j) * 4];
+#pragma unroll
+            for (int mt = 0; mt < MTL; ++mt) xf[slot][mt][j] = xp[mt][(sr * 4 + j) * 4];
         }
     };
-    float4v acc[TWL];
+    float4v acc[TWL][MTL];
 #pragma unroll
-    for (int t = 0; t < TWL; ++t) acc[t] = (float4v){0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < TWL; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MTL; ++mt) acc[t][mt] = (float4v){0.f, 0.f, 0.f, 0.f};
     auto compute = [&](int slot) {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int t = 0; t < TWL; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, w[slot][t][j]),
-                                                                __builtin_bit_cast(half8v, xf[slot][j]), acc[t], 0, 0, 0);
+#pragma unroll
+                for (int mt = 0; mt < MTL; ++mt)
+                    acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, w[slot][t][j]),
+                                                                        __builtin_bit_cast(half8v, xf[slot][mt][j]),
+                                                                        acc[t][mt], 0, 0, 0);
     };
     if constexpr (EVEN) {   // steps is a multiple of the ring depth: every load of the steady state is unconditional
 #pragma unroll
-        for (int u = 0; u < kLmDepth; ++u) load(u, u);
+        for (int u = 0; u < DEPTH; ++u) load(u, u);
         int s0 = 0;
-        for (; s0 + kLmDepth < steps; s0 += kLmDepth) {
+        for (; s0 + DEPTH < steps; s0 += DEPTH) {
 #pragma unroll
-            for (int u = 0; u < kLmDepth; ++u) {
+            for (int u = 0; u < DEPTH; ++u) {
                 compute(u);
-                load(s0 + u + kLmDepth, u);
+                load(s0 + u + DEPTH, u);
             }
         }
 #pragma unroll
-        for (int u = 0; u < kLmDepth; ++u) compute(u);
+        for (int u = 0; u < DEPTH; ++u) compute(u);
     } else {
 #pragma unroll
-        for (int u = 0; u < kLmDepth; ++u)
+        for (int u = 0; u < DEPTH; ++u)
             if (u < steps) load(u, u);
-        for (int s0 = 0; s0 < steps; s0 += kLmDepth) {
+        for (int s0 = 0; s0 < steps; s0 += DEPTH) {
 #pragma unroll
-            for (int u = 0; u < kLmDepth; ++u) {
+            for (int u = 0; u < DEPTH; ++u) {
                 if (s0 + u < steps) {   // uniform
                     compute(u);
-                    if (s0 + u + kLmDepth < steps) load(s0 + u + kLmDepth, u);
+                    if (s0 + u + DEPTH < steps) load(s0 + u + DEPTH, u);
                 }
             }
         }
     }
-    // lane (r, c) holds the logits of tokens 16 tile + 4 r .. + 3 for hidden-state row c
+    // lane (r, c) holds the logits of tokens 16 tile + 4 r .. + 3 for hidden-state row 16 mt + c
 #pragma unroll
-    for (int t = 0; t < TWL; ++t) {
-        const int v0 = (tile0 + t) * 16 + 4 * r;
-        if (c < M && tile0 + t < tiles) {
-            float *dst = logits + (size_t)c * V + v0;
-            if ((V & 3) == 0 && v0 + 3 < V) {
-                *reinterpret_cast<float4v *>(dst) = acc[t];
-            } else {
+    for (int t = 0; t < TWL; ++t)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (v0 + i < V) dst[i] = acc[t][i];
+        for (int mt = 0; mt < MTL; ++mt) {
+            const int v0 = (tile0 + t) * 16 + 4 * r, row = mt * 16 + c;
+            if (row < M && tile0 + t < tiles) {
+                float *dst = logits + (size_t)row * V + v0;
+                if ((V & 3) == 0 && v0 + 3 < V) {
+                    *reinterpret_cast<float4v *>(dst) = acc[t][mt];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (v0 + i < V) dst[i] = acc[t][mt][i];
+                }
             }
         }
-    }
 }
 
 // (value, token) pairs ordered by value, equal values by ascending token
@@ -331,7 +341,7 @@ static int check_lm_head(int M, int V, int K, int top_k)
 {
     if (M < 1 || V < 1 || K < 1 || top_k < 1 || top_k > V) return W4A16_EINVAL;
     if (K % kLmStepK != 0) return W4A16_EINVAL;
-    if (M > 16 || top_k > kLmMaxTopK) return W4A16_EUNSUP;
+    if (M > W4A16_MAX_M || top_k > kLmMaxTopK) return W4A16_EUNSUP;
     if (lm_chunks(V) > 64 * kLmListsPerLane || (long long)lm_chunks(V) * top_k > kLmMaxCandidates) return W4A16_EUNSUP;
     return W4A16_OK;
 }
@@ -389,23 +399,36 @@ int lm_head_topk(const void *x, const void *packed, int M, int V, int K, int top
         lds_ok = true;
     }
     hipStream_t s = (hipStream_t)stream;
-    const bool even = (K / kLmStepK) % kLmDepth == 0;
-    // tiles per wavefront: two halve the x-fragment traffic from L2, which matters once the hidden-state
-    // rows differ (M = 16: 240 -> 194 us at K = 4096); a single row is a broadcast and runs best with one
-    const int twl = params().lm_tiles > 0 ? params().lm_tiles : (M <= 4 ? 1 : 2);
+    // tiles per wavefront: every x fragment fetched from L2 serves all of them, which matters once the
+    // hidden-state rows differ (K = 4096: M = 16 240 -> 194 us with two, M = 60 567 -> 278 us with four); a
+    // single row is a broadcast and runs best with one.  More than 16 rows: up to four row tiles and a
+    // ring of two macro steps (registers).
+    const int mtl = (M + 15) / 16;
+    const int twl = params().lm_tiles > 0 ? params().lm_tiles : (M <= 4 ? 1 : M <= 16 ? 2 : 4);
+    if (twl != 1 && twl != 2 && !(twl == 4 && mtl >= 2)) return W4A16_EUNSUP;
+    const int depth = mtl > 1 ? 2 : kLmDepth;
+    const bool even = (K / kLmStepK) % depth == 0;
     const dim3 grid((unsigned)((tiles + 4 * twl - 1) / (4 * twl)));
-#define W4_LM_LAUNCH(EVEN_, TWL_)                                                                                       \
-    hipLaunchKernelGGL((lm_head_logits_kernel<EVEN_, TWL_>), grid, dim3(256), 0, s, (const _Float16 *)x,                \
-                       (const u32x4 *)packed, logits, M, V, K, tiles)
-    if (twl == 1) {
-        if (even) W4_LM_LAUNCH(true, 1);
-        else W4_LM_LAUNCH(false, 1);
-    } else if (twl == 2) {
-        if (even) W4_LM_LAUNCH(true, 2);
-        else W4_LM_LAUNCH(false, 2);
-    } else {
-        return W4A16_EUNSUP;
-    }
+#define W4_LM_LAUNCH(TWL_, MTL_, DEPTH_)                                                                                \
+    do {                                                                                                                \
+        if (even)                                                                                                       \
+            hipLaunchKernelGGL((lm_head_logits_kernel<true, TWL_, MTL_, DEPTH_>), grid, dim3(256), 0, s,                \
+                               (const _Float16 *)x, (const u32x4 *)packed, logits, M, V, K, tiles);                     \
+        else                                                                                                            \
+            hipLaunchKernelGGL((lm_head_logits_kernel<false, TWL_, MTL_, DEPTH_>), grid, dim3(256), 0, s,               \
+                               (const _Float16 *)x, (const u32x4 *)packed, logits, M, V, K, tiles);                     \
+    } while (0)
+    if (mtl == 1 && twl == 1) W4_LM_LAUNCH(1, 1, kLmDepth);
+    else if (mtl == 1) W4_LM_LAUNCH(2, 1, kLmDepth);
+    else if (mtl == 2 && twl == 1) W4_LM_LAUNCH(1, 2, 2);
+    else if (mtl == 2 && twl == 2) W4_LM_LAUNCH(2, 2, 2);
+    else if (mtl == 2) W4_LM_LAUNCH(4, 2, 2);
+    else if (mtl == 3 && twl == 1) W4_LM_LAUNCH(1, 3, 2);
+    else if (mtl == 3 && twl == 2) W4_LM_LAUNCH(2, 3, 2);
+    else if (mtl == 3) W4_LM_LAUNCH(4, 3, 2);
+    else if (twl == 1) W4_LM_LAUNCH(1, 4, 2);
+    else if (twl == 2) W4_LM_LAUNCH(2, 4, 2);
+    else W4_LM_LAUNCH(4, 4, 2);
 #undef W4_LM_LAUNCH
     hipLaunchKernelGGL(lm_head_chunk_kernel, dim3((unsigned)((chunks + kLmThreads / 64 - 1) / (kLmThreads / 64)), (unsigned)M), dim3(kLmThreads), 0, s,
                        (const float *)logits, V, top_k, chunks, chunk_max, chunk_sum, cand_val, cand_idx);

@@ -156,7 +156,7 @@ def test_lm_head_validation_happens_before_any_gpu_call():
     EINVAL, ENULL, EALIGN, EUNSUP, EWS = -1, -2, -3, -4, -5
     f = lib.lm_head_topk
     assert f(a, a, 0, 1000, 4096, 10, a, a, a, a, 1 << 30, None) == EINVAL        # M = 0
-    assert f(a, a, 17, 1000, 4096, 10, a, a, a, a, 1 << 30, None) == EUNSUP       # more than one row tile
+    assert f(a, a, 65, 1000, 4096, 10, a, a, a, a, 1 << 30, None) == EUNSUP       # more than four row tiles
     assert f(a, a, 4, 1000, 4000, 10, a, a, a, a, 1 << 30, None) == EINVAL        # K % 128
     assert f(a, a, 4, 8, 4096, 10, a, a, a, a, 1 << 30, None) == EINVAL           # top_k > V
     assert f(a, a, 4, 1000, 4096, 65, a, a, a, a, 1 << 30, None) == EUNSUP
@@ -173,7 +173,7 @@ def test_lm_head_validation_happens_before_any_gpu_call():
     assert lib.lm_head_pack(None, a, 1000, 128, None) == ENULL
     assert lib.lm_head_pack(a, a + 4, 1000, 128, None) == EALIGN
     assert B.lm_head_workspace_bytes(10, 128256, 4096, 10) > 0
-    assert B.lm_head_workspace_bytes(17, 128256, 4096, 10) == 0
+    assert B.lm_head_workspace_bytes(65, 128256, 4096, 10) == 0
 
 
 def test_decoder_layer_validation_happens_before_any_gpu_call():

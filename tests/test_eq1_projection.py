@@ -43,3 +43,13 @@ def test_projection_with_measured_heads_and_the_8b_tables():
     ratio = (32 * 0.070 + 0.175) / t_t
     assert row["d"] == 6 and abs(row["T_v_over_T_t"] - ratio) < 1e-12 and row["T_v_over_T_t_paper_A100"] == 1.803
     assert abs(row["speedup_over_own_autoregressive_estimated_draft"] - 4.046 / (6 * draft_ms / t_t + ratio)) < 1e-12
+
+
+def test_projection_from_whole_model_passes():
+    model_ms = {1: 9.0, 24: 11.7, 32: 12.6, 40: 14.4, 48: 14.4 * 1.1}
+    out = bench.eq1_projection({}, 6500.0, lm_head_ms=0.33, draft_lm_head_ms=0.35, model_ms=model_ms)
+    assert out["inputs"]["T_t_ms"] == 9.0
+    assert abs(out["24"]["T_v_over_T_t"] - 11.7 / 9.0) < 1e-12
+    d, tau = bench.PAPER_TAU_70B_W4A16[48]
+    draft = out["inputs"]["T_d_ms_estimated"]
+    assert abs(out["48"]["speedup_over_own_autoregressive_estimated_draft"] - tau / (d * draft / 9.0 + model_ms[48] / 9.0)) < 1e-12

@@ -68,13 +68,14 @@ def check(x, W, top_k, what):
 
 @pytest.mark.parametrize("M,K,V,top_k", [
     (1, 128, 16, 3), (3, 384, 1001, 7), (16, 512, 4096, 10), (10, 1024, 5000, 1), (7, 2048, 2049, 64),
-    (2, 4096, 32000, 32), (16, 8192, 6000, 10),
+    (2, 4096, 32000, 32), (16, 8192, 6000, 10), (17, 1024, 3000, 4), (40, 2048, 4104, 10), (48, 384, 2000, 3),
+    (64, 4096, 8000, 10), (60, 8192, 2048, 1),
 ])
 def test_lm_head_parity(M, K, V, top_k):
     print(f"lm_head M={M} K={K} V={V} top_k={top_k}", flush=True)
     x, W = I.make_lm_head(9500 + M + K + V, M, K, V)
     try:
-        for tiles_per_wave in (0, 1, 2):
+        for tiles_per_wave in (0, 1, 2) + ((4,) if M > 16 else ()):
             B.w4a16_set_param("lm_tiles", tiles_per_wave)
             e = check(x, W, top_k, f"M={M} K={K} V={V} k={top_k} tiles per wavefront {tiles_per_wave}")
     finally:
