@@ -24,9 +24,20 @@ constexpr int kRowsPad = 64;
 constexpr int attn_lds_bytes(int rt, int rg) { return 4 * rg * (8 * rt * 4 + 2 * rt) * 64 * 4; }
 constexpr int kMaxSplits = 16;   // key ranges per head (the merge keeps one value per range in registers)
 
-__device__ __forceinline__ float xor_max(float v, int lane_mask)
+// Maximum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (the lanes that share a query row), returned to
+// all four.  v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of
+// its second, v_permlane32_swap the upper half of the first with the lower half of the second; applied
+// to two copies of a value each leaves the two partners of a pair side by side in the two registers.
+// They run on the vector ALU: no LDS round trip as with a cross-lane shuffle.  (Written in assembly:
+// the compiler's builtin folded the maximum of the two results into one of them.)
+__device__ __forceinline__ float row_group_max(float v)
 {
-    return fmaxf(v, __shfl_xor(v, lane_mask, 64));
+    float a = v, b = v;
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    a = fmaxf(a, b);
+    b = a;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    return fmaxf(a, b);
 }
 
 constexpr float kLowest = -1.0e30f;   // "no key seen yet": finite, so differences of two of them are 0, not NaN
@@ -208,8 +219,7 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
             float m_blk = s[0];
 #pragma unroll
             for (int i = 1; i < 8; ++i) m_blk = fmaxf(m_blk, s[i]);
-            m_blk = xor_max(m_blk, 16);
-            m_blk = xor_max(m_blk, 32);
+            m_blk = row_group_max(m_blk);
             const float m_new = fmaxf(m_run[rt], m_blk);
             const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
             float psum = 0.f;
