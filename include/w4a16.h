@@ -67,7 +67,9 @@ const char *w4a16_strerror(int code);
  * "attn_pack" (0 = the query heads that share a KV head share one 64-row tile whenever
  * M * Hq/Hkv <= 64, 1 = one tile per query head always), "attn_row_tiles" (0 = chosen by the
  * number of rows in a tile; 2 = a wavefront of tree_verify_attn carries 32 query rows, in two row groups
- * for taller tiles; 4 = 64 rows, one wavefront per SIMD), "lm_tiles" (0 = heuristic, else 1, 2 or
+ * for taller tiles; 4 = 64 rows, one wavefront per SIMD), "attn_fused_merge" (how the key ranges of a
+ * row tile are merged: 2 = by the last of its workgroups to finish, 1 = by a second kernel, 0 = the former while
+ * rows x ranges of a tile stay small), "lm_tiles" (0 = heuristic, else 1, 2 or
  * -- for more than 16 rows -- 4 vocabulary tiles per wavefront in lm_head_topk).
  * Returns W4A16_EINVAL for an unknown name or an out-of-range value.  Not thread-safe. */
 int w4a16_set_param(const char *name, int value);

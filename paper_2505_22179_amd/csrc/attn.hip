@@ -8,6 +8,7 @@
 // stored with the head dimension contiguous.  Key ranges of different workgroups are combined by
 // a second small kernel, in range order, so the result does not depend on scheduling.
 #include "internal.h"
+#include "devscope.h"
 
 namespace w4 {
 
@@ -42,6 +43,61 @@ __device__ __forceinline__ float row_group_max(float v)
 
 constexpr float kLowest = -1.0e30f;   // "no key seen yet": finite, so differences of two of them are 0, not NaN
 
+// Merge of the key ranges of one tile by the workgroup that finished last (fused mode): NS = compiled
+// upper bound of the number of ranges, IT = items a thread handles at once (all their loads are issued
+// together).  Loads are device-scope: other workgroups, on other XCDs, wrote the partials in this kernel.
+template <int NS, int IT>
+__device__ __forceinline__ void merge_ranges(PartialBuffer unit_o, PartialBuffer unit_ml, _Float16 *__restrict__ out,
+                                             int tid, int threads, int items, int M, int Hq, int nsplit, int rep,
+                                             int unit)
+{
+    const float NEG_INF = -__builtin_inff();
+    for (int base = tid; base < items; base += threads * IT) {
+        float ms[IT][NS], ls[IT][NS];
+        float4v os[IT][NS];
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            const int idx = base + it * threads;
+            const int trow = idx / (kHeadDim / 4), d4 = idx % (kHeadDim / 4);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                ms[it][s] = NEG_INF;
+                ls[it][s] = 0.f;
+                os[it][s] = (float4v){0.f, 0.f, 0.f, 0.f};
+                if (s < nsplit && idx < items) {
+                    ms[it][s] = load_partial_f32(unit_ml, (s * kRowsPad + trow) * 2);
+                    ls[it][s] = load_partial_f32(unit_ml, (s * kRowsPad + trow) * 2 + 1);
+                    os[it][s] = load_partial(unit_o, (s * kRowsPad + trow) * (kHeadDim / 4) + d4);
+                }
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            const int idx = base + it * threads;
+            if (idx >= items) break;
+            const int trow = idx / (kHeadDim / 4), d4 = idx % (kHeadDim / 4);
+            float m_all = NEG_INF;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) m_all = fmaxf(m_all, ms[it][s]);
+            float den = 0.f;
+            float4v num = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                float wgt = (ms[it][s] == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms[it][s] - m_all);
+                den += wgt * ls[it][s];
+                num += wgt * os[it][s];
+            }
+            const float inv = 1.f / den;
+            // tile row -> (query row, head): see tree_attn_kernel
+            const int j = rep ? trow / M : 0;
+            const int qrow = trow - j * M, h = rep ? unit * rep + j : unit;
+            typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+            half4v hv = {(_Float16)(num[0] * inv), (_Float16)(num[1] * inv), (_Float16)(num[2] * inv), (_Float16)(num[3] * inv)};
+            *reinterpret_cast<half4v *>(out + ((size_t)qrow * Hq + h) * kHeadDim + d4 * 4) = hv;
+        }
+    }
+}
+
 // One workgroup = one 64-row tile (a query head, or the heads of a KV group) x one contiguous range
 // of 32-key steps.  Its 4 * RG wavefronts are RG row groups of four: the four wavefronts of a row
 // group split the KEYS -- wavefront kw takes steps kw, kw + 4, ... of the range -- and each carries,
@@ -68,10 +124,17 @@ template <int RT, int RG>
 __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
     const _Float16 *__restrict__ q, const _Float16 *__restrict__ k, const _Float16 *__restrict__ v,
     const uint8_t *__restrict__ mask, _Float16 *__restrict__ out, float *__restrict__ part_o,
-    float *__restrict__ part_ml, int M, int P, int Hq, int Hkv,
-    float scale_log2e, int nsplit, int bq, int brem, int rep)
+    float *__restrict__ part_ml, uint32_t *__restrict__ tickets, int M, int P, int Hq, int Hkv,
+    float scale_log2e, int nsplit, int bq, int brem, int rep, int fused)
 {
     extern __shared__ float4v smem4[];
+    // Every argument is fetched by one batch of scalar loads up front: left to itself the compiler fetches
+    // them block by block where first used, three dependent round trips to the argument buffer (about
+    // a microsecond each) before the first K/V request goes out.
+    const unsigned grid = gridDim.x;
+    asm volatile("" ::"s"(q), "s"(k), "s"(v), "s"(mask), "s"(out), "s"(part_o), "s"(part_ml), "s"(tickets), "s"(M),
+                 "s"(P), "s"(Hq), "s"(Hkv), "s"(scale_log2e), "s"(nsplit), "s"(bq), "s"(brem), "s"(rep), "s"(fused),
+                 "s"(grid));
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kw = wave & 3, rg = wave >> 2;   // key wavefront inside the row group, row group
@@ -80,7 +143,7 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
     // Renumber so that the workgroups of one KV head (consecutive logical ids) share an XCD and
     // its K/V rows are fetched into one L2 instead of all eight.
     int lid = blockIdx.x;
-    if ((gridDim.x & 7) == 0) lid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    if ((grid & 7) == 0) lid = (blockIdx.x & 7) * (grid >> 3) + (blockIdx.x >> 3);
     // A workgroup's 64-row tile holds the M rows of one query head (rep == 0), or -- when they fit --
     // the M rows of all rep query heads that share a KV head (tile row j * M + m = head j of the
     // group, query row m): few-row calls then read K and V once per KV head instead of once per head.
@@ -108,11 +171,15 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) mbits[rt] = 0;
     const bool reaches_draft = b1 * kKeyBlock > P;   // uniform over the workgroup
-    uint8_t mask_byte[16];   // requested first, used after the Q, K and V requests: the oldest loads
+    // Requested first and used after the Q, K and V requests: the oldest loads.  Every lane loads from a
+    // clamped, valid address and discards what lies outside the mask afterwards: a load under a per-lane
+    // condition would be compiled as a branch with its own wait, sixteen memory round trips in a row.
+    uint8_t mask_byte[16];
+    const int mcol = min(lane, M - 1);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int mrow = wave * 16 + i;   // wavefronts 0..3 cover the 64 rows
-        mask_byte[i] = (reaches_draft && mrow < M && lane < M) ? mask[(size_t)mrow * M + lane] : 0;
+        const int mrow = min((wave & 3) * 16 + i, M - 1);   // wavefronts 0..3 cover the 64 rows
+        mask_byte[i] = mask[(size_t)mrow * M + mcol];
     }
     // Q^T fragments (second operand of S^T): lane (r, c) holds q[row, h, 32 j + 8 r .. +7]
     half8v qf[RT][4];
@@ -178,10 +245,10 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
     // One 32-key step.  The K fragments and the V rows of the wavefront's next step are requested
     // into the very registers this step has just emptied (V after its rows are parked in LDS, K after
     // the score products), so one register set each gives a prefetch distance of most of a step.
-    auto step_fn = [&](int step, int next, half8v (&fa)[4], half8v (&fb)[4], u32x4 (&vr)[2][4]) {
-        const int key0 = step * kKeyBlock;
+    auto step_fn = [&](int step, bool more, half8v (&fa)[4], half8v (&fb)[4], u32x4 (&vr)[2][4]) {
+        const int key0 = step * kKeyBlock, next = step + 4;
         park_v(vr);
-        load_v(next, vr);
+        if (more) load_v(next, vr);
         __builtin_amdgcn_sched_barrier(0);
         float4v sa[RT], sb[RT];
 #pragma unroll
@@ -196,7 +263,7 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
                 sa[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[j], qf[rt][j], sa[rt], 0, 0, 0);
                 sb[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb[j], qf[rt][j], sb[rt], 0, 0, 0);
             }
-        load_k(next, fa, fb);
+        if (more) load_k(next, fa, fb);
         __builtin_amdgcn_sched_barrier(0);
         half8v pb[RT];
         const bool prefix_only = key0 + kKeyBlock <= P;   // uniform: committed keys, all visible
@@ -256,7 +323,7 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
     if (reaches_draft) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const uint64_t bits = __ballot(mask_byte[i] != 0);
+            const uint64_t bits = __ballot(mask_byte[i] != 0 && wave * 16 + i < M && lane < M);
             if (lane == 0 && wave < 4) row_bits[wave * 16 + i] = bits;
         }
         __syncthreads();
@@ -264,7 +331,7 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
         for (int rt = 0; rt < RT; ++rt) mbits[rt] = row_bits[row[rt]];
     }
     for (int step = first; step < b1; step += 4)
-        step_fn(step, step + 4 < b1 ? step + 4 : step, ka, kb, vr);   // past the end: the same rows again, unused
+        step_fn(step, step + 4 < b1, ka, kb, vr);
 
     // a row's sum over this wavefront's keys: add the four lanes (r = 0..3) that share the row
 #pragma unroll
@@ -292,6 +359,10 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
     const bool last = nsplit == 1;
     float *po = part_o + (size_t)lid * kRowsPad * kHeadDim;
     float *pml = part_ml + (size_t)lid * kRowsPad * 2;
+    // fused mode: the partials of a tile's key ranges are published with device-scope stores and merged by
+    // the last workgroup of the tile to finish (below)
+    const PartialBuffer unit_o = partial_buffer(part_o + (size_t)unit * nsplit * kRowsPad * kHeadDim);
+    const PartialBuffer unit_ml = partial_buffer(part_ml + (size_t)unit * nsplit * kRowsPad * 2);
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         float ms[4], wgt[4], m_all = kLowest, l_all = 0.f;
@@ -320,18 +391,42 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
                     typedef _Float16 half4v __attribute__((ext_vector_type(4)));
                     half4v hv = {(_Float16)val[0], (_Float16)val[1], (_Float16)val[2], (_Float16)val[3]};
                     *reinterpret_cast<half4v *>(out + ((size_t)row[rt] * Hq + head[rt]) * kHeadDim + dt * 16 + 4 * r) = hv;
+                } else if (fused) {
+                    store_partial(unit_o, (sp * kRowsPad + orow) * (kHeadDim / 4) + dt * 4 + r, val);
                 } else {
                     *reinterpret_cast<float4v *>(po + orow * kHeadDim + dt * 16 + 4 * r) = val;
                 }
             }
         }
         if (!last && kw == 0 && r == 0 && orow < R) {
-            // partial state of this key range: a second kernel merges the ranges (the kernel boundary
-            // makes them visible, at no fence cost)
-            pml[orow * 2] = m_all;
-            pml[orow * 2 + 1] = l_all;
+            // partial state of this key range
+            if (fused) {
+                store_partial_f32(unit_ml, (sp * kRowsPad + orow) * 2, m_all);
+                store_partial_f32(unit_ml, (sp * kRowsPad + orow) * 2 + 1, l_all);
+            } else {   // a second kernel merges the ranges (the kernel boundary makes them visible, at no fence cost)
+                pml[orow * 2] = m_all;
+                pml[orow * 2 + 1] = l_all;
+            }
         }
     }
+    if (last || !fused) return;   // uniform over the grid
+    // The workgroups of a tile take a ticket each once their partials have reached device scope; the one
+    // that draws the last ticket merges the tile's key ranges, in range order, with the arithmetic of
+    // tree_attn_merge_kernel, and leaves the ticket at zero for the next call.
+    __shared__ uint32_t ticket_sh;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (ticket_sh != (uint32_t)(nsplit - 1)) return;
+    if (tid == 0) __hip_atomic_store(&tickets[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int items = R * (kHeadDim / 4);   // one item = four consecutive outputs of a tile row
+    if (nsplit <= 4)
+        merge_ranges<4, 4>(unit_o, unit_ml, out, tid, 256 * RG, items, M, Hq, nsplit, rep, unit);
+    else if (nsplit <= 8)
+        merge_ranges<8, 2>(unit_o, unit_ml, out, tid, 256 * RG, items, M, Hq, nsplit, rep, unit);
+    else
+        merge_ranges<kMaxSplits, 1>(unit_o, unit_ml, out, tid, 256 * RG, items, M, Hq, nsplit, rep, unit);
 }
 
 // merge of the key ranges: one thread per four consecutive output elements, ranges in order;
@@ -517,11 +612,16 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
     const int rows = rep ? M * rep : M;
     const int knob = params().attn_row_tiles;
     const int rt = knob == 4 ? 4 : knob == 2 ? 2 : (rows <= 32 ? 2 : 4), rgroups = (rt == 2 && rows > 32) ? 2 : 1;
+    // the key ranges of a tile are merged by the last of its workgroups to finish, or by a second kernel
+    // (fused: one launch less, but a single workgroup then reads all the partials of its tile, which pays only
+    // while they are few: measured 10.1 against 11.0 us at M = 1, 23.7 against 16.3 us at M = 8, prefix 2048)
+    const int fm = params().attn_fused_merge;
+    const int fused = (ns > 1 && fm != 1 && (fm == 2 || (rep ? M * rep : M) * ns <= 128)) ? 1 : 0;
     rc = launch_attn(rt, rgroups, units * ns, (hipStream_t)stream, (const _Float16 *)q, (const _Float16 *)k,
-                     (const _Float16 *)v, mask, (_Float16 *)out, part_o, part_ml, M, P, Hq, Hkv, scale_log2e, ns,
-                     nblk / ns, nblk % ns, rep);
+                     (const _Float16 *)v, mask, (_Float16 *)out, part_o, part_ml, reinterpret_cast<uint32_t *>(workspace),
+                     M, P, Hq, Hkv, scale_log2e, ns, nblk / ns, nblk % ns, rep, fused);
     if (rc != W4A16_OK) return rc;
-    if (ns > 1) {
+    if (ns > 1 && !fused) {
         const int quads = M * Hq * (kHeadDim / 4);
         const dim3 grid((unsigned)((quads + 255) / 256));
         if (ns <= 4)

@@ -14,6 +14,7 @@
 // fixed order (by the last workgroup to finish a column unit, or by a second kernel), so results
 // do not depend on scheduling.
 #include "internal.h"
+#include "devscope.h"
 
 namespace w4 {
 
@@ -365,25 +366,6 @@ __device__ __forceinline__ KRange k_range(int ks, int gq, int grem)
 {
     const int begin = ks * gq + (ks < grem ? ks : grem);
     return {begin, begin + gq + (ks < grem ? 1 : 0)};
-}
-
-// Coherent-at-device-scope 16-byte accesses for the split-K partials of the last-arriver mode: they
-// bypass the per-XCD L2's non-coherent lines one access at a time, so no whole-cache write-back or
-// invalidate is needed.  The partials of one column unit are addressed through a buffer descriptor
-// (wavefront-uniform base) and the index of the 16-byte quad.
-typedef __amdgpu_buffer_rsrc_t PartialBuffer;
-constexpr int kDeviceScope = 16;   // cache-policy bit sc1
-__device__ __forceinline__ PartialBuffer partial_buffer(const float *base)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0, 0x7FFFFFFF, 0x00020000);
-}
-__device__ __forceinline__ void store_partial(PartialBuffer b, int quad, float4v v)
-{
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), b, quad * 16, 0, kDeviceScope);
-}
-__device__ __forceinline__ float4v load_partial(PartialBuffer b, int quad)
-{
-    return __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(b, quad * 16, 0, kDeviceScope));
 }
 
 // Epilogue shared by the K-split kernels: the NW wavefronts' accumulators are summed through LDS

@@ -60,9 +60,10 @@ __global__ __launch_bounds__(kNormThreads) void rms_norm_kernel(const _Float16 *
 }
 
 // one workgroup per row: thread t owns the element pair (i, i + D/2), i = t % (D/2), of the heads
-// t / (D/2), t / (D/2) + heads_per_pass, ...; its table entry is fetched once and serves every head
+// t / (D/2), t / (D/2) + heads_per_pass, ...; its table entry is fetched once and serves every head.
+// The general form (any even D, tables at any 4-byte alignment).
 constexpr int kRopeThreads = 1024;
-__global__ __launch_bounds__(kRopeThreads) void rope_append_kernel(
+__global__ __launch_bounds__(kRopeThreads) void rope_append_scalar_kernel(
     const _Float16 *__restrict__ qkv, const int32_t *__restrict__ pos, const float *__restrict__ cos_t,
     const float *__restrict__ sin_t, int n_pos, _Float16 *__restrict__ q, _Float16 *__restrict__ k_cache,
     _Float16 *__restrict__ v_cache, int P, int Hq, int Hkv, int D)
@@ -86,6 +87,72 @@ __global__ __launch_bounds__(kRopeThreads) void rope_append_kernel(
             _Float16 *dst = head < Hq ? q + ((size_t)m * Hq + head) * D : k_cache + ((size_t)(P + m) * Hkv + (head - Hq)) * D;
             dst[i] = (_Float16)fmaf(lo, c, -hi * s);
             dst[i + h] = (_Float16)fmaf(hi, c, lo * s);
+        }
+    }
+}
+
+// The form for D % 8 == 0 and 16-byte-aligned tables (every model shape): a thread owns four consecutive
+// pairs (i .. i+3, i + D/2 ..), so D/8 threads cover a head and the workgroup covers 8192 / D heads per
+// pass.  The kernel is a chain of memory round trips and little else, so it is arranged to have as few
+// as possible in a row: all arguments in one batch of scalar loads, then the row's position, and -- not
+// waiting for it -- the data of up to kRopePasses passes; then the table entry; then the stores.  The
+// arithmetic per element is that of the general form.
+constexpr int kRopePasses = 4;
+__global__ __launch_bounds__(kRopeThreads) void rope_append_kernel(
+    const _Float16 *__restrict__ qkv, const int32_t *__restrict__ pos, const float *__restrict__ cos_t,
+    const float *__restrict__ sin_t, int n_pos, _Float16 *__restrict__ q, _Float16 *__restrict__ k_cache,
+    _Float16 *__restrict__ v_cache, int P, int Hq, int Hkv, int D)
+{
+    asm volatile("" ::"s"(qkv), "s"(pos), "s"(cos_t), "s"(sin_t), "s"(n_pos), "s"(q), "s"(k_cache), "s"(v_cache), "s"(P),
+                 "s"(Hq), "s"(Hkv), "s"(D));
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    typedef float float4 __attribute__((ext_vector_type(4)));
+    const int m = blockIdx.x, h = D >> 1;
+    const int lanes = h >> 2;   // threads per head
+    const int heads_per_pass = kRopeThreads / lanes;
+    const int i = (threadIdx.x % lanes) * 4, slot = threadIdx.x / lanes;
+    if (slot >= heads_per_pass) return;
+    const int heads = Hq + 2 * Hkv;
+    const int p = pos[m];
+    const bool in_table = p >= 0 && p < n_pos;   // otherwise this row's q and k are left untouched
+    float4 c = {0.f, 0.f, 0.f, 0.f}, s = c;
+    bool have_table = false;
+    for (int head0 = slot; head0 < heads; head0 += heads_per_pass * kRopePasses) {
+        half4 lo[kRopePasses], hi[kRopePasses];
+#pragma unroll
+        for (int u = 0; u < kRopePasses; ++u) {
+            const int head = head0 + u * heads_per_pass;
+            if (head < heads) {
+                const _Float16 *src = qkv + ((size_t)m * heads + head) * D;
+                lo[u] = *reinterpret_cast<const half4 *>(src + i);
+                hi[u] = *reinterpret_cast<const half4 *>(src + i + h);
+            }
+        }
+        if (in_table && !have_table) {
+            c = *reinterpret_cast<const float4 *>(cos_t + (size_t)p * h + i);
+            s = *reinterpret_cast<const float4 *>(sin_t + (size_t)p * h + i);
+            have_table = true;
+        }
+#pragma unroll
+        for (int u = 0; u < kRopePasses; ++u) {
+            const int head = head0 + u * heads_per_pass;
+            if (head >= heads) break;
+            if (head >= Hq + Hkv) {   // value head: plain copy into the cache
+                _Float16 *dst = v_cache + ((size_t)(P + m) * Hkv + (head - Hq - Hkv)) * D;
+                *reinterpret_cast<half4 *>(dst + i) = lo[u];
+                *reinterpret_cast<half4 *>(dst + i + h) = hi[u];
+            } else if (in_table) {
+                _Float16 *dst = head < Hq ? q + ((size_t)m * Hq + head) * D : k_cache + ((size_t)(P + m) * Hkv + (head - Hq)) * D;
+                half4 olo, ohi;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a = (float)lo[u][e], b = (float)hi[u][e];
+                    olo[e] = (_Float16)fmaf(a, c[e], -b * s[e]);
+                    ohi[e] = (_Float16)fmaf(b, c[e], a * s[e]);
+                }
+                *reinterpret_cast<half4 *>(dst + i) = olo;
+                *reinterpret_cast<half4 *>(dst + i + h) = ohi;
+            }
         }
     }
 }
@@ -118,7 +185,8 @@ int rope_append(const void *qkv, const int32_t *pos, const float *cos_table, con
     if ((reinterpret_cast<uintptr_t>(pos) & 3u) || (reinterpret_cast<uintptr_t>(cos_table) & 3u) ||
         (reinterpret_cast<uintptr_t>(sin_table) & 3u))
         return W4A16_EALIGN;
-    hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)M), dim3(kRopeThreads), 0,
+    const bool wide = D % 8 == 0 && !misaligned(cos_table) && !misaligned(sin_table);
+    hipLaunchKernelGGL(wide ? rope_append_kernel : rope_append_scalar_kernel, dim3((unsigned)M), dim3(kRopeThreads), 0,
                        (hipStream_t)stream, (const _Float16 *)qkv, pos, cos_table, sin_table, n_pos, (_Float16 *)q,
                        (_Float16 *)k_cache, (_Float16 *)v_cache, P, Hq, Hkv, D);
     return launch_status();

@@ -196,6 +196,7 @@ static int *param_slot(const char *name)
     if (!strcmp(name, "fused_reduce")) return &p.fused_reduce;
     if (!strcmp(name, "attn_splits")) return &p.attn_splits;
     if (!strcmp(name, "attn_pack")) return &p.attn_pack;
+    if (!strcmp(name, "attn_fused_merge")) return &p.attn_fused_merge;
     if (!strcmp(name, "lm_tiles")) return &p.lm_tiles;
     if (!strcmp(name, "attn_row_tiles")) return &p.attn_row_tiles;
     if (!strcmp(name, "tiles_per_wave")) return &p.tiles_per_wave;

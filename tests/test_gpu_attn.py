@@ -18,6 +18,7 @@ def _reset_knobs():
     B.w4a16_set_param("attn_splits", 0)
     B.w4a16_set_param("attn_pack", 0)
     B.w4a16_set_param("attn_row_tiles", 0)
+    B.w4a16_set_param("attn_fused_merge", 0)
 
 
 def run_attn(a: I.AttnInputs, ws=None):
@@ -69,9 +70,16 @@ def test_attn_parity(M, P, Hq, Hkv, tree):
         B.w4a16_set_param("attn_pack", pack)
         for row_tiles in (0, 2, 4):   # by tile height; 32 rows per wavefront (one or two row groups); all 64
             B.w4a16_set_param("attn_row_tiles", row_tiles)
-            for splits in (0, 1, 3, 16):
+            for splits in (0, 1, 3, 6, 16):
                 B.w4a16_set_param("attn_splits", splits)
-                stats = check(run_attn(a), ref64, f"M={M} P={P} {tree} splits={splits} pack={pack} row_tiles={row_tiles}")
+                B.w4a16_set_param("attn_fused_merge", 2)   # the last workgroup of a tile merges its key ranges
+                got = run_attn(a)
+                stats = check(got, ref64, f"M={M} P={P} {tree} splits={splits} pack={pack} row_tiles={row_tiles}")
+                B.w4a16_set_param("attn_fused_merge", 1)   # a second kernel does: the same arithmetic in the same order
+                two = run_attn(a)
+                assert np.array_equal(two.view(np.uint16), got.view(np.uint16)), (splits, pack, row_tiles)
+                B.w4a16_set_param("attn_fused_merge", 0)   # chosen by size
+                assert np.array_equal(run_attn(a).view(np.uint16), got.view(np.uint16)), (splits, pack, row_tiles)
     print("   ", stats, flush=True)
 
 
@@ -80,6 +88,12 @@ def test_attn_determinism_and_workspace_reuse():
     ws = B.new_workspace(B.tree_verify_attn_workspace_bytes(a.M, a.P, a.Hq, a.Hkv, a.D))
     first = run_attn(a, ws)
     for _ in range(4):
+        assert np.array_equal(run_attn(a, ws).view(np.uint16), first.view(np.uint16))
+    # the fused merge leaves its tickets at zero: the same workspace serves calls of other shapes in between
+    b = I.make_attn(8101, 8, 500, 64, 8, 128)
+    ref_b, _ = R.tree_verify_attn(b.q, b.k, b.v, b.mask, b.scale)
+    for _ in range(2):
+        check(run_attn(b, ws), ref_b, "shared workspace, second shape")
         assert np.array_equal(run_attn(a, ws).view(np.uint16), first.view(np.uint16))
 
 

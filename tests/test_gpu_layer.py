@@ -267,6 +267,41 @@ def test_rope_append(M, P, Hq, Hkv, D):
     assert np.array_equal(ko[:P].view(np.uint16), kc[:P].view(np.uint16)) and np.array_equal(ko[P + M:].view(np.uint16), kc[P + M:].view(np.uint16))
 
 
+@pytest.mark.parametrize("D,table_offset", [(10, 0), (16, 1), (128, 3)])
+def test_rope_append_general_form(D, table_offset):
+    """Head dimensions that are not multiples of 8, and tables that are only 4-byte aligned, take the
+    element-wise kernel: same results to the same bar."""
+    M, P, Hq, Hkv = 5, 6, 3, 1
+    print(f"rope_append general form D={D} table offset {table_offset} floats", flush=True)
+    rng = np.random.default_rng(9300 + D)
+    n_pos = P + 8
+    qkv = rng.standard_normal((M, (Hq + 2 * Hkv) * D), dtype=np.float32).astype(np.float16)
+    pos = np.array([6, 7, 7, 8, 13], dtype=np.int32)
+    cos, sin = I.make_rope_tables(n_pos, D)
+    kc = rng.standard_normal((P + M, Hkv, D), dtype=np.float32).astype(np.float16)
+    vc = rng.standard_normal((P + M, Hkv, D), dtype=np.float32).astype(np.float16)
+    q64, _, k_want, v_want = R.rope_append(qkv, pos, cos, sin, kc, vc, P, Hq, Hkv, D)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+    def shifted(t):   # the same values at an address table_offset floats past a 16-byte boundary
+        buf = torch.empty(t.size + table_offset, dtype=torch.float32, device=DEV)
+        buf[table_offset:] = dev(t).reshape(-1)
+        return buf[table_offset:]
+
+    q = torch.full((M, Hq, D), SENTINEL, dtype=torch.float16, device=DEV)
+    kd, vd = dev(kc), dev(vc)
+    B.rope_append(dev(qkv), dev(pos), shifted(cos), shifted(sin), n_pos, q, kd, vd, M, P, Hq, Hkv, D)
+    torch.cuda.synchronize()
+    close_to_rounded(q.cpu().numpy(), q64, "rotated q")
+    a = qkv.astype(np.float64).reshape(M, Hq + 2 * Hkv, D)[:, Hq:Hq + Hkv]
+    h = D // 2
+    c, s = cos.astype(np.float64)[pos][:, None, :], sin.astype(np.float64)[pos][:, None, :]
+    k64 = np.concatenate([a[..., :h] * c - a[..., h:] * s, a[..., h:] * c + a[..., :h] * s], axis=-1)
+    close_to_rounded(kd.cpu().numpy()[P:], k64, "rotated k")
+    assert np.array_equal(vd.cpu().numpy().view(np.uint16), v_want.view(np.uint16))
+    assert np.array_equal(kd.cpu().numpy()[:P].view(np.uint16), kc[:P].view(np.uint16))
+
+
 def test_rope_position_outside_the_tables_is_skipped():
     M, P, Hq, Hkv, D = 3, 2, 2, 1, 16
     rng = np.random.default_rng(9200)
