@@ -128,13 +128,10 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
     float scale_log2e, int nsplit, int bq, int brem, int rep, int fused)
 {
     extern __shared__ float4v smem4[];
-    // Every argument is fetched by one batch of scalar loads up front: left to itself the compiler fetches
-    // them block by block where first used, three dependent round trips to the argument buffer (about
-    // a microsecond each) before the first K/V request goes out.
+    // one batch of scalar loads instead of three dependent ones before the first K/V request goes out
     const unsigned grid = gridDim.x;
-    asm volatile("" ::"s"(q), "s"(k), "s"(v), "s"(mask), "s"(out), "s"(part_o), "s"(part_ml), "s"(tickets), "s"(M),
-                 "s"(P), "s"(Hq), "s"(Hkv), "s"(scale_log2e), "s"(nsplit), "s"(bq), "s"(brem), "s"(rep), "s"(fused),
-                 "s"(grid));
+    fetch_arguments_together(q, k, v, mask, out, part_o, part_ml, tickets, M, P, Hq, Hkv, scale_log2e, nsplit, bq, brem, rep,
+                             fused, grid);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kw = wave & 3, rg = wave >> 2;   // key wavefront inside the row group, row group
@@ -437,6 +434,7 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(const float *__res
                                                               _Float16 *__restrict__ out, int M, int Hq, int nsplit,
                                                               int rep)
 {
+    fetch_arguments_together(part_o, part_ml, out, M, Hq, nsplit, rep);
     const int idx = blockIdx.x * 256 + threadIdx.x;   // over M * Hq * 32 quads
     if (idx >= M * Hq * (kHeadDim / 4)) return;
     const int d4 = idx % (kHeadDim / 4), h = (idx / (kHeadDim / 4)) % Hq, qrow = idx / (kHeadDim / 4) / Hq;
@@ -490,6 +488,7 @@ __global__ __launch_bounds__(256) void tree_accept_kernel(const int32_t *__restr
 {
     __shared__ int32_t path_sh[kRowsPad];
     __shared__ int32_t n_sh;
+    fetch_arguments_together(parent, token, target, M, path, result, k, v, P, row_chunks);
     const int tid = threadIdx.x;
     if (tid < 64) {
         const int lane = tid;

@@ -19,6 +19,16 @@ inline int check_weight_shape(int N, int K, int G)
     return W4A16_OK;
 }
 
+// Device side: makes the compiler fetch the named kernel arguments (uniform values) in ONE batch of scalar
+// loads where this is called -- the top of a kernel.  Left alone it fetches arguments block by block where
+// they are first used; in a short kernel that is several dependent round trips to the argument buffer, a
+// good part of a microsecond each, ahead of the first useful memory request.
+template <typename... T>
+__device__ __forceinline__ void fetch_arguments_together(const T &...args)
+{
+    (..., [](const T &a) { asm volatile("" ::"s"(a)); }(args));
+}
+
 inline int launch_status()
 {
     return hipGetLastError() == hipSuccess ? W4A16_OK : W4A16_EHIP;

@@ -103,8 +103,7 @@ __global__ __launch_bounds__(kRopeThreads) void rope_append_kernel(
     const float *__restrict__ sin_t, int n_pos, _Float16 *__restrict__ q, _Float16 *__restrict__ k_cache,
     _Float16 *__restrict__ v_cache, int P, int Hq, int Hkv, int D)
 {
-    asm volatile("" ::"s"(qkv), "s"(pos), "s"(cos_t), "s"(sin_t), "s"(n_pos), "s"(q), "s"(k_cache), "s"(v_cache), "s"(P),
-                 "s"(Hq), "s"(Hkv), "s"(D));
+    fetch_arguments_together(qkv, pos, cos_t, sin_t, n_pos, q, k_cache, v_cache, P, Hq, Hkv, D);
     typedef _Float16 half4 __attribute__((ext_vector_type(4)));
     typedef float float4 __attribute__((ext_vector_type(4)));
     const int m = blockIdx.x, h = D >> 1;

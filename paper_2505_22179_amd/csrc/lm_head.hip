@@ -207,6 +207,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_chunk_kernel(const float *
                                                                    float *__restrict__ cand_val, int *__restrict__ cand_idx)
 {
     constexpr int kPerLane = kLmChunk / 64;
+    fetch_arguments_together(logits, V, top_k, chunks, chunk_max, chunk_sum, cand_val, cand_idx);
     const int lane = threadIdx.x & 63;
     const int chunk = blockIdx.x * (kLmThreads / 64) + (threadIdx.x >> 6), m = blockIdx.y;
     if (chunk >= chunks) return;
@@ -266,6 +267,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_merge_kernel(const float *
                                                            int32_t *__restrict__ top_idx, float *__restrict__ top_logprob)
 {
     extern __shared__ float lds_f[];
+    fetch_arguments_together(chunk_max, chunk_sum, cand_val, cand_idx, chunks, top_k, top_idx, top_logprob);
     const int m = blockIdx.x, lane = threadIdx.x & 63;
     const int total = chunks * top_k;
     float *lval = lds_f;
