@@ -272,22 +272,35 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_merge_kernel(const float *
     const int total = chunks * top_k;
     float *lval = lds_f;
     int *lidx = reinterpret_cast<int *>(lds_f + total);
-    {   // all four wavefronts stage the lists, every load of a thread in flight at once
+    // the first wavefront's share of the chunk maxima and sums, requested together with the lists
+    float cmax[kLmListsPerLane], csum[kLmListsPerLane];
+#pragma unroll
+    for (int h = 0; h < kLmListsPerLane; ++h) {
+        const int ch = lane + 64 * h, chc = ch < chunks ? ch : chunks - 1;   // clamped address, value discarded:
+        const float a = chunk_max[(size_t)m * chunks + chc];                 // no branch around the load
+        const float b = chunk_sum[(size_t)m * chunks + chc];
+        cmax[h] = ch < chunks ? a : kNegInf;
+        csum[h] = ch < chunks ? b : 0.f;
+    }
+    {   // all four wavefronts stage the lists, every load of a thread in flight at once: whether a round of
+        // loads happens is a uniform decision and a lane past the end reads the last entry (and drops it), so
+        // no load sits under a per-lane condition, which would be compiled as a branch with a wait of its own
         constexpr int kPer = kLmMaxCandidates / kLmThreads;
+        const int rounds = (total + kLmThreads - 1) / kLmThreads;
         float sv[kPer];
         int si[kPer];
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
-            const int e = threadIdx.x + kLmThreads * i;
-            if (e < total) {
-                sv[i] = cand_val[(size_t)m * total + e];
-                si[i] = cand_idx[(size_t)m * total + e];
+            if (i < rounds) {
+                const int e = threadIdx.x + kLmThreads * i, ec = e < total ? e : total - 1;
+                sv[i] = cand_val[(size_t)m * total + ec];
+                si[i] = cand_idx[(size_t)m * total + ec];
             }
         }
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
             const int e = threadIdx.x + kLmThreads * i;
-            if (e < total) {
+            if (i < rounds && e < total) {
                 lval[e] = sv[i];
                 lidx[e] = si[i];
             }
@@ -296,11 +309,12 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_merge_kernel(const float *
     __syncthreads();
     if (threadIdx.x >= 64) return;   // the merge itself is one wavefront's work
     float mx = kNegInf;
-    for (int ch = lane; ch < chunks; ch += 64) mx = fmaxf(mx, chunk_max[(size_t)m * chunks + ch]);
+#pragma unroll
+    for (int h = 0; h < kLmListsPerLane; ++h) mx = fmaxf(mx, cmax[h]);
     mx = wave_max(mx);
     float se = 0.f;
-    for (int ch = lane; ch < chunks; ch += 64)
-        se += chunk_sum[(size_t)m * chunks + ch] * __expf(chunk_max[(size_t)m * chunks + ch] - mx);
+#pragma unroll
+    for (int h = 0; h < kLmListsPerLane; ++h) se += csum[h] * __expf(cmax[h] - mx);   // absent chunks: 0 * exp(-inf) = 0
     se = wave_sum(se);
     const float lse = mx + __logf(se);
     Cand head[kLmListsPerLane];
