@@ -141,11 +141,11 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
     // its K/V rows are fetched into one L2 instead of all eight.
     int lid = blockIdx.x;
     if ((grid & 7) == 0) lid = (blockIdx.x & 7) * (grid >> 3) + (blockIdx.x >> 3);
-    // A workgroup's 64-row tile holds the M rows of one query head (rep == 0), or -- when they fit --
-    // the M rows of all rep query heads that share a KV head (tile row j * M + m = head j of the
-    // group, query row m): few-row calls then read K and V once per KV head instead of once per head.
+    // A workgroup's row tile holds the M rows of one query head (rep == 0), or -- when they fit -- the M rows
+    // of rep consecutive query heads that share a KV head (tile row j * M + m = head unit * rep + j, query
+    // row m): few-row calls then read K and V once per rep heads instead of once per head.
     const int unit = lid / nsplit, sp = lid % nsplit;
-    const int kvh = rep ? unit : unit / (Hq / Hkv);
+    const int kvh = (rep ? unit * rep : unit) / (Hq / Hkv);
     const int R = rep ? M * rep : M;   // valid rows of the tile
     const int T = P + M;
     // key steps of this split: bq = nblk / nsplit each, the first brem = nblk % nsplit one more (host-computed)
@@ -527,11 +527,19 @@ __global__ __launch_bounds__(256) void tree_accept_kernel(const int32_t *__restr
     }
 }
 
-// query heads per 64-row tile: Hq / Hkv when the rows of a whole KV group fit (and the knob allows), else 0
+// Query heads per row tile (0 = one head per tile).  The heads of a KV group can share a tile, which reads K
+// and V once for all of them.  A tile of at most 32 rows runs in the two-row-tile kernel, two workgroups to a
+// compute unit and half the work per key step, so the largest divisor of the group size that keeps the tile
+// within 32 rows is taken when there is one (M = 8 with groups of 8: two tiles of 4 heads, 12.6 us, against
+// one tile of 8 heads, 16.3 us; K and V are then read twice, from L2); else the whole group if it fits 64 rows.
 static int attn_rep(int M, int Hq, int Hkv)
 {
-    const int rep = Hq / Hkv;
-    return (params().attn_pack != 1 && rep > 1 && M * rep <= kRowsPad) ? rep : 0;
+    const int group = Hq / Hkv, knob = params().attn_pack;
+    if (knob == 1 || group < 2) return 0;
+    if (knob != 2)
+        for (int d = group; d >= 2; --d)
+            if (group % d == 0 && M * d <= 32) return d;
+    return M * group <= kRowsPad ? group : 0;
 }
 
 static int attn_splits(int M, int P, int units)
@@ -597,7 +605,7 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
     if (!q || !k || !v || !mask || !out) return W4A16_ENULL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace)) return W4A16_EALIGN;
     const int rep = attn_rep(M, Hq, Hkv);
-    const int units = rep ? Hkv : Hq;
+    const int units = rep ? Hq / rep : Hq;
     const int ns = attn_splits(M, P, units);
     const size_t need = kTicketBytes + (size_t)units * ns * kRowsPad * (kHeadDim + 2) * sizeof(float);
     if (ns > 1 && (!workspace || workspace_bytes < need)) return W4A16_EWORKSPACE;

@@ -57,6 +57,8 @@ CASES = [
     (5, 70, 24, 3, "random"),        # 40 of 64 tile rows in use, three KV heads
     (16, 333, 16, 4, "chain"),       # 4 heads x 16 rows
     (3, 2, 12, 2, "chain"),          # fewer keys than one step
+    (12, 300, 32, 4, "random"),      # groups of 8 heads, two heads per 24-row tile
+    (7, 129, 12, 2, "chain"),        # groups of 6 heads: three per 21-row tile (42 rows would need the tall tile)
 ]
 
 
@@ -66,7 +68,7 @@ def test_attn_parity(M, P, Hq, Hkv, tree):
     depth = 6 if M > 6 else max(M - 1, 0)
     a = I.make_attn(8000 + M + P + Hq, M, P, Hq, Hkv, 128, tree=tree, depth=depth)
     ref64, _ = R.tree_verify_attn(a.q, a.k, a.v, a.mask, a.scale)
-    for pack in ((0, 1) if M * (Hq // Hkv) <= 64 and Hq > Hkv else (0,)):   # shared tile per KV group, and without
+    for pack in ((0, 1, 2) if Hq > Hkv else (0,)):   # heads of a KV group sharing a tile (by size, never, whole group)
         B.w4a16_set_param("attn_pack", pack)
         for row_tiles in (0, 2, 4):   # by tile height; 32 rows per wavefront (one or two row groups); all 64
             B.w4a16_set_param("attn_row_tiles", row_tiles)
