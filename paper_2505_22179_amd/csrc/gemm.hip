@@ -304,8 +304,30 @@ struct Out {
     int epi;
 };
 
+// The residual of a quad is fetched apart from the store, so that a thread can request the residuals of all
+// its quads (and the partial sums it has to add) before it waits for any of them: inside the store, under
+// the per-lane bounds test, each load became a branch with a wait of its own -- one memory round trip per
+// quad, in a row.  The load is unconditional: a quad outside the matrix reads a clamped address and its value
+// is never used (with y == residual that may be a location another thread is writing: just as unused).
 template <int MT>
-__device__ __forceinline__ void store_quad(const Out &o, float4v v, int e4, int first_col, int M, int N)
+__device__ __forceinline__ half4v load_residual(const Out &o, int e4, int first_col, int M, int N)
+{
+    half4v r = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
+    if (o.residual) {   // uniform
+        int ln = (e4 * 4) & 63, reg = e4 >> 4;
+        int i = reg & 3, tm = reg >> 2;
+        int mt = tm % MT, t = tm / MT;
+        int m = mt * 16 + 4 * (ln >> 4) + i;
+        int n = first_col + t * 16 + (ln & 15);
+        m = m < M ? m : M - 1;
+        n = n < N ? n : N - 4;
+        r = *reinterpret_cast<const half4v *>(o.residual + (size_t)m * N + n);
+    }
+    return r;
+}
+
+template <int MT>
+__device__ __forceinline__ void store_quad(const Out &o, float4v v, half4v r, int e4, int first_col, int M, int N)
 {
     int ln = (e4 * 4) & 63, reg = e4 >> 4;
     int i = reg & 3, tm = reg >> 2;
@@ -313,12 +335,42 @@ __device__ __forceinline__ void store_quad(const Out &o, float4v v, int e4, int 
     int m = mt * 16 + 4 * (ln >> 4) + i;
     int n = first_col + t * 16 + (ln & 15);
     if (m < M && n < N) {   // N % 8 == 0 and n % 4 == 0: the quad never straddles the edge
-        if (o.residual) {   // uniform
-            const half4v r = *reinterpret_cast<const half4v *>(o.residual + (size_t)m * N + n);
-            v += (float4v){(float)r[0], (float)r[1], (float)r[2], (float)r[3]};
-        }
+        if (o.residual) v += (float4v){(float)r[0], (float)r[1], (float)r[2], (float)r[3]};   // uniform
         half4v h = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
         *reinterpret_cast<half4v *>(o.y + (size_t)m * N + n) = h;
+    }
+}
+
+template <int MT>
+__device__ __forceinline__ void store_quad(const Out &o, float4v v, int e4, int first_col, int M, int N)
+{
+    store_quad<MT>(o, v, load_residual<MT>(o, e4, first_col, M, N), e4, first_col, M, N);
+}
+
+// Sum over the S split-K partials of Q quads, in split order from zero.  The loads are unconditional (a quad of
+// rows that do not exist reads whatever the workspace holds; its sum is never stored) and go out four splits
+// at a time, so a thread waits for a batch, not for each load: under the row test, or in a plain loop over the
+// splits, every partial had been a memory round trip of its own.  LOAD(index) fetches quad `index` of the unit.
+constexpr int kSplitBatch = 4;
+template <int Q, typename Load>
+__device__ __forceinline__ void sum_partials(float4v (&sum)[Q], const int (&e4)[Q], int S, int E4, Load load)
+{
+#pragma unroll
+    for (int q = 0; q < Q; ++q) sum[q] = (float4v){0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < S; s0 += kSplitBatch) {
+        float4v v[kSplitBatch][Q];
+#pragma unroll
+        for (int i = 0; i < kSplitBatch; ++i) {
+            const int sc = s0 + i < S ? s0 + i : S - 1;   // uniform
+#pragma unroll
+            for (int q = 0; q < Q; ++q) v[i][q] = load(sc * E4 + e4[q]);
+        }
+#pragma unroll
+        for (int i = 0; i < kSplitBatch; ++i)
+            if (s0 + i < S) {   // uniform
+#pragma unroll
+                for (int q = 0; q < Q; ++q) sum[q] += v[i][q];
+            }
     }
 }
 
@@ -407,6 +459,13 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
         }
         return;
     }
+    int quad[Q];   // this thread's quads (clamped where the unit has fewer: those are never stored)
+    half4v res[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        quad[q] = (!kRagged || tid + kThreads * q < E4) ? tid + kThreads * q : E4 - 1;
+        if (S == 1) res[q] = load_residual<MT>(y, quad[q], first_col, M, N);   // requested before the LDS sums
+    }
     float4v sum[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
@@ -422,7 +481,7 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
     if (S == 1) {
 #pragma unroll
         for (int q = 0; q < Q; ++q)
-            if (!kRagged || tid + kThreads * q < E4) store_quad<MT>(y, sum[q], tid + kThreads * q, first_col, M, N);
+            if (!kRagged || tid + kThreads * q < E4) store_quad<MT>(y, sum[q], res[q], tid + kThreads * q, first_col, M, N);
         return;
     }
     float *mine = partial + ((size_t)unit * S + ks) * E4 * 4;
@@ -445,31 +504,23 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
     if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (ticket_sh != (uint32_t)(S - 1)) return;
+    const auto load = [&](int index) { return load_partial(all, index); };
     if (y.epi == kEpiSiluMul) {   // uniform
         for (int idx = tid; idx < E4 / 2; idx += kThreads) {
-            const int e4 = gate_quad<MT>(idx);
-            if (quad_row<MT>(e4) >= M) continue;
-            float4v g = (float4v){0.f, 0.f, 0.f, 0.f}, u = g;
-            for (int s = 0; s < S; ++s) {
-                g += load_partial(all, s * E4 + e4);
-                u += load_partial(all, s * E4 + e4 + 64 * MT);
-            }
-            store_gated<MT>(y, g, u, e4, first_col, M, N);
+            const int pair[2] = {gate_quad<MT>(idx), gate_quad<MT>(idx) + 64 * MT};
+            float4v gu[2];
+            sum_partials<2>(gu, pair, S, E4, load);
+            store_gated<MT>(y, gu[0], gu[1], pair[0], first_col, M, N);
         }
         if (tid == 0) __hip_atomic_store(&tickets[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
 #pragma unroll
-    for (int q = 0; q < Q; ++q) sum[q] = (float4v){0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < S; ++s) {
-#pragma unroll
-        for (int q = 0; q < Q; ++q)
-            if ((!kRagged || tid + kThreads * q < E4) && quad_row<MT>(tid + kThreads * q) < M)
-                sum[q] += load_partial(all, s * E4 + tid + kThreads * q);
-    }
+    for (int q = 0; q < Q; ++q) res[q] = load_residual<MT>(y, quad[q], first_col, M, N);
+    sum_partials<Q>(sum, quad, S, E4, load);
 #pragma unroll
     for (int q = 0; q < Q; ++q)
-        if (!kRagged || tid + kThreads * q < E4) store_quad<MT>(y, sum[q], tid + kThreads * q, first_col, M, N);
+        if (!kRagged || tid + kThreads * q < E4) store_quad<MT>(y, sum[q], res[q], tid + kThreads * q, first_col, M, N);
     if (tid == 0) __hip_atomic_store(&tickets[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -995,12 +1046,22 @@ __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const
             }
             return;
         }
-        for (int q = kset; q < E4 / 64; q += KS) {
+        constexpr int kMine = (E4 / 64 + KS - 1) / KS;   // quads of this lane: lane + 64 (kset + KS j)
+        half4v res[kMine];
+#pragma unroll
+        for (int j = 0; j < kMine; ++j) {
+            const int q = kset + KS * j;
+            res[j] = load_residual<MT>(y, lane + 64 * (q < E4 / 64 ? q : E4 / 64 - 1), first_col, M, N);
+        }
+#pragma unroll
+        for (int j = 0; j < kMine; ++j) {
+            const int q = kset + KS * j;
+            if (q >= E4 / 64) break;   // uniform
             const int e4 = lane + 64 * q;
             float4v v = out4[colq * E4 + e4];
 #pragma unroll
             for (int s = 1; s < KS; ++s) v += out4[(s * 4 + colq) * E4 + e4];
-            store_quad<MT>(y, v, e4, first_col, M, N);
+            store_quad<MT>(y, v, res[j], e4, first_col, M, N);
         }
         return;
     }
@@ -1028,25 +1089,25 @@ __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const
     if (ticket_sh != (uint32_t)(S - 1)) return;
     if (tid == 0) __hip_atomic_store(&tickets[wg_unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (!active) return;
+    const auto load = [&](int index) { return load_partial(all, index); };
     if (y.epi == kEpiSiluMul) {   // uniform
         for (int idx = kset * 64 + lane; idx < E4 / 2; idx += 64 * KS) {
-            const int e4 = gate_quad<MT>(idx);
-            if (quad_row<MT>(e4) >= M) continue;
-            float4v g = (float4v){0.f, 0.f, 0.f, 0.f}, u = g;
-            for (int s = 0; s < S; ++s) {
-                g += load_partial(all, s * E4 + e4);
-                u += load_partial(all, s * E4 + e4 + 64 * MT);
-            }
-            store_gated<MT>(y, g, u, e4, first_col, M, N);
+            const int pair[2] = {gate_quad<MT>(idx), gate_quad<MT>(idx) + 64 * MT};
+            float4v gu[2];
+            sum_partials<2>(gu, pair, S, E4, load);
+            store_gated<MT>(y, gu[0], gu[1], pair[0], first_col, M, N);
         }
         return;
     }
-    for (int q = kset; q < E4 / 64; q += KS) {
-        const int e4 = lane + 64 * q;
-        if (quad_row<MT>(e4) >= M) continue;
-        float4v v = (float4v){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < S; ++s) v += load_partial(all, s * E4 + e4);
-        store_quad<MT>(y, v, e4, first_col, M, N);
+    // two quads of the lane at a time: their residuals and a batch of their partials are in flight together
+    for (int q = kset; q < E4 / 64; q += 2 * KS) {
+        const int q1 = q + KS < E4 / 64 ? q + KS : q;   // uniform; the last round may have one quad only
+        const int pair[2] = {lane + 64 * q, lane + 64 * q1};
+        const half4v r0 = load_residual<MT>(y, pair[0], first_col, M, N), r1 = load_residual<MT>(y, pair[1], first_col, M, N);
+        float4v v[2];
+        sum_partials<2>(v, pair, S, E4, load);
+        store_quad<MT>(y, v[0], r0, pair[0], first_col, M, N);
+        if (q1 != q) store_quad<MT>(y, v[1], r1, pair[1], first_col, M, N);
     }
 }
 
@@ -1097,32 +1158,29 @@ __global__ __launch_bounds__(kReduceThreads) void splitk_reduce_kernel(const flo
     const int unit = blockIdx.x, tid = threadIdx.x;
     const int nb = (unit * TW) >> 3, t0 = (unit * TW) & 7;
     const float4v *all = reinterpret_cast<const float4v *>(partial) + (size_t)unit * S * E4;
+    const auto load = [&](int index) { return all[index]; };
+    const int first_col = nb * kBlockCols + t0 * 16;
     if (y.epi == kEpiSiluMul) {   // uniform
         for (int idx = tid; idx < E4 / 2; idx += kReduceThreads) {
-            const int e4 = gate_quad<MT>(idx);
-            if (quad_row<MT>(e4) >= M) continue;
-            float4v g = (float4v){0.f, 0.f, 0.f, 0.f}, u = g;
-            for (int s = 0; s < S; ++s) {
-                g += all[(size_t)s * E4 + e4];
-                u += all[(size_t)s * E4 + e4 + 64 * MT];
-            }
-            store_gated<MT>(y, g, u, e4, nb * kBlockCols + t0 * 16, M, N);
+            const int pair[2] = {gate_quad<MT>(idx), gate_quad<MT>(idx) + 64 * MT};
+            float4v gu[2];
+            sum_partials<2>(gu, pair, S, E4, load);
+            store_gated<MT>(y, gu[0], gu[1], pair[0], first_col, M, N);
         }
         return;
     }
-    float4v sum[Q];
+    int quad[Q];
+    half4v res[Q];
 #pragma unroll
-    for (int q = 0; q < Q; ++q) sum[q] = (float4v){0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < S; ++s) {
-#pragma unroll
-        for (int q = 0; q < Q; ++q)
-            if ((!kRagged || tid + kReduceThreads * q < E4) && quad_row<MT>(tid + kReduceThreads * q) < M)
-                sum[q] += all[(size_t)s * E4 + tid + kReduceThreads * q];
+    for (int q = 0; q < Q; ++q) {
+        quad[q] = (!kRagged || tid + kReduceThreads * q < E4) ? tid + kReduceThreads * q : E4 - 1;
+        res[q] = load_residual<MT>(y, quad[q], first_col, M, N);
     }
+    float4v sum[Q];
+    sum_partials<Q>(sum, quad, S, E4, load);
 #pragma unroll
     for (int q = 0; q < Q; ++q)
-        if (!kRagged || tid + kReduceThreads * q < E4)
-            store_quad<MT>(y, sum[q], tid + kReduceThreads * q, nb * kBlockCols + t0 * 16, M, N);
+        if (!kRagged || tid + kReduceThreads * q < E4) store_quad<MT>(y, sum[q], res[q], tid + kReduceThreads * q, first_col, M, N);
 }
 
 // ---- host side ---------------------------------------------------------------------------------
