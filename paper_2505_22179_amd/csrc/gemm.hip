@@ -843,12 +843,18 @@ __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW
         return;
     }
     float4v *part4 = reinterpret_cast<float4v *>(partial) + ((size_t)unit * S + ks) * E4;
+    if (S == 1) {   // uniform: all residuals requested first, then the stores
+        half4v res[E4 / 64];
+#pragma unroll
+        for (int q = 0; q < E4 / 64; ++q) res[q] = load_residual<MT>(y, lane + 64 * q, first_col, M, N);
+#pragma unroll
+        for (int q = 0; q < E4 / 64; ++q) store_quad<MT>(y, out4[wave * E4 + lane + 64 * q], res[q], lane + 64 * q, first_col, M, N);
+        return;
+    }
 #pragma unroll
     for (int q = 0; q < E4 / 64; ++q) {
         const int e4 = lane + 64 * q;
-        const float4v v = out4[wave * E4 + e4];
-        if (S == 1) store_quad<MT>(y, v, e4, first_col, M, N);
-        else if (quad_row<MT>(e4) < M) part4[e4] = v;
+        if (quad_row<MT>(e4) < M) part4[e4] = out4[wave * E4 + e4];
     }
 }
 
