@@ -318,11 +318,13 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
         load_v(first, vr);
     }
     if (reaches_draft) {
+        uint64_t mine = 0;   // lane i keeps the word of row 16 wave + i: one LDS write per wavefront instead of sixteen
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const uint64_t bits = __ballot(mask_byte[i] != 0 && wave * 16 + i < M && lane < M);
-            if (lane == 0 && wave < 4) row_bits[wave * 16 + i] = bits;
+            mine = lane == i ? bits : mine;
         }
+        if (lane < 16 && wave < 4) row_bits[wave * 16 + lane] = mine;
         __syncthreads();
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) mbits[rt] = row_bits[row[rt]];
