@@ -37,6 +37,9 @@ def weight_bytes(K: int, N: int) -> int:
     return K * N // 2 + (K // G) * N * 2 + (K // G) * N // 2
 
 
+HEAD_DIM = 128   # of both Llama-3 models
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -57,8 +60,14 @@ class Layer:
             sc = (torch.rand((K // G, N), device="cuda", generator=gen) * 9e-3 + 1e-3).to(torch.float16)
             qz = torch.randint(-2 ** 31, 2 ** 31 - 1, (K // G, N // 8), dtype=torch.int32, device="cuda", generator=gen)
             p = torch.empty(B.w4a16_packed_bytes(N, K, G), dtype=torch.uint8, device="cuda")
-            # gate_up in the paired tile order the fused SiLU-gate epilogue reads (same bytes, same cost for the plain GEMM)
-            (B.w4a16_pack_gate_up if name == "gate_up" else B.w4a16_pack)(qw, sc, qz, p, N, K, G)
+            # gate_up in the paired tile order the fused SiLU-gate epilogue reads, qkv with the halves of every head
+            # paired for the rotary epilogue (same bytes, same cost for the plain GEMM)
+            if name == "gate_up":
+                B.w4a16_pack_gate_up(qw, sc, qz, p, N, K, G)
+            elif name == "qkv":
+                B.w4a16_pack_heads(qw, sc, qz, p, N, K, HEAD_DIM, G)
+            else:
+                B.w4a16_pack(qw, sc, qz, p, N, K, G)
             first.append(p)
             del qw, sc, qz
         self.packed.append(first)
@@ -101,8 +110,9 @@ class Layer:
 
 class DecoderLayer:
     """One whole decoder layer of the target model on M draft-tree tokens over a P-token prefix, chained
-    through w4a16_decoder_layer: norm, qkv, rotary + K/V append, tree attention, o_proj + residual, norm,
-    gate/up with the SiLU gate, down + residual (8 kernel launches plus the split-K / merge passes).  The
+    through w4a16_decoder_layer: norm, qkv with the rotary embedding and the K/V append in its store, tree
+    attention, o_proj + residual, norm, gate/up with the SiLU gate, down + residual (7 kernel launches plus the
+    split-K / merge passes).  The
     hidden state of a step is one of several kept per object and is updated in place."""
 
     def __init__(self, layer: "Layer", M: int, P: int, kv_copies: int, Hq: int = 64, Hkv: int = 8, D: int = 128):
@@ -141,7 +151,8 @@ class DecoderLayer:
         L, M, P, Hq, Hkv, D, H = self.L, self.M, self.P, self.Hq, self.Hkv, self.D, self.H
         w = L.packed[c % L.copies]
         k, v = self.k[c % len(self.k)], self.v[c % len(self.v)]
-        weights = B.layer_weights(w[0], w[1], w[2], w[3], self.g1, self.g2, H, Hq, Hkv, D, self.Ngu // 2, 1e-5)
+        weights = B.layer_weights(w[0], w[1], w[2], w[3], self.g1, self.g2, H, Hq, Hkv, D, self.Ngu // 2, 1e-5,
+                                  qkv_heads_packed=True)
         scratch = B.layer_scratch(self.n1, self.qkv, self.q, self.att, self.act, L.ws, self.aws)
         hs = self.h_work[c % len(self.h_work)]   # updated in place
         B.w4a16_decoder_layer(weights, hs, M, P, self.pos, self.cos, self.sin, self.n_pos, self.mask, k, v, scratch)
@@ -200,7 +211,7 @@ class Model:
         for l in range(self.n_layers):
             w = L.packed[l]
             weights = B.layer_weights(w[0], w[1], w[2], w[3], self.g[0], self.g[1], self.H, self.Hq, self.Hkv, self.D,
-                                      self.F, 1e-5)
+                                      self.F, 1e-5, qkv_heads_packed=True)
             B.w4a16_decoder_layer(weights, b["h"], M, self.P, b["pos"], self.cos, self.sin, self.n_pos, b["mask"],
                                   self.k[l], self.v[l], b["scratch"])
         B.rms_norm(b["h"], self.g[2], b["hn"], M, self.H, 1e-5)

@@ -209,6 +209,26 @@ int rms_norm(const void *x, const void *gamma, void *y, int M, int K, float eps,
 int rope_append(const void *qkv, const int32_t *pos, const float *cos_table, const float *sin_table, int n_pos,
                 void *q, void *k_cache, void *v_cache, int M, int P, int Hq, int Hkv, int D, void *stream);
 
+/* w4a16_pack for a weight whose columns are heads of head_dim columns each (a q/k/v projection): inside
+ * every head the 16-column tiles of its two halves alternate -- packed tile 2j of the head is tile j of
+ * elements 0..head_dim/2-1, packed tile 2j+1 tile j of elements head_dim/2.. -- so that the element pair
+ * (d, d + head_dim/2) the rotary embedding turns lies in neighbouring tiles.  This is the layout
+ * w4a16_gemm_rope needs; every other entry point sees the weight with its columns permuted that way.
+ * Requires head_dim % 32 == 0 and N % head_dim == 0, otherwise as w4a16_pack. */
+int w4a16_pack_heads(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
+                     int N, int K, int G, int head_dim, void *stream);
+
+/* The q/k/v projection of a decoder layer with rope_append fused into its store: one launch and one round
+ * trip of the [M, (Hq + 2 Hkv) D] projection less (3 us per layer at these sizes).  Equal, bit for bit, to
+ *   w4a16_gemm(x, Wqkv) -> fp16 qkv;  rope_append(qkv, ...)
+ * -- the sums are rounded to fp16 first and then rotated with rope_append's own expressions.  `packed` must
+ * come from w4a16_pack_heads with head_dim = D; N is (Hq + 2 Hkv) D.  x, workspace, errors: as w4a16_gemm;
+ * pos, tables, q, k_cache, v_cache, P: as rope_append, except that the tables must be 16-byte aligned and
+ * D % 32 == 0 (W4A16_EALIGN / W4A16_EINVAL otherwise: use the two calls). */
+int w4a16_gemm_rope(const void *x, const void *packed, int M, int K, int G, const int32_t *pos, const float *cos_table,
+                    const float *sin_table, int n_pos, void *q, void *k_cache, void *v_cache, int P, int Hq, int Hkv, int D,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
 /* One decoder layer of a Llama-type target model on M token rows over a P-token prefix, enqueued as one
  * call (paper section 2.1: a verification is one forward pass of the target over the draft tokens):
  *   n = rms_norm(h, norm1_gamma);  qkv = n . Wqkv;  rope_append(qkv) -> q, cache rows P..P+M-1;
@@ -222,13 +242,17 @@ int rope_append(const void *qkv, const int32_t *pos, const float *cos_table, con
  * caller: norm [M, hidden], qkv [M, (n_q_heads + 2 n_kv_heads) head_dim], q and attn [M, n_q_heads,
  * head_dim], act [M, ffn]; gemm_workspace sized for the largest of the four linears
  * (w4a16_workspace_bytes) and attn_workspace (tree_verify_attn_workspace_bytes), both initialised with
- * w4a16_workspace_init.  Returns the first error of the calls it makes; validation failures of the
- * first call enqueue nothing, a failure further on leaves the earlier steps enqueued. */
+ * w4a16_workspace_init.  With qkv_heads_packed set, qkv_packed is a w4a16_pack_heads output and the second
+ * and third step are one call of w4a16_gemm_rope (same results bit for bit; the qkv scratch is not used and
+ * may be NULL; head_dim % 32 == 0 and 16-byte-aligned tables are then required).  Returns the first error
+ * of the calls it makes; validation failures of the first call enqueue nothing, a failure further on leaves
+ * the earlier steps enqueued. */
 typedef struct {
     const void *qkv_packed, *o_packed, *gate_up_packed, *down_packed;
     const void *norm1_gamma, *norm2_gamma; /* fp16 [hidden] */
     int hidden, n_q_heads, n_kv_heads, head_dim, ffn;
     float eps;
+    int qkv_heads_packed; /* nonzero: qkv_packed comes from w4a16_pack_heads and the layer uses w4a16_gemm_rope */
 } w4a16_layer_weights;
 typedef struct {
     void *norm, *qkv, *q, *attn, *act;

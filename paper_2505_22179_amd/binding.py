@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("W4A16_LIB") or os.path.join(_HERE, "lib", "libw4a16.s
 EXPORTS = (
     "w4a16_version", "w4a16_strerror", "w4a16_set_param", "w4a16_get_param", "w4a16_packed_bytes",
     "w4a16_workspace_bytes", "w4a16_workspace_init", "w4a16_pack", "w4a16_unpack", "w4a16_dequant",
-    "w4a16_gemm", "w4a16_gemm_fused", "w4a16_pack_gate_up", "w4a16_read_probe", "tree_verify_attn_workspace_bytes",
+    "w4a16_gemm", "w4a16_gemm_fused", "w4a16_gemm_rope", "w4a16_pack_heads", "w4a16_pack_gate_up", "w4a16_read_probe", "tree_verify_attn_workspace_bytes",
     "tree_verify_attn", "tree_accept", "rms_norm", "rope_append", "lm_head_workspace_bytes", "lm_head_topk",
     "lm_head_packed_bytes", "lm_head_pack", "w4a16_decoder_layer",
 )
@@ -30,7 +30,8 @@ class LayerWeights(ctypes.Structure):
     _fields_ = [("qkv_packed", ctypes.c_void_p), ("o_packed", ctypes.c_void_p), ("gate_up_packed", ctypes.c_void_p),
                 ("down_packed", ctypes.c_void_p), ("norm1_gamma", ctypes.c_void_p), ("norm2_gamma", ctypes.c_void_p),
                 ("hidden", ctypes.c_int), ("n_q_heads", ctypes.c_int), ("n_kv_heads", ctypes.c_int),
-                ("head_dim", ctypes.c_int), ("ffn", ctypes.c_int), ("eps", ctypes.c_float)]
+                ("head_dim", ctypes.c_int), ("ffn", ctypes.c_int), ("eps", ctypes.c_float),
+                ("qkv_heads_packed", ctypes.c_int)]
 
 
 class LayerScratch(ctypes.Structure):
@@ -75,6 +76,8 @@ def load() -> ctypes.CDLL:
     L.tree_accept.argtypes = [vp, vp, vp, i, vp, vp, vp, vp, i, i, i, vp]
     L.w4a16_gemm_fused.argtypes = [vp, vp, vp, i, i, i, i, i, vp, vp, sz, vp]
     L.w4a16_pack_gate_up.argtypes = [vp, vp, vp, vp, i, i, i, vp]
+    L.w4a16_pack_heads.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
+    L.w4a16_gemm_rope.argtypes = [vp, vp, i, i, i, vp, vp, vp, i, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.rms_norm.argtypes = [vp, vp, vp, i, i, ctypes.c_float, vp]
     L.rope_append.argtypes = [vp, vp, vp, vp, i, vp, vp, vp, i, i, i, i, i, vp]
     L.w4a16_decoder_layer.argtypes = [ctypes.POINTER(LayerWeights), vp, i, i, vp, vp, vp, i, vp, vp, vp,
@@ -170,6 +173,19 @@ def w4a16_pack_gate_up(qweight, scales, qzeros, packed, N: int, K: int, G: int =
            "w4a16_pack_gate_up")
 
 
+def w4a16_pack_heads(qweight, scales, qzeros, packed, N: int, K: int, head_dim: int, G: int = 128) -> None:
+    _check(load().w4a16_pack_heads(_ptr(qweight), _ptr(scales), _ptr(qzeros), _ptr(packed), N, K, G, head_dim, _stream()),
+           "w4a16_pack_heads")
+
+
+def w4a16_gemm_rope(x, packed, M: int, K: int, G: int, pos, cos_table, sin_table, n_pos: int, q, k_cache, v_cache,
+                    P: int, Hq: int, Hkv: int, D: int, workspace) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().w4a16_gemm_rope(_ptr(x), _ptr(packed), M, K, G, _ptr(pos), _ptr(cos_table), _ptr(sin_table), n_pos,
+                                  _ptr(q), _ptr(k_cache), _ptr(v_cache), P, Hq, Hkv, D, _ptr(workspace), nbytes, _stream()),
+           "w4a16_gemm_rope")
+
+
 def rms_norm(x, gamma, y, M: int, K: int, eps: float) -> None:
     _check(load().rms_norm(_ptr(x), _ptr(gamma), _ptr(y), M, K, float(eps), _stream()), "rms_norm")
 
@@ -181,9 +197,10 @@ def rope_append(qkv, pos, cos_table, sin_table, n_pos: int, q, k_cache, v_cache,
 
 
 def layer_weights(qkv_packed, o_packed, gate_up_packed, down_packed, norm1_gamma, norm2_gamma, hidden: int,
-                  n_q_heads: int, n_kv_heads: int, head_dim: int, ffn: int, eps: float) -> LayerWeights:
+                  n_q_heads: int, n_kv_heads: int, head_dim: int, ffn: int, eps: float,
+                  qkv_heads_packed: bool = False) -> LayerWeights:
     return LayerWeights(_ptr(qkv_packed), _ptr(o_packed), _ptr(gate_up_packed), _ptr(down_packed), _ptr(norm1_gamma),
-                        _ptr(norm2_gamma), hidden, n_q_heads, n_kv_heads, head_dim, ffn, float(eps))
+                        _ptr(norm2_gamma), hidden, n_q_heads, n_kv_heads, head_dim, ffn, float(eps), int(qkv_heads_packed))
 
 
 def layer_scratch(norm, qkv, q, attn, act, gemm_workspace, attn_workspace) -> LayerScratch:
@@ -234,11 +251,15 @@ def tree_accept(parent, token, target, M: int, path, result, k=None, v=None, P: 
 
 # ---- conveniences for tests and the benchmark (still marshalling only) ----
 
-def pack_from_numpy(inp, device="cuda", gate_up: bool = False):
-    """Upload a LinearInputs' canonical tensors and return the packed device buffer."""
+def pack_from_numpy(inp, device="cuda", gate_up: bool = False, head_dim: int = 0):
+    """Upload a LinearInputs' canonical tensors and return the packed device buffer (plain, gate/up paired,
+    or -- head_dim > 0 -- with the halves of every head paired)."""
     qw = torch.from_numpy(inp.qweight).to(device)
     sc = torch.from_numpy(inp.scales).to(device)
     qz = torch.from_numpy(inp.qzeros).to(device)
     packed = torch.empty(w4a16_packed_bytes(inp.N, inp.K, inp.G), dtype=torch.uint8, device=device)
-    (w4a16_pack_gate_up if gate_up else w4a16_pack)(qw, sc, qz, packed, inp.N, inp.K, inp.G)
+    if head_dim:
+        w4a16_pack_heads(qw, sc, qz, packed, inp.N, inp.K, head_dim, inp.G)
+    else:
+        (w4a16_pack_gate_up if gate_up else w4a16_pack)(qw, sc, qz, packed, inp.N, inp.K, inp.G)
     return packed

@@ -297,12 +297,24 @@ __device__ __forceinline__ int quad_row(int e4)
 // Where the finished sums go.  epi selects what is stored: the sums themselves, the sums plus a
 // residual of the same shape (which may be y itself), or -- for a weight whose 16-column tiles
 // alternate between a gate projection and an up projection -- silu(gate) * up, half as wide.
-constexpr int kEpiNone = 0, kEpiResidual = 1, kEpiSiluMul = 2;
+// or -- for a q/k/v projection whose heads were packed with their two halves alternating tile by tile -- the
+// rotary embedding of the q and k heads and the scatter of q, k and v to their own buffers (kEpiRope).
+// The last two are the paired epilogues: one thread finishes a quad of a packed tile 2j together with the
+// quad of tile 2j+1 that belongs to it.
+constexpr int kEpiNone = 0, kEpiResidual = 1, kEpiSiluMul = 2, kEpiRope = 3;
+struct RopeOut {   // arguments of rope_append, minus the fp16 q/k/v rows, which are the linear's own sums
+    const int32_t *pos;
+    const float *cos_t, *sin_t;
+    _Float16 *q, *k_cache, *v_cache;
+    int n_pos, P, Hq, Hkv, D;
+};
 struct Out {
     _Float16 *y;
     const _Float16 *residual;
     int epi;
+    RopeOut rope;
 };
+__device__ __forceinline__ bool paired_epilogue(const Out &o) { return o.epi >= kEpiSiluMul; }
 
 // The residual of a quad is fetched apart from the store, so that a thread can request the residuals of all
 // its quads (and the partial sums it has to add) before it waits for any of them: inside the store, under
@@ -403,6 +415,87 @@ __device__ __forceinline__ void store_gated(const Out &o, float4v g, float4v u, 
     }
 }
 
+// Rotary epilogue: lo / hi are the sums of elements d .. d+3 and d + D/2 .. of one head of one row (packed
+// tiles 2j and 2j+1 of the head are tile j of its first and of its second half).  They are rounded to fp16
+// first and then treated exactly as rope_append treats the linear's fp16 output -- same expressions, same
+// results bit for bit: q heads rotated into q, k heads rotated into cache row P + m, v heads copied; a row
+// whose position lies outside the tables gets its values appended and nothing else.
+// What the epilogue has to fetch -- the row's position, then its table entries -- is asked for by
+// prefetch_paired before the sums are formed (unconditionally, from clamped addresses), so that these two
+// round trips overlap with the loads of the sums instead of following them.
+struct PairedPre {
+    int p;            // position of the quad's row
+    float4v c, s;     // table entries of elements d .. d+3 at that position (clamped into the tables)
+};
+
+template <int MT>
+__device__ __forceinline__ PairedPre prefetch_paired(const Out &o, int e4, int first_col, int M, int N)
+{
+    PairedPre pre = {0, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    if (o.epi != kEpiRope) return pre;   // uniform
+    int ln = (e4 * 4) & 63, reg = e4 >> 4;
+    int i = reg & 3, tm = reg >> 2;
+    int mt = tm % MT, t = tm / MT;
+    int m = mt * 16 + 4 * (ln >> 4) + i;
+    int pc = first_col + t * 16 + (ln & 15);
+    const RopeOut &r = o.rope;
+    m = m < M ? m : M - 1;
+    pc = pc < N ? pc : N - 32;
+    const int D = r.D, h = D >> 1;
+    const int within = pc % D;
+    const int d = (within >> 5) * 16 + (within & 15);
+    pre.p = r.pos[m];
+    const int pcl = pre.p < 0 ? 0 : (pre.p < r.n_pos ? pre.p : r.n_pos - 1);
+    pre.c = *reinterpret_cast<const float4v *>(r.cos_t + (size_t)pcl * h + d);
+    pre.s = *reinterpret_cast<const float4v *>(r.sin_t + (size_t)pcl * h + d);
+    return pre;
+}
+
+template <int MT>
+__device__ __forceinline__ void store_roped(const Out &o, float4v lo, float4v hi, const PairedPre &pre, int e4,
+                                            int first_col, int M, int N)
+{
+    int ln = (e4 * 4) & 63, reg = e4 >> 4;
+    int i = reg & 3, tm = reg >> 2;
+    int mt = tm % MT, t = tm / MT;          // t is even: a first-half tile
+    int m = mt * 16 + 4 * (ln >> 4) + i;
+    int pc = first_col + t * 16 + (ln & 15);   // packed column of the first-half quad
+    if (m >= M || pc >= N) return;
+    const RopeOut &r = o.rope;
+    const int D = r.D, h = D >> 1;
+    const int head = pc / D, within = pc - head * D;
+    const int d = (within >> 5) * 16 + (within & 15);
+    const half4v l16 = {(_Float16)lo[0], (_Float16)lo[1], (_Float16)lo[2], (_Float16)lo[3]};
+    const half4v h16 = {(_Float16)hi[0], (_Float16)hi[1], (_Float16)hi[2], (_Float16)hi[3]};
+    if (head >= r.Hq + r.Hkv) {   // value head: appended as it is
+        _Float16 *dst = r.v_cache + ((size_t)(r.P + m) * r.Hkv + (head - r.Hq - r.Hkv)) * D;
+        *reinterpret_cast<half4v *>(dst + d) = l16;
+        *reinterpret_cast<half4v *>(dst + d + h) = h16;
+        return;
+    }
+    if (pre.p < 0 || pre.p >= r.n_pos) return;
+    half4v olo, ohi;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float a = (float)l16[e], b = (float)h16[e];
+        olo[e] = (_Float16)keep_f32(fmaf(a, pre.c[e], -b * pre.s[e]));
+        ohi[e] = (_Float16)keep_f32(fmaf(b, pre.c[e], a * pre.s[e]));
+    }
+    _Float16 *dst = head < r.Hq ? r.q + ((size_t)m * r.Hq + head) * D
+                                : r.k_cache + ((size_t)(r.P + m) * r.Hkv + (head - r.Hq)) * D;
+    *reinterpret_cast<half4v *>(dst + d) = olo;
+    *reinterpret_cast<half4v *>(dst + d + h) = ohi;
+}
+
+// a paired epilogue for the quad e4 of an even packed tile (a) and its partner 64 * MT quads further on (b)
+template <int MT>
+__device__ __forceinline__ void store_paired(const Out &o, float4v a, float4v b, const PairedPre &pre, int e4,
+                                             int first_col, int M, int N)
+{
+    if (o.epi == kEpiRope) store_roped<MT>(o, a, b, pre, e4, first_col, M, N);   // uniform
+    else store_gated<MT>(o, a, b, e4, first_col, M, N);
+}
+
 constexpr int kFlatMaxRows = 4;   // most rows the all-loads-up-front variant stages
 
 // wavefronts per SIMD the register allocator must leave room for: one workgroup has to fit
@@ -446,16 +539,17 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
                 lds[(wave * R + (t * MT + mt) * 4 + i) * 64 + lane] = acc[t][mt][i];
     __syncthreads();
     const int first_col = nb * kBlockCols + t0 * 16;
-    if (S == 1 && y.epi == kEpiSiluMul) {   // uniform
+    if (S == 1 && paired_epilogue(y)) {   // uniform
         for (int idx = tid; idx < E4 / 2; idx += kThreads) {
             const int e4 = gate_quad<MT>(idx);
+            const PairedPre pre = prefetch_paired<MT>(y, e4, first_col, M, N);
             float4v g = lds4[e4], u = lds4[e4 + 64 * MT];
 #pragma unroll
             for (int w2 = 1; w2 < NW; ++w2) {
                 g += lds4[w2 * E4 + e4];
                 u += lds4[w2 * E4 + e4 + 64 * MT];
             }
-            store_gated<MT>(y, g, u, e4, first_col, M, N);
+            store_paired<MT>(y, g, u, pre, e4, first_col, M, N);
         }
         return;
     }
@@ -505,12 +599,13 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
     __syncthreads();
     if (ticket_sh != (uint32_t)(S - 1)) return;
     const auto load = [&](int index) { return load_partial(all, index); };
-    if (y.epi == kEpiSiluMul) {   // uniform
+    if (paired_epilogue(y)) {   // uniform
         for (int idx = tid; idx < E4 / 2; idx += kThreads) {
             const int pair[2] = {gate_quad<MT>(idx), gate_quad<MT>(idx) + 64 * MT};
+            const PairedPre pre = prefetch_paired<MT>(y, pair[0], first_col, M, N);
             float4v gu[2];
             sum_partials<2>(gu, pair, S, E4, load);
-            store_gated<MT>(y, gu[0], gu[1], pair[0], first_col, M, N);
+            store_paired<MT>(y, gu[0], gu[1], pre, pair[0], first_col, M, N);
         }
         if (tid == 0) __hip_atomic_store(&tickets[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
@@ -835,10 +930,11 @@ __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW
             for (int k4 = 0; k4 < 4; ++k4) mine_lds[((t * MT + mt) * 4 + k4) * 64 + lane] = acc[t][mt][k4];
     if (!active) return;
     const int first_col = nb * kBlockCols + t0 * 16;
-    if (S == 1 && y.epi == kEpiSiluMul) {   // uniform
+    if (S == 1 && paired_epilogue(y)) {   // uniform
         for (int idx = lane; idx < E4 / 2; idx += 64) {
             const int e4 = gate_quad<MT>(idx);
-            store_gated<MT>(y, out4[wave * E4 + e4], out4[wave * E4 + e4 + 64 * MT], e4, first_col, M, N);
+            const PairedPre pre = prefetch_paired<MT>(y, e4, first_col, M, N);
+            store_paired<MT>(y, out4[wave * E4 + e4], out4[wave * E4 + e4 + 64 * MT], pre, e4, first_col, M, N);
         }
         return;
     }
@@ -1039,16 +1135,17 @@ __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const
     const int first_col = nb * kBlockCols + t0 * 16;
     if (S == 1) {
         if (!active) return;
-        if (y.epi == kEpiSiluMul) {   // uniform
+        if (paired_epilogue(y)) {   // uniform
             for (int idx = kset * 64 + lane; idx < E4 / 2; idx += 64 * KS) {
                 const int e4 = gate_quad<MT>(idx);
+                const PairedPre pre = prefetch_paired<MT>(y, e4, first_col, M, N);
                 float4v g = out4[colq * E4 + e4], u = out4[colq * E4 + e4 + 64 * MT];
 #pragma unroll
                 for (int s = 1; s < KS; ++s) {
                     g += out4[(s * 4 + colq) * E4 + e4];
                     u += out4[(s * 4 + colq) * E4 + e4 + 64 * MT];
                 }
-                store_gated<MT>(y, g, u, e4, first_col, M, N);
+                store_paired<MT>(y, g, u, pre, e4, first_col, M, N);
             }
             return;
         }
@@ -1096,12 +1193,13 @@ __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const
     if (tid == 0) __hip_atomic_store(&tickets[wg_unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (!active) return;
     const auto load = [&](int index) { return load_partial(all, index); };
-    if (y.epi == kEpiSiluMul) {   // uniform
+    if (paired_epilogue(y)) {   // uniform
         for (int idx = kset * 64 + lane; idx < E4 / 2; idx += 64 * KS) {
             const int pair[2] = {gate_quad<MT>(idx), gate_quad<MT>(idx) + 64 * MT};
+            const PairedPre pre = prefetch_paired<MT>(y, pair[0], first_col, M, N);
             float4v gu[2];
             sum_partials<2>(gu, pair, S, E4, load);
-            store_gated<MT>(y, gu[0], gu[1], pair[0], first_col, M, N);
+            store_paired<MT>(y, gu[0], gu[1], pre, pair[0], first_col, M, N);
         }
         return;
     }
@@ -1166,12 +1264,13 @@ __global__ __launch_bounds__(kReduceThreads) void splitk_reduce_kernel(const flo
     const float4v *all = reinterpret_cast<const float4v *>(partial) + (size_t)unit * S * E4;
     const auto load = [&](int index) { return all[index]; };
     const int first_col = nb * kBlockCols + t0 * 16;
-    if (y.epi == kEpiSiluMul) {   // uniform
+    if (paired_epilogue(y)) {   // uniform
         for (int idx = tid; idx < E4 / 2; idx += kReduceThreads) {
             const int pair[2] = {gate_quad<MT>(idx), gate_quad<MT>(idx) + 64 * MT};
+            const PairedPre pre = prefetch_paired<MT>(y, pair[0], first_col, M, N);
             float4v gu[2];
             sum_partials<2>(gu, pair, S, E4, load);
-            store_gated<MT>(y, gu[0], gu[1], pair[0], first_col, M, N);
+            store_paired<MT>(y, gu[0], gu[1], pre, pair[0], first_col, M, N);
         }
         return;
     }
@@ -1579,6 +1678,22 @@ int w4a16_gemm_fused(const void *x, const void *packed, void *y, int M, int N, i
                   "public and internal epilogue codes agree");
     return gemm_entry(x, packed, Out{(_Float16 *)y, (const _Float16 *)residual, epilogue}, M, N, K, G, workspace,
                       workspace_bytes, stream);
+}
+
+
+int w4a16_gemm_rope(const void *x, const void *packed, int M, int K, int G, const int32_t *pos, const float *cos_table,
+                    const float *sin_table, int n_pos, void *q, void *k_cache, void *v_cache, int P, int Hq, int Hkv, int D,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (P < 0 || Hq < 1 || Hkv < 1 || D < 32 || D % 32 != 0 || n_pos < 1) return W4A16_EINVAL;
+    if ((long long)(Hq + 2 * Hkv) * D > 0x7fffffff) return W4A16_EUNSUP;
+    if (!pos || !cos_table || !sin_table || !q || !k_cache || !v_cache) return W4A16_ENULL;
+    if (misaligned(q) || misaligned(k_cache) || misaligned(v_cache) || misaligned(cos_table) || misaligned(sin_table) ||
+        (reinterpret_cast<uintptr_t>(pos) & 3u))
+        return W4A16_EALIGN;
+    Out out = {(_Float16 *)q, nullptr, kEpiRope,
+               {pos, cos_table, sin_table, (_Float16 *)q, (_Float16 *)k_cache, (_Float16 *)v_cache, n_pos, P, Hq, Hkv, D}};
+    return gemm_entry(x, packed, out, M, (Hq + 2 * Hkv) * D, K, G, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -29,6 +29,15 @@ __device__ __forceinline__ void fetch_arguments_together(const T &...args)
     (..., [](const T &a) { asm volatile("" ::"s"(a)); }(args));
 }
 
+// An fp32 value the compiler must materialise as such.  Without it a following conversion to fp16 may or may
+// not be folded into the multiply-add that produced the value (one rounding instead of two), kernel by kernel:
+// the rotary arithmetic exists in three kernels that have to agree bit for bit.
+__device__ __forceinline__ float keep_f32(float v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
 inline int launch_status()
 {
     return hipGetLastError() == hipSuccess ? W4A16_OK : W4A16_EHIP;

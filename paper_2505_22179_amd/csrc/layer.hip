@@ -85,8 +85,8 @@ __global__ __launch_bounds__(kRopeThreads) void rope_append_scalar_kernel(
         } else if (in_table) {
             const float lo = (float)src[i], hi = (float)src[i + h];
             _Float16 *dst = head < Hq ? q + ((size_t)m * Hq + head) * D : k_cache + ((size_t)(P + m) * Hkv + (head - Hq)) * D;
-            dst[i] = (_Float16)fmaf(lo, c, -hi * s);
-            dst[i + h] = (_Float16)fmaf(hi, c, lo * s);
+            dst[i] = (_Float16)keep_f32(fmaf(lo, c, -hi * s));
+            dst[i + h] = (_Float16)keep_f32(fmaf(hi, c, lo * s));
         }
     }
 }
@@ -146,8 +146,8 @@ __global__ __launch_bounds__(kRopeThreads) void rope_append_kernel(
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float a = (float)lo[u][e], b = (float)hi[u][e];
-                    olo[e] = (_Float16)fmaf(a, c[e], -b * s[e]);
-                    ohi[e] = (_Float16)fmaf(b, c[e], a * s[e]);
+                    olo[e] = (_Float16)keep_f32(fmaf(a, c[e], -b * s[e]));
+                    ohi[e] = (_Float16)keep_f32(fmaf(b, c[e], a * s[e]));
                 }
                 *reinterpret_cast<half4 *>(dst + i) = olo;
                 *reinterpret_cast<half4 *>(dst + i + h) = ohi;
@@ -204,18 +204,24 @@ extern "C" int w4a16_decoder_layer(const w4a16_layer_weights *w, void *h, int M,
     if (H < 1 || Hq < 1 || Hkv < 1 || D < 1 || F < 1 || M < 1 || P < 0) return W4A16_EINVAL;
     if (!w->qkv_packed || !w->o_packed || !w->gate_up_packed || !w->down_packed || !w->norm1_gamma || !w->norm2_gamma)
         return W4A16_ENULL;
-    if (!h || !s->norm || !s->qkv || !s->q || !s->attn || !s->act) return W4A16_ENULL;
+    if (!h || !s->norm || (!s->qkv && !w->qkv_heads_packed) || !s->q || !s->attn || !s->act) return W4A16_ENULL;
     const int Nqkv = (Hq + 2 * Hkv) * D;
     const float scale = 1.0f / sqrtf((float)D);
     int rc;
     // attention block: h += Wo . attn(rope(Wqkv . norm(h)))
     if ((rc = rms_norm(h, w->norm1_gamma, s->norm, M, H, w->eps, stream)) != W4A16_OK) return rc;
-    if ((rc = w4a16_gemm(s->norm, w->qkv_packed, s->qkv, M, Nqkv, H, kGroup, s->gemm_workspace, s->gemm_workspace_bytes,
-                         stream)) != W4A16_OK)
-        return rc;
-    if ((rc = rope_append(s->qkv, pos, cos_table, sin_table, n_pos, s->q, k_cache, v_cache, M, P, Hq, Hkv, D, stream)) !=
-        W4A16_OK)
-        return rc;
+    if (w->qkv_heads_packed) {   // projection, rotary embedding and K/V append in one kernel
+        if ((rc = w4a16_gemm_rope(s->norm, w->qkv_packed, M, H, kGroup, pos, cos_table, sin_table, n_pos, s->q, k_cache,
+                                  v_cache, P, Hq, Hkv, D, s->gemm_workspace, s->gemm_workspace_bytes, stream)) != W4A16_OK)
+            return rc;
+    } else {
+        if ((rc = w4a16_gemm(s->norm, w->qkv_packed, s->qkv, M, Nqkv, H, kGroup, s->gemm_workspace, s->gemm_workspace_bytes,
+                             stream)) != W4A16_OK)
+            return rc;
+        if ((rc = rope_append(s->qkv, pos, cos_table, sin_table, n_pos, s->q, k_cache, v_cache, M, P, Hq, Hkv, D, stream)) !=
+            W4A16_OK)
+            return rc;
+    }
     if ((rc = tree_verify_attn(s->q, k_cache, v_cache, mask, s->attn, M, P, Hq, Hkv, D, scale, s->attn_workspace,
                                s->attn_workspace_bytes, stream)) != W4A16_OK)
         return rc;

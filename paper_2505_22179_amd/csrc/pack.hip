@@ -23,21 +23,23 @@ __device__ __forceinline__ uint32_t permute_fields_to_canonical(uint32_t packed)
     return out;
 }
 
-// canonical column held at packed column n (n < N): n itself, or -- paired layout -- the tiles of
-// the two halves of the weight alternate: packed tile 2j is tile j of columns 0..N/2-1, packed tile
-// 2j+1 is tile j of columns N/2..N-1
-__device__ __forceinline__ int source_column(int n, int N, int paired)
+// canonical column held at packed column n (n < N): n itself, or -- paired layout, pair_block > 0 -- inside
+// every block of pair_block columns the tiles of the block's two halves alternate: packed tile 2j of the
+// block is tile j of its first half, packed tile 2j+1 tile j of its second half.  pair_block = N pairs a
+// gate projection with its up projection; pair_block = head_dim pairs the two halves of every head.
+__device__ __forceinline__ int source_column(int n, int N, int pair_block)
 {
-    if (!paired) return n;
-    const int tile = n >> 4;
-    return (tile & 1) * (N >> 1) + (tile >> 1) * 16 + (n & 15);
+    if (!pair_block) return n;
+    const int block = n / pair_block, within = n - block * pair_block;
+    const int tile = within >> 4;
+    return block * pair_block + (tile & 1) * (pair_block >> 1) + (tile >> 1) * 16 + (within & 15);
 }
 
 // one thread per (record, tile, lane): writes the lane's 16 bytes of codes; threads with t == 0
 // and r == 0 also write the record's scales and zero-points for their column index c.
 __global__ void pack_kernel(const uint32_t *__restrict__ qweight, const uint16_t *__restrict__ scales,
                             const uint32_t *__restrict__ qzeros, uint8_t *__restrict__ packed,
-                            int N, int K, long long total, int paired)
+                            int N, int K, long long total, int pair_block)
 {
     long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
@@ -51,7 +53,7 @@ __global__ void pack_kernel(const uint32_t *__restrict__ qweight, const uint16_t
     int n = nb * kBlockCols + t * 16 + c;
     uint8_t *base = packed + record_offset(nb, g, groups);
     uint4 w = make_uint4(0, 0, 0, 0);
-    const int src = n < N ? source_column(n, N, paired) : 0;
+    const int src = n < N ? source_column(n, N, pair_block) : 0;
     if (n < N) {
         uint32_t v[4];
 #pragma unroll
@@ -72,7 +74,7 @@ __global__ void pack_kernel(const uint32_t *__restrict__ qweight, const uint16_t
                 int nn = nb * kBlockCols + tt * 16 + c;
                 uint32_t z = 0;
                 if (nn < N) {
-                    const int ns = source_column(nn, N, paired);
+                    const int ns = source_column(nn, N, pair_block);
                     z = (qzeros[(size_t)g * (N / 8) + (ns >> 3)] >> (4 * (ns & 7))) & 0xFu;
                 }
                 zw |= z << (4 * tt);
@@ -253,17 +255,17 @@ int w4a16_read_probe(const void *buf, size_t bytes, void *sink, void *stream)
 }
 
 static int pack_entry(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
-                      int N, int K, int G, void *stream, int paired)
+                      int N, int K, int G, void *stream, int pair_block)
 {
     int rc = check_weight_shape(N, K, G);
     if (rc != W4A16_OK) return rc;
-    if (paired && N % 32 != 0) return W4A16_EINVAL;
+    if (pair_block && (pair_block < 32 || pair_block % 32 != 0 || N % pair_block != 0)) return W4A16_EINVAL;
     if (!qweight || !scales || !qzeros || !packed) return W4A16_ENULL;
     if (misaligned(qweight) || misaligned(scales) || misaligned(qzeros) || misaligned(packed)) return W4A16_EALIGN;
     long long total = (long long)(pad_cols(N) / kBlockCols) * (K / kGroup) * 512;
     hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
                        (const uint32_t *)qweight, (const uint16_t *)scales, (const uint32_t *)qzeros,
-                       (uint8_t *)packed, N, K, total, paired);
+                       (uint8_t *)packed, N, K, total, pair_block);
     return launch_status();
 }
 
@@ -276,7 +278,14 @@ int w4a16_pack(const int32_t *qweight, const void *scales, const int32_t *qzeros
 int w4a16_pack_gate_up(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
                        int N, int K, int G, void *stream)
 {
-    return pack_entry(qweight, scales, qzeros, packed, N, K, G, stream, 1);
+    return pack_entry(qweight, scales, qzeros, packed, N, K, G, stream, N > 0 ? N : 1);
+}
+
+int w4a16_pack_heads(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
+                     int N, int K, int G, int head_dim, void *stream)
+{
+    if (head_dim < 32) return W4A16_EINVAL;
+    return pack_entry(qweight, scales, qzeros, packed, N, K, G, stream, head_dim);
 }
 
 int w4a16_unpack(const void *packed, int32_t *qweight, void *scales, int32_t *qzeros,

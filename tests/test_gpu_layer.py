@@ -76,6 +76,23 @@ def test_pack_gate_up_is_pack_of_permuted_columns(K, N):
     assert np.array_equal(sc.cpu().numpy().view(np.uint16), inp.scales[:, perm].view(np.uint16))
 
 
+@pytest.mark.parametrize("K,N,D", [(128, 64, 32), (256, 384, 128), (384, 320, 64), (1024, 1280, 128)])
+def test_pack_heads_is_pack_of_permuted_columns(K, N, D):
+    inp = I.make_linear(8150 + K + N, 1, K, N)
+    packed = B.pack_from_numpy(inp, head_dim=D)
+    W = torch.empty((K, N), dtype=torch.float32, device=DEV)
+    B.w4a16_dequant(packed, W, N, K)
+    torch.cuda.synchronize()
+    perm = np.empty(N, dtype=np.int64)
+    for n in range(N):          # inside a head: packed tile 2j = tile j of the first half, 2j+1 = tile j of the second
+        head, within = divmod(n, D)
+        tile, c = divmod(within, 16)
+        perm[n] = head * D + (tile % 2) * (D // 2) + (tile // 2) * 16 + c
+    assert sorted(perm.tolist()) == list(range(N))
+    Wref = R.dequant(inp.qweight, inp.scales, inp.qzeros, 128)[:, perm]
+    assert np.array_equal(W.cpu().numpy().view(np.uint32), np.ascontiguousarray(Wref).view(np.uint32))
+
+
 # ---- fused epilogues -----------------------------------------------------------------------------
 
 # knob settings that reach every kernel family and every way the K splits are summed
@@ -320,6 +337,91 @@ def test_rope_position_outside_the_tables_is_skipped():
     assert np.array_equal(vo[P:], qkv.reshape(M, Hq + 2 * Hkv, D)[:, Hq + Hkv:])
 
 
+# ---- the q/k/v projection with the rotary embedding and the append in its store ----------------------
+
+ROPE_CASES = [(1, 1024, 4, 2, 64, 0), (5, 512, 2, 1, 128, 9), (17, 2048, 3, 1, 32, 40), (40, 1024, 8, 2, 64, 3), (64, 2048, 4, 4, 128, 100),
+              (3, 4096, 6, 2, 128, 7)]
+
+
+def gemm_rope_both_ways(inp, M, K, Hq, Hkv, D, P, pos, ws, plain, heads):
+    """(q, k_cache, v_cache) from w4a16_gemm + rope_append and from w4a16_gemm_rope, same knobs"""
+    N = (Hq + 2 * Hkv) * D
+    rng = np.random.default_rng(9777)
+    cos, sin = I.make_rope_tables(P + 16, D)
+    kc = rng.standard_normal((P + M + 2, Hkv, D), dtype=np.float32).astype(np.float16)
+    vc = rng.standard_normal((P + M + 2, Hkv, D), dtype=np.float32).astype(np.float16)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    x, posd, cosd, sind = dev(inp.x), dev(pos), dev(cos), dev(sin)
+    out = []
+    for fused in (False, True):
+        q = torch.full((M + 1, Hq, D), SENTINEL, dtype=torch.float16, device=DEV)
+        kd, vd = dev(kc), dev(vc)
+        if fused:
+            B.w4a16_gemm_rope(x, heads, M, K, 128, posd, cosd, sind, P + 16, q, kd, vd, P, Hq, Hkv, D, ws)
+        else:
+            qkv = torch.empty((M, N), dtype=torch.float16, device=DEV)
+            B.w4a16_gemm(x, plain, qkv, M, N, K, 128, ws)
+            B.rope_append(qkv, posd, cosd, sind, P + 16, q, kd, vd, M, P, Hq, Hkv, D)
+        torch.cuda.synchronize()
+        out.append((q.cpu().numpy(), kd.cpu().numpy(), vd.cpu().numpy()))
+    return out, (cos, sin, kc, vc)
+
+
+@pytest.mark.parametrize("M,K,Hq,Hkv,D,P", ROPE_CASES)
+def test_gemm_rope_is_gemm_then_rope_append(M, K, Hq, Hkv, D, P, big_ws):
+    """every kernel family and reduction mode: q, the cache rows and everything around them bit for bit"""
+    print(f"projection + rotary + append in one kernel M={M} K={K} Hq={Hq} Hkv={Hkv} D={D} P={P}", flush=True)
+    N = (Hq + 2 * Hkv) * D
+    inp = I.make_linear(9700 + M + K + N, M, K, N)
+    plain, heads = B.pack_from_numpy(inp), B.pack_from_numpy(inp, head_dim=D)
+    pos = (P + np.arange(M) % 7).astype(np.int32)
+    if M >= 3:
+        pos[1], pos[2] = -1, P + 16   # outside the tables: that row's q and k stay untouched, its v is appended
+    ran = []
+    for name in each_family(M, K):
+        (two, one), _ = gemm_rope_both_ways(inp, M, K, Hq, Hkv, D, P, pos, big_ws, plain, heads)
+        for a, b, what in zip(two, one, ("q", "k_cache", "v_cache")):
+            assert np.array_equal(a.view(np.uint16), b.view(np.uint16)), f"{what}, {name}"
+        ran.append(name)
+    assert len(ran) >= 4, ran
+    if M >= 3:
+        assert (one[0][1:3] == np.float16(SENTINEL)).all()
+
+
+def test_gemm_rope_against_the_oracle(big_ws):
+    M, K, Hq, Hkv, D, P = 12, 1024, 4, 2, 64, 30
+    N = (Hq + 2 * Hkv) * D
+    inp = I.make_linear(9790, M, K, N)
+    parent, _, _ = I.make_tree(9791, M, 4, 3)
+    pos = I.tree_positions(parent, P)
+    (_, (q, kd, vd)), (cos, sin, kc, vc) = gemm_rope_both_ways(inp, M, K, Hq, Hkv, D, P, pos, big_ws, B.pack_from_numpy(inp),
+                                                            B.pack_from_numpy(inp, head_dim=D))
+    _, y64, y16 = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros)
+    q64, _, k_want, v_want = R.rope_append(y16, pos, cos, sin, kc, vc, P, Hq, Hkv, D)
+    # one more fp16 rounding than the linear alone (the projection's own), then rope_append's bar
+    assert (np.abs(q[:M].astype(np.float64) - q64) <= 1.5 * fp16_ulp(q64) + 1e-2).all()
+    rel = np.linalg.norm(q[:M].astype(np.float64) - q64) / np.linalg.norm(q64)
+    assert rel <= 1e-3, rel
+    assert (np.abs(kd[P:P + M].astype(np.float64) - k_want[P:P + M].astype(np.float64)) <= 1e-2 + 1.5 * fp16_ulp(k_want[P:P + M].astype(np.float64))).all()
+    check_gemm(vd[P:P + M].reshape(M, Hkv * D), y64.reshape(M, Hq + 2 * Hkv, D)[:, Hq + Hkv:].reshape(M, Hkv * D), "appended values")
+    assert np.array_equal(kd[:P].view(np.uint16), kc[:P].view(np.uint16)) and np.array_equal(kd[P + M:].view(np.uint16), kc[P + M:].view(np.uint16))
+
+
+@pytest.mark.parametrize("M", [1, 7, 60])
+def test_gemm_rope_model_shapes(M):
+    """Llama-3-70B and 8B q/k/v projections, committed launch plans: the one kernel against the two"""
+    for K, Hq, Hkv, D in ((8192, 64, 8, 128), (4096, 32, 8, 128)):
+        N = (Hq + 2 * Hkv) * D
+        print(f"   K={K} N={N} M={M}", flush=True)
+        inp = I.make_linear(9795 + M + K, M, K, N)
+        ws = B.new_workspace(B.w4a16_workspace_bytes(M, N, K))
+        parent = I.make_tree(9796, M, 6, 4)[0] if M > 6 else np.arange(-1, M - 1)
+        pos = I.tree_positions(parent, 2048)
+        (two, one), _ = gemm_rope_both_ways(inp, M, K, Hq, Hkv, D, 2048, pos, ws, B.pack_from_numpy(inp), B.pack_from_numpy(inp, head_dim=D))
+        for a, b, what in zip(two, one, ("q", "k_cache", "v_cache")):
+            assert np.array_equal(a.view(np.uint16), b.view(np.uint16)), f"{what}, K={K}"
+
+
 # ---- a whole decoder layer from the library's entry points -----------------------------------------
 
 def test_decoder_layer_chain(big_ws):
@@ -376,6 +478,15 @@ def test_decoder_layer_chain(big_ws):
     B.w4a16_decoder_layer(weights, hd, M, P, posd, cosd, sind, P + 16, maskd, kd1, vd1, scratch)
     torch.cuda.synchronize()
     assert np.array_equal(host(hd).view(np.uint16), h2.view(np.uint16)), "one-call layer differs from the chained calls"
+    assert np.array_equal(host(kd1).view(np.uint16), kd.view(np.uint16)) and np.array_equal(host(vd1).view(np.uint16), vd.view(np.uint16))
+    # and with the rotary embedding and the append inside the q/k/v projection (no qkv scratch): the same bits again
+    hd, kd1, vd1 = dev(h0), dev(kc), dev(vc)
+    weights = B.layer_weights(B.pack_from_numpy(lin["qkv"], head_dim=D), packed["o"], packed["gate_up"], packed["down"], g1d, g2d,
+                              H, Hq, Hkv, D, Iff, 1e-5, qkv_heads_packed=True)
+    scratch = B.layer_scratch(bufs[0], None, *bufs[2:], big_ws, aws)
+    B.w4a16_decoder_layer(weights, hd, M, P, posd, cosd, sind, P + 16, maskd, kd1, vd1, scratch)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(hd).view(np.uint16), h2.view(np.uint16)), "layer with the fused projection differs"
     assert np.array_equal(host(kd1).view(np.uint16), kd.view(np.uint16)) and np.array_equal(host(vd1).view(np.uint16), vd.view(np.uint16))
     # step by step, each oracle step on the GPU's input to that step
     close_to_rounded(n1, R.rms_norm(h0, g1, 1e-5)[0], "norm 1")
