@@ -150,6 +150,32 @@ def test_layer_glue_validation_happens_before_any_gpu_call():
     assert r(a, a, a, a, 64, a + 8, a, a, 4, 10, 8, 2, 128, None) == EALIGN
 
 
+def test_gemm_rope_validation_happens_before_any_gpu_call():
+    lib = B.load()
+    a = 0x1000
+    EINVAL, ENULL, EALIGN, EUNSUP = -1, -2, -3, -4
+    ph = lib.w4a16_pack_heads
+    assert ph(a, a, a, a, 10240, 8192, 128, 16, None) == EINVAL      # heads of fewer than 32 columns
+    assert ph(a, a, a, a, 10240, 8192, 128, 48, None) == EINVAL      # not a multiple of 32
+    assert ph(a, a, a, a, 10240, 8192, 128, 96, None) == EINVAL      # N is not a whole number of heads
+    assert ph(a, a, None, a, 10240, 8192, 128, 128, None) == ENULL
+    assert ph(a, a, a, a + 8, 10240, 8192, 128, 128, None) == EALIGN
+    g = lib.w4a16_gemm_rope
+    ok = dict(x=a, packed=a, M=4, K=8192, G=128, pos=a, cos=a, sin=a, n_pos=64, q=a, k=a, v=a, P=10, Hq=64, Hkv=8, D=128)
+
+    def call(**kw):
+        v = {**ok, **kw}
+        return g(v["x"], v["packed"], v["M"], v["K"], v["G"], v["pos"], v["cos"], v["sin"], v["n_pos"], v["q"], v["k"], v["v"],
+                 v["P"], v["Hq"], v["Hkv"], v["D"], a, 1 << 30, None)
+
+    assert call(P=-1) == EINVAL and call(Hkv=0) == EINVAL and call(n_pos=0) == EINVAL
+    assert call(D=16) == EINVAL and call(D=80) == EINVAL           # head size: a multiple of 32
+    assert call(pos=None) == ENULL and call(q=None) == ENULL and call(v=None) == ENULL
+    assert call(cos=a + 4) == EALIGN and call(k=a + 8) == EALIGN and call(pos=a + 2) == EALIGN
+    assert call(M=0) == EINVAL and call(M=65) == EUNSUP and call(x=None) == ENULL   # the linear's own checks
+    assert call(K=8200) == EINVAL
+
+
 def test_lm_head_validation_happens_before_any_gpu_call():
     lib = B.load()
     a = 0x1000
