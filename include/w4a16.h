@@ -88,7 +88,9 @@ size_t w4a16_workspace_bytes(int M_max, int N, int K, int G);
 /* Zero the ticket area at the start of a workspace.  Must be enqueued once before the first
  * w4a16_gemm / tree_verify_attn that uses the buffer; each of those calls leaves the tickets zero
  * again, so one initialisation serves any number of later calls (of any shape that fits).  Two
- * calls that may run concurrently must not share a workspace. */
+ * calls that may run concurrently must not share a workspace.  A workspace must be 256-byte aligned
+ * (W4A16_EALIGN otherwise): workgroups exchange partial sums through it inside a kernel, cache line by
+ * cache line, and no line may belong to two of them. */
 int w4a16_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Re-lay the canonical quantised weight into the streaming layout the GEMM kernels read

@@ -605,7 +605,7 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
     int rc = check_attn(M, P, Hq, Hkv, D);
     if (rc != W4A16_OK) return rc;
     if (!q || !k || !v || !mask || !out) return W4A16_ENULL;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(workspace)) return W4A16_EALIGN;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || workspace_misaligned(workspace)) return W4A16_EALIGN;
     const int rep = attn_rep(M, Hq, Hkv);
     const int units = rep ? Hq / rep : Hq;
     const int ns = attn_splits(M, P, units);

@@ -1642,7 +1642,7 @@ static int gemm_entry(const void *x, const void *packed, const Out &out, int M, 
     if (M < 1) return W4A16_EINVAL;
     if (M > W4A16_MAX_M) return W4A16_EUNSUP;
     if (!x || !packed || !out.y) return W4A16_ENULL;
-    if (misaligned(x) || misaligned(packed) || misaligned(out.y) || misaligned(workspace)) return W4A16_EALIGN;
+    if (misaligned(x) || misaligned(packed) || misaligned(out.y) || workspace_misaligned(workspace)) return W4A16_EALIGN;
     const int nblocks = pad_cols(N) / kBlockCols;
     const int mt = (M + 15) / 16;
     Plan pl = choose_plan(M, N, K);

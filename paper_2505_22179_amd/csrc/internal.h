@@ -8,6 +8,9 @@
 namespace w4 {
 
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+// workspaces: 256 bytes, so that the partial-sum region of one workgroup never shares a cache line with
+// another's -- the exchange of partials inside a kernel goes through device-scope accesses line by line
+inline bool workspace_misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) != 0; }
 
 // shape checks common to every weight entry point; returns W4A16_OK or an error code
 inline int check_weight_shape(int N, int K, int G)

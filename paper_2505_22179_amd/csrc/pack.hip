@@ -234,7 +234,7 @@ size_t w4a16_packed_bytes(int N, int K, int G)
 int w4a16_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!workspace) return W4A16_ENULL;
-    if (misaligned(workspace)) return W4A16_EALIGN;
+    if (workspace_misaligned(workspace)) return W4A16_EALIGN;
     if (workspace_bytes < kTicketBytes) return W4A16_EWORKSPACE;
     size_t words = kTicketBytes / 4;
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,

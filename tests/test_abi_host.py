@@ -150,6 +150,14 @@ def test_layer_glue_validation_happens_before_any_gpu_call():
     assert r(a, a, a, a, 64, a + 8, a, a, 4, 10, 8, 2, 128, None) == EALIGN
 
 
+def test_workspaces_must_be_256_byte_aligned():
+    lib = B.load()
+    a = 0x1000
+    assert lib.w4a16_workspace_init(a + 128, 1 << 20, None) == -3
+    assert lib.w4a16_gemm(a, a, a, 1, 4096, 4096, 128, a + 16, 1 << 30, None) == -3
+    assert lib.tree_verify_attn(a, a, a, a, a, 4, 100, 8, 2, 128, 0.1, a + 64, 1 << 30, None) == -3
+
+
 def test_gemm_rope_validation_happens_before_any_gpu_call():
     lib = B.load()
     a = 0x1000
