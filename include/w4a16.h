@@ -47,35 +47,6 @@ int w4a16_version(void);
 /* Static, NUL-terminated description of a return code. */
 const char *w4a16_strerror(int code);
 
-/* Ablation knob for benchmarks and tests: overrides an internal launch heuristic process-wide.
- * Names: "split_k" (0 = heuristic, else forced number of K splits), "fused_reduce" (1 = the last
- * workgroup of a column unit sums the split-K partials inside the GEMM kernel, 0 = a second
- * kernel does, 2 = per-shape choice, the default),
- * "tiles_per_wave" (0 = heuristic, else 2, 4 or 8 sixteen-column tiles per wavefront),
- * "waves_per_wg" (0 = heuristic; 4, 8 or 16 wavefronts per workgroup that split K; 1 selects the
- * variant whose four wavefronts split the columns and share x through LDS), "prefetch_depth" (0 =
- * heuristic, else 1, 2 or 4 groups of codes in flight per wavefront), "k_sets" (0 = heuristic, else
- * 1, 2 or 3: forces the M > 16 variant whose workgroup has 4 * k_sets wavefronts, four column
- * quarters times k_sets interleaved sets of quantisation groups; waves_per_wg is then ignored and
- * fused_reduce = 2 means the second kernel), "even_split" (with k_sets: 1 deals the (column unit, group)
- * pairs in equal runs to one workgroup per compute unit instead of splitting K into split_k equal parts
- * per unit; the runs that share a unit are summed by the last to arrive), "flat_groups" (0 = heuristic, else 4, 7 or 8: forces the M <= 4 variant in which a
- * wavefront owns that many quantisation groups and requests all of their weights up front; needs
- * K / 128 == split_k * waves_per_wg * flat_groups); a combination that is not compiled, or that
- * does not fit the shape, makes w4a16_gemm return W4A16_EUNSUP,
- * "attn_splits" (0 = heuristic, else the number of key ranges per row tile in tree_verify_attn),
- * "attn_pack" (how many query heads of a KV group share a row tile of tree_verify_attn: 0 = as many as keep
- * the tile within 32 rows when that is two or more, else the whole group if it fits 64 rows, else one;
- * 1 = one tile per query head always; 2 = the whole group whenever it fits 64 rows), "attn_row_tiles" (0 = chosen by the
- * number of rows in a tile; 2 = a wavefront of tree_verify_attn carries 32 query rows, in two row groups
- * for taller tiles; 4 = 64 rows, one wavefront per SIMD), "attn_fused_merge" (how the key ranges of a
- * row tile are merged: 2 = by the last of its workgroups to finish, 1 = by a second kernel, 0 = the former while
- * rows x ranges of a tile stay small), "lm_tiles" (0 = heuristic, else 1, 2 or
- * -- for more than 16 rows -- 4 vocabulary tiles per wavefront in lm_head_topk).
- * Returns W4A16_EINVAL for an unknown name or an out-of-range value.  Not thread-safe. */
-int w4a16_set_param(const char *name, int value);
-int w4a16_get_param(const char *name);
-
 /* Size in bytes of the opaque packed weight buffer for an N-column, K-row weight with group size G
  * (it holds the 4-bit codes, the fp16 scales and the 4-bit zero-points; columns are padded up to a
  * multiple of 128 inside the buffer).  0 if the shape is not supported. */
@@ -147,14 +118,6 @@ int w4a16_gemm_fused(const void *x, const void *packed, void *y, int M, int N, i
  * Requires N % 32 == 0, otherwise as w4a16_pack. */
 int w4a16_pack_gate_up(const int32_t *qweight, const void *scales, const int32_t *qzeros, void *packed,
                        int N, int K, int G, void *stream);
-
-/* Measurement aid, not part of the method: enqueues a kernel that only reads the first
- * bytes - bytes % 16 bytes of `buf` with 16-byte streaming loads (one 32 KB chunk per workgroup)
- * and writes nothing, except -- practically never -- one 32-bit word to `sink` (4-byte aligned, device)
- * so that the loads cannot be dropped.  Timed beside w4a16_gemm on the same packed buffer it
- * gives the read bandwidth this GPU reaches at that size, the ceiling the paper's memory-bound
- * decoding argument (section 2.1) refers to. */
-int w4a16_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
 
 /* Scratch needed by tree_verify_attn for these sizes (partial softmax states of the key splits). */
 size_t tree_verify_attn_workspace_bytes(int M, int P, int Hq, int Hkv, int D);
@@ -295,6 +258,63 @@ size_t lm_head_workspace_bytes(int M, int V, int K, int top_k);
  * lm_head_workspace_bytes(M, V, K, top_k) bytes and needs no initialisation.  Deterministic. */
 int lm_head_topk(const void *x, const void *packed, int M, int V, int K, int top_k, float *logits, int32_t *top_idx,
                  float *top_logprob, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------------
+ * Measurement and ablation aids.  Not part of the method's interface: nothing above needs them, a
+ * deployment never calls them.  They exist so that the benchmark and the tests can force a kernel
+ * variant, ask which variant a call would run, and time a plain read beside the GEMM.
+ * ------------------------------------------------------------------------------------------------- */
+
+/* Ablation knob for benchmarks and tests: overrides an internal launch heuristic process-wide.
+ * Names: "split_k" (0 = heuristic, else forced number of K splits), "fused_reduce" (1 = the last
+ * workgroup of a column unit sums the split-K partials inside the GEMM kernel, 0 = a second
+ * kernel does, 2 = per-shape choice, the default),
+ * "tiles_per_wave" (0 = heuristic, else 2, 4 or 8 sixteen-column tiles per wavefront),
+ * "waves_per_wg" (0 = heuristic; 4, 8 or 16 wavefronts per workgroup that split K; 1 selects the
+ * variant whose four wavefronts split the columns and share x through LDS), "prefetch_depth" (0 =
+ * heuristic, else 1, 2 or 4 groups of codes in flight per wavefront), "k_sets" (0 = heuristic, else
+ * 1, 2 or 3: forces the M > 16 variant whose workgroup has 4 * k_sets wavefronts, four column
+ * quarters times k_sets interleaved sets of quantisation groups; waves_per_wg is then ignored and
+ * fused_reduce = 2 means the second kernel), "even_split" (with k_sets: 1 deals the (column unit, group)
+ * pairs in equal runs to one workgroup per compute unit instead of splitting K into split_k equal parts
+ * per unit; the runs that share a unit are summed by the last to arrive), "flat_groups" (0 = heuristic, else 4, 7 or 8: forces the M <= 4 variant in which a
+ * wavefront owns that many quantisation groups and requests all of their weights up front; needs
+ * K / 128 == split_k * waves_per_wg * flat_groups); a combination that is not compiled, or that
+ * does not fit the shape, makes w4a16_gemm return W4A16_EUNSUP,
+ * "attn_splits" (0 = heuristic, else the number of key ranges per row tile in tree_verify_attn),
+ * "attn_pack" (how many query heads of a KV group share a row tile of tree_verify_attn: 0 = as many as keep
+ * the tile within 32 rows when that is two or more, else the whole group if it fits 64 rows, else one;
+ * 1 = one tile per query head always; 2 = the whole group whenever it fits 64 rows), "attn_row_tiles" (0 = chosen by the
+ * number of rows in a tile; 2 = a wavefront of tree_verify_attn carries 32 query rows, in two row groups
+ * for taller tiles; 4 = 64 rows, one wavefront per SIMD), "attn_fused_merge" (how the key ranges of a
+ * row tile are merged: 2 = by the last of its workgroups to finish, 1 = by a second kernel, 0 = the former while
+ * rows x ranges of a tile stay small), "lm_tiles" (0 = heuristic, else 1, 2 or
+ * -- for more than 16 rows -- 4 vocabulary tiles per wavefront in lm_head_topk).
+ * Returns W4A16_EINVAL for an unknown name or an out-of-range value.  Not thread-safe. */
+int w4a16_set_param(const char *name, int value);
+int w4a16_get_param(const char *name);
+
+/* The launch shape w4a16_gemm (and its fused forms) would use for this call with the current knobs, so
+ * that a test can show that every kernel the default plans reach has been compared with the oracle and a
+ * benchmark can name what it timed.  out receives 8 ints:
+ *   [0] kernel family: 0 = workgroup whose wavefronts split K, 1 = all loads up front (M <= 4),
+ *       2 = column-split software-pipelined, 3 = column-split with interleaved K sets
+ *   [1] 16-row tiles (ceil(M / 16))            [2] 16-column tiles per wavefront
+ *   [3] wavefronts per workgroup (families 0, 1; 1 for family 2) or K sets (family 3)
+ *   [4] groups of codes in flight per wavefront, or groups per wavefront (family 1)
+ *   [5] K splits across workgroups (0 = even split)   [6] 1 if the last workgroup of a unit sums the splits
+ *   [7] 1 if every zero-point of the weight is taken to be 8 (symmetric fast path), else 0
+ * Host only: touches no GPU.  Errors as w4a16_gemm's shape checks; W4A16_EUNSUP if the knobs name a
+ * variant that is not compiled. */
+int w4a16_plan_describe(int M, int N, int K, int G, int *out);
+
+/* Measurement aid, not part of the method: enqueues a kernel that only reads the first
+ * bytes - bytes % 16 bytes of `buf` with 16-byte streaming loads (one 32 KB chunk per workgroup)
+ * and writes nothing, except -- practically never -- one 32-bit word to `sink` (4-byte aligned, device)
+ * so that the loads cannot be dropped.  Timed beside w4a16_gemm on the same packed buffer it
+ * gives the read bandwidth this GPU reaches at that size, the ceiling the paper's memory-bound
+ * decoding argument (section 2.1) refers to. */
+int w4a16_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -17,7 +17,7 @@ EXPORTS = (
     "w4a16_workspace_bytes", "w4a16_workspace_init", "w4a16_pack", "w4a16_unpack", "w4a16_dequant",
     "w4a16_gemm", "w4a16_gemm_fused", "w4a16_gemm_rope", "w4a16_pack_heads", "w4a16_pack_gate_up", "w4a16_read_probe", "tree_verify_attn_workspace_bytes",
     "tree_verify_attn", "tree_accept", "rms_norm", "rope_append", "lm_head_workspace_bytes", "lm_head_topk",
-    "lm_head_packed_bytes", "lm_head_pack", "w4a16_decoder_layer",
+    "lm_head_packed_bytes", "lm_head_pack", "w4a16_decoder_layer", "w4a16_plan_describe",
 )
 
 EPI_NONE, EPI_RESIDUAL, EPI_SILU_MUL = 0, 1, 2
@@ -70,6 +70,7 @@ def load() -> ctypes.CDLL:
     L.w4a16_dequant.argtypes = [vp, vp, i, i, i, vp]
     L.w4a16_gemm.argtypes = [vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.w4a16_read_probe.argtypes = [vp, sz, vp, vp]
+    L.w4a16_plan_describe.argtypes = [i, i, i, i, ctypes.POINTER(ctypes.c_int)]
     L.tree_verify_attn_workspace_bytes.restype = sz
     L.tree_verify_attn_workspace_bytes.argtypes = [i, i, i, i, i]
     L.tree_verify_attn.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, ctypes.c_float, vp, sz, vp]
@@ -236,6 +237,17 @@ def lm_head_topk(x, packed, M: int, V: int, K: int, top_k: int, logits, top_idx,
 
 def w4a16_read_probe(buf, nbytes: int, sink) -> None:
     _check(load().w4a16_read_probe(_ptr(buf), int(nbytes), _ptr(sink), _stream()), "w4a16_read_probe")
+
+
+PLAN_FIELDS = ("family", "row_tiles", "tiles_per_wave", "waves_or_k_sets", "depth_or_groups", "split_k", "fused_reduce",
+               "symmetric")
+
+
+def w4a16_plan_describe(M: int, N: int, K: int, G: int = 128) -> tuple:
+    """the eight plan fields of include/w4a16.h (see PLAN_FIELDS); host only"""
+    out = (ctypes.c_int * 8)()
+    _check(load().w4a16_plan_describe(M, N, K, G, out), "w4a16_plan_describe")
+    return tuple(out)
 
 
 def tree_verify_attn(q, k, v, mask, out, M: int, P: int, Hq: int, Hkv: int, D: int, scale: float, workspace) -> None:

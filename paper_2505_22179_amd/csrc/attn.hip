@@ -580,7 +580,7 @@ static int check_attn(int M, int P, int Hq, int Hkv, int D)
 {
     if (M < 1 || P < 0 || Hq < 1 || Hkv < 1 || D < 1) return W4A16_EINVAL;
     if (Hq % Hkv != 0) return W4A16_EINVAL;
-    if (D != kHeadDim || M > W4A16_MAX_M || Hq > kMaxTickets) return W4A16_EUNSUP;
+    if (D != kHeadDim || M > W4A16_MAX_M || Hq > kMaxTickets || Hq / Hkv > 8) return W4A16_EUNSUP;
     return W4A16_OK;
 }
 

@@ -1647,13 +1647,34 @@ static int gemm_entry(const void *x, const void *packed, const Out &out, int M, 
     const int mt = (M + 15) / 16;
     Plan pl = choose_plan(M, N, K);
     if (pl.tw == 0) return W4A16_EUNSUP;
-    if (pl.S != 1 && nblocks * kTiles / pl.tw > kMaxTickets) pl.S = 1;
+    // one ticket per column unit: only the last-arriver sums use them
+    const bool wants_tickets = pl.S == 0 || (pl.S > 1 && pl.fused && pl.nw != 1);
+    if (wants_tickets && nblocks * kTiles / pl.tw > kMaxTickets) {
+        if (pl.S == 0) return W4A16_EUNSUP;   // the even split has no two-kernel form
+        pl.fused = 0;                         // same K split, summed by the second kernel
+    }
     if (pl.S != 1) {
         const size_t need = partial_bytes(mt, nblocks, pl, K / kGroup);
         if (need > 0 && !workspace) return W4A16_EWORKSPACE;
         if (need > 0 && workspace_bytes < kTicketBytes + need) return W4A16_EWORKSPACE;
     }
     return dispatch(mt, pl, x, packed, out, M, N, K, workspace, (hipStream_t)stream);
+}
+
+int w4a16_plan_describe(int M, int N, int K, int G, int *out)
+{
+    if (!out) return W4A16_ENULL;
+    int rc = check_weight_shape(N, K, G);
+    if (rc != W4A16_OK) return rc;
+    if (M < 1) return W4A16_EINVAL;
+    if (M > W4A16_MAX_M) return W4A16_EUNSUP;
+    const Plan pl = choose_plan(M, N, K);
+    if (pl.tw == 0) return W4A16_EUNSUP;
+    const int family = pl.ng > 0 ? 1 : pl.ks > 0 ? 3 : pl.nw == 1 ? 2 : 0;
+    const int plan[8] = {family, (M + 15) / 16, pl.tw, family == 3 ? pl.ks : pl.nw, family == 1 ? pl.ng : pl.depth,
+                         pl.S, pl.S > 1 ? pl.fused : 0, 0};
+    for (int i = 0; i < 8; ++i) out[i] = plan[i];
+    return W4A16_OK;
 }
 
 int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, int G,

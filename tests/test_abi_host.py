@@ -92,8 +92,29 @@ def test_argument_validation_happens_before_any_gpu_call():
     assert t(a, a, a, a, a, 65, 2048, 64, 8, 128, f, a, 1 << 30, None) == EUNSUP   # M > 64
     assert t(a, a, a, a, a, 60, 2048, 64, 7, 128, f, a, 1 << 30, None) == EINVAL   # Hq % Hkv
     assert t(a, a, a, a, a, 0, 2048, 64, 8, 128, f, a, 1 << 30, None) == EINVAL
+    assert t(a, a, a, a, a, 1, 2048, 64, 4, 128, f, a, 1 << 30, None) == EUNSUP    # more than 8 query heads per KV head
     assert t(a, a, a, None, a, 60, 2048, 64, 8, 128, f, a, 1 << 30, None) == ENULL
     assert t(a, a, a, a, a, 60, 2048, 64, 8, 128, f, None, 0, None) == EWS
+
+
+def test_plan_describe():
+    out = (ctypes.c_int * 8)()
+    lib = B.load()
+    assert lib.w4a16_plan_describe(1, 4096, 4096, 128, None) == -2
+    assert lib.w4a16_plan_describe(0, 4096, 4096, 128, out) == -1
+    assert lib.w4a16_plan_describe(65, 4096, 4096, 128, out) == -4
+    assert lib.w4a16_plan_describe(1, 4096, 4096, 64, out) == -4
+    for M in (1, 8, 16, 17, 64):
+        for N, K in ((4096, 4096), (57344, 8192), (8192, 28672), (1000, 1536)):
+            plan = B.w4a16_plan_describe(M, N, K)
+            assert plan[0] in (0, 1, 2, 3) and plan[1] == (M + 15) // 16 and plan[2] in (2, 4, 8), plan
+    B.w4a16_set_param("tiles_per_wave", 8)
+    B.w4a16_set_param("waves_per_wg", 16)
+    try:
+        assert lib.w4a16_plan_describe(40, 128, 256, 128, out) == -4   # a variant that is not compiled
+    finally:
+        B.w4a16_set_param("tiles_per_wave", 0)
+        B.w4a16_set_param("waves_per_wg", 0)
 
 
 def test_product_never_imports_the_oracle():

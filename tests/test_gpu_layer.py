@@ -103,6 +103,11 @@ def kernel_families(M):
     if M <= 4:
         fam += [("flat S=1", dict(tw=2, nw=8, ng=1, split=1, fused=1)), ("flat last-arriver", dict(tw=4, nw=4, ng=1, split=2, fused=1)),
                 ("flat two kernels", dict(tw=8, nw=4, ng=1, split=2, fused=0))]
+    if M <= 16:
+        fam += [("column split, two groups in flight", dict(tw=8, nw=1, depth=2, split=2))]
+    if 16 < M <= 48:
+        fam += [("high occupancy three sets last-arriver", dict(tw=2, ks=3, depth=1, split=3, fused=1)),
+                ("high occupancy three sets S=1", dict(tw=2, ks=3, depth=1, split=1))]
     if M > 16:
         fam += [("column split S=1", dict(tw=4, nw=1, depth=1, split=1)), ("column split S=3", dict(tw=8, nw=1, depth=1, split=3)),
                 ("high occupancy S=1", dict(tw=2, ks=2, depth=2, split=1)), ("high occupancy S=2", dict(tw=4, ks=1, depth=2, split=2)),
