@@ -36,7 +36,7 @@ extern "C" {
 #define W4A16_ENULL (-2)      /* a required pointer is NULL */
 #define W4A16_EALIGN (-3)     /* a pointer is not 16-byte aligned */
 #define W4A16_EUNSUP (-4)     /* valid but not implemented (group size other than 128, M > 64, ...) */
-#define W4A16_EWORKSPACE (-5) /* workspace missing or smaller than the *_workspace_bytes() value */
+#define W4A16_EWORKSPACE (-5) /* workspace missing or smaller than the *_workspace_bytes() value (or than the built-in scratch) */
 #define W4A16_EHIP (-6)       /* the HIP runtime reported an error while enqueuing */
 
 #define W4A16_MAX_M 64
@@ -91,6 +91,17 @@ int w4a16_dequant(const void *packed, float *W, int N, int K, int G, void *strea
  * have been initialised with w4a16_workspace_init. */
 int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, int G,
                void *workspace, size_t workspace_bytes, void *stream);
+
+/* w4a16_gemm for callers that cannot allocate device memory and so cannot provide a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels,
+ * same results bit for bit; the split-K partial sums and tickets live in a scratch array built into the
+ * library (16 KB of tickets + 32 MiB of partial sums, held on every GPU the library is loaded on until the
+ * process ends).  The call allocates nothing and frees nothing.  W4A16_EWORKSPACE if the launch plan of this
+ * (M, N, K) needs more partial-sum space than the array holds (no Llama-3 8B / 70B layer shape does); all
+ * other errors as w4a16_gemm.  Every call on a GPU shares that GPU's array: two calls that may run at the same
+ * time on one GPU (different streams, different host threads) race and must not be issued; calls ordered on
+ * one stream are safe.  The first call on a GPU looks up the array's address and is not thread-safe. */
+int w4a16_gemm_static(const void *x, const void *packed, void *y, int M, int N, int K, int G, void *stream);
 
 /* w4a16_gemm with the element-wise step that follows the linear in a Llama-type decoder layer fused
  * into the store (paper section 2.1 counts a whole forward pass of the target model per

@@ -17,7 +17,7 @@ EXPORTS = (
     "w4a16_workspace_bytes", "w4a16_workspace_init", "w4a16_pack", "w4a16_unpack", "w4a16_dequant",
     "w4a16_gemm", "w4a16_gemm_fused", "w4a16_gemm_rope", "w4a16_pack_heads", "w4a16_pack_gate_up", "w4a16_read_probe", "tree_verify_attn_workspace_bytes",
     "tree_verify_attn", "tree_accept", "rms_norm", "rope_append", "lm_head_workspace_bytes", "lm_head_topk",
-    "lm_head_packed_bytes", "lm_head_pack", "w4a16_decoder_layer", "w4a16_plan_describe",
+    "lm_head_packed_bytes", "lm_head_pack", "w4a16_decoder_layer", "w4a16_plan_describe", "w4a16_gemm_static",
 )
 
 EPI_NONE, EPI_RESIDUAL, EPI_SILU_MUL = 0, 1, 2
@@ -70,6 +70,7 @@ def load() -> ctypes.CDLL:
     L.w4a16_dequant.argtypes = [vp, vp, i, i, i, vp]
     L.w4a16_gemm.argtypes = [vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.w4a16_read_probe.argtypes = [vp, sz, vp, vp]
+    L.w4a16_gemm_static.argtypes = [vp, vp, vp, i, i, i, i, vp]
     L.w4a16_plan_describe.argtypes = [i, i, i, i, ctypes.POINTER(ctypes.c_int)]
     L.tree_verify_attn_workspace_bytes.restype = sz
     L.tree_verify_attn_workspace_bytes.argtypes = [i, i, i, i, i]
@@ -161,6 +162,10 @@ def w4a16_dequant(packed, W, N: int, K: int, G: int = 128) -> None:
 def w4a16_gemm(x, packed, y, M: int, N: int, K: int, G: int, workspace) -> None:
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().w4a16_gemm(_ptr(x), _ptr(packed), _ptr(y), M, N, K, G, _ptr(workspace), nbytes, _stream()), "w4a16_gemm")
+
+
+def w4a16_gemm_static(x, packed, y, M: int, N: int, K: int, G: int = 128) -> None:
+    _check(load().w4a16_gemm_static(_ptr(x), _ptr(packed), _ptr(y), M, N, K, G, _stream()), "w4a16_gemm_static")
 
 
 def w4a16_gemm_fused(x, packed, y, M: int, N: int, K: int, G: int, epilogue: int, residual, workspace) -> None:

@@ -1661,6 +1661,51 @@ static int gemm_entry(const void *x, const void *packed, const Out &out, int M, 
     return dispatch(mt, pl, x, packed, out, M, N, K, workspace, (hipStream_t)stream);
 }
 
+// ---- w4a16_gemm for callers that cannot allocate a workspace ---------------------------------------
+// The split-K partial sums and tickets live in a file-scope device array instead of a caller buffer.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the device address it yields
+// (one per GPU, each GPU holds its own copy) is what kernels and the ticket clear receive.
+constexpr size_t kStaticScratchPartials = (size_t)32 << 20;
+constexpr size_t kStaticScratchBytes = kTicketBytes + kStaticScratchPartials;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *scratch_of_device[kMaxDevices];   // device address of `scratch`, by HIP device ordinal
+
+static int static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return W4A16_EHIP;
+    if (!scratch_of_device[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return W4A16_EHIP;
+        scratch_of_device[dev] = p;
+    }
+    *ptr = scratch_of_device[dev];
+    return W4A16_OK;
+}
+
+int w4a16_gemm_static(const void *x, const void *packed, void *y, int M, int N, int K, int G, void *stream)
+{
+    int rc = check_weight_shape(N, K, G);
+    if (rc != W4A16_OK) return rc;
+    if (M < 1) return W4A16_EINVAL;
+    if (M > W4A16_MAX_M) return W4A16_EUNSUP;
+    if (!x || !packed || !y) return W4A16_ENULL;
+    if (misaligned(x) || misaligned(packed) || misaligned(y)) return W4A16_EALIGN;
+    const Plan pl = choose_plan(M, N, K);
+    if (pl.tw == 0) return W4A16_EUNSUP;
+    const size_t need = pl.S != 1 ? partial_bytes((M + 15) / 16, pad_cols(N) / kBlockCols, pl, K / kGroup) : 0;
+    if (need > kStaticScratchPartials) return W4A16_EWORKSPACE;   // this shape needs more than the built-in scratch holds
+    void *ws = nullptr;
+    if ((rc = static_scratch(&ws)) != W4A16_OK) return rc;
+    // The array keeps what the previous call left.  Partial sums are all written before they are read; the
+    // tickets must start at zero, and although a finished call leaves them so, one that was cut short would
+    // not: they are cleared here (a fill kernel, so the call can be captured in a graph) whenever they are used.
+    if (pl.S == 0 || (pl.S > 1 && pl.fused && pl.nw != 1))
+        if ((rc = w4a16_workspace_init(ws, kStaticScratchBytes, stream)) != W4A16_OK) return rc;
+    return gemm_entry(x, packed, Out{(_Float16 *)y, nullptr, kEpiNone}, M, N, K, G, ws, kStaticScratchBytes, stream);
+}
+
 int w4a16_plan_describe(int M, int N, int K, int G, int *out)
 {
     if (!out) return W4A16_ENULL;
