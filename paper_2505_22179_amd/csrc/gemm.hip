@@ -1037,14 +1037,30 @@ __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const
     const int full = n / KS;                       // steps in which every k set has a group
     const int mine = n > kset ? (n - kset + KS - 1) / KS : 0;   // groups of this wavefront: g_begin + kset + KS*i
 
-    // x fragment this lane fetches for its k set: k step colq, row tile mt (byte offsets from a
-    // wavefront-uniform base, so the loads address with a scalar base and a 32-bit lane offset)
+    // The x tile of a group is kept in LDS as MT * 4 blocks of 1 KB, block (mt, jp, h) = the eight rows
+    // 16 mt + 8 h .. + 7 times the 128 bytes of k steps 2 jp and 2 jp + 1, and a wavefront fetches MT of them for
+    // its k set, lane l row l / 8: such a load touches whole cache lines (fetching matrix-operand fragments
+    // directly -- sixteen rows times 64 bytes per load -- occupies the load path four times as long).  Inside a
+    // block the eight 16-byte chunks of a row sit at chunk ^ (4 h + row / 2), which spreads the sixteen rows of
+    // a fragment read over all LDS banks.  (Byte offsets from a wavefront-uniform base, so the loads address
+    // with a scalar base and a 32-bit lane offset.)
     uint32_t xoff[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        int row = mt * 16 + c;
+    for (int i = 0; i < MT; ++i) {
+        const int blk = colq * MT + i;
+        const int mt = blk >> 2, jp = (blk >> 1) & 1, h = blk & 1, row8 = lane >> 3;
+        const int chunk = (lane & 7) ^ (4 * h + (row8 >> 1));
+        int row = mt * 16 + h * 8 + row8;
         row = row < M ? row : M - 1;   // rows >= M are never read; their products are never stored
-        xoff[mt] = (uint32_t)(((size_t)row * K + colq * 32 + r * 8) * sizeof(_Float16));
+        xoff[i] = (uint32_t)(((size_t)row * K + jp * 64 + chunk * 8) * sizeof(_Float16));
+    }
+    // fragment (mt, j) for lane (r, c) -- row 16 mt + c, elements 32 j + 8 r .. + 7 -- lies in block pair
+    // (mt, j / 2) at this lane's offset for even or odd k steps
+    uint32_t xfrag[2];
+    {
+        const int h = c >> 3, row8 = c & 7, sw = 4 * h + (row8 >> 1);
+        xfrag[0] = (uint32_t)(h * 1024 + (row8 * 8 + (r ^ sw)) * 16);
+        xfrag[1] = (uint32_t)(h * 1024 + (row8 * 8 + ((4 + r) ^ sw)) * 16);
     }
     const uint8_t *xbase = reinterpret_cast<const uint8_t *>(x + (size_t)(g_begin + kset) * kGroup);
     const uint8_t *recw = packed + record_offset(nb, g_begin + (kset < n ? kset : 0), groups);   // group 0 of this wavefront
@@ -1067,13 +1083,15 @@ __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const
     };
     auto park_x = [&](int buf) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) xa[buf * kBufQuads + ((kset * MT + mt) * 4 + colq) * 64 + lane] = xreg[mt];
+        for (int i = 0; i < MT; ++i) xa[buf * kBufQuads + (kset * MT * 4 + colq * MT + i) * 64 + lane] = xreg[i];
     };
     auto fetch_a = [&](int buf) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a[mt][j] = xa[buf * kBufQuads + ((kset * MT + mt) * 4 + j) * 64 + lane];
+            for (int j = 0; j < 4; ++j)
+                a[mt][j] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint8_t *>(xa + buf * kBufQuads + kset * MT * 4 * 64) +
+                                                           (mt * 2 + (j >> 1)) * 2048 + xfrag[j & 1]);
     };
     auto rec_of = [&](int i) { return recw + (size_t)i * (KS * kRecordBytes); };
 
