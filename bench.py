@@ -226,7 +226,7 @@ def model_leg(name: str, shapes, n_layers: int, Hq: int, Hkv: int, Ms, args, use
     out = {}
     for M in Ms:
         steps, warm = max(5, min(args.steps, 20)), 3
-        ms = time_steps(lambda c, M=M: model.forward(M), steps, warm, use_graph, 1)
+        ms = time_steps(lambda c, M=M: model.forward(M), steps, warm, use_graph, 1, repeats=5)
         out[str(M)] = {"ms_per_forward": ms}
         log(f"{name} whole model M={M}: {ms:.3f} ms per forward pass")
     t_t = out["1"]["ms_per_forward"]
@@ -321,46 +321,100 @@ def lm_head_leg(args, use_graph: bool) -> dict:
     return lm
 
 
-def time_steps(fn, steps: int, warmup: int, use_graph: bool, copies: int):
-    """fn(copy_index) enqueues one step.  Warm up, then time exactly `steps` steps between two
-    events on the launch stream.  With graphs, `copies` consecutive steps form one HIP graph (so the
-    host never gates the GPU) and a tail of single-step graphs makes the count exact."""
+REPEATS = 9   # timed regions per figure; the median is reported
+MAX_GRAPH_STEPS = 512   # a timed region of up to this many steps is one HIP graph
+
+
+def percentile(sorted_vals, q: float) -> float:
+    if len(sorted_vals) == 1:
+        return sorted_vals[0]
+    pos = q * (len(sorted_vals) - 1)
+    lo = int(pos)
+    hi = min(lo + 1, len(sorted_vals) - 1)
+    return sorted_vals[lo] + (sorted_vals[hi] - sorted_vals[lo]) * (pos - lo)
+
+
+def time_steps(fn, steps: int, warmup: int, use_graph: bool, copies: int, stats: dict | None = None, repeats: int = REPEATS):
+    """fn(copy_index) enqueues one step.  Warm up, then time exactly `steps` steps between two events on the
+    launch stream, `repeats` times over, and return the median in ms per step (p10 / p90 / min go to `stats`).
+    With graphs, a region of up to MAX_GRAPH_STEPS steps is ONE HIP graph (step i uses copy i % copies), so
+    the host never gates the GPU inside a region whatever `steps` is; longer regions replay a graph of
+    `copies` steps and finish with single-step graphs to make the count exact."""
     stream = torch.cuda.current_stream()
     if use_graph:
         for c in range(copies):   # one-time kernel attributes are set outside capture
             fn(c)
         torch.cuda.synchronize()
-        full = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(full):
-            for c in range(copies):
-                fn(c)
-        singles = []
-        for c in range(steps % copies):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                fn(c)
-            singles.append(g)
-        stream = torch.cuda.current_stream()
+        if steps <= MAX_GRAPH_STEPS:
+            region = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(region):
+                for i in range(steps):
+                    fn(i % copies)
 
-        def run(n):
-            for _ in range(n // copies):
-                full.replay()
-            for g in singles[: n % copies]:
-                g.replay()
+            def run_region():
+                region.replay()
+        else:
+            full = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(full):
+                for c in range(copies):
+                    fn(c)
+            singles = []
+            for c in range(steps % copies):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    fn(c)
+                singles.append(g)
+
+            def run_region():
+                for _ in range(steps // copies):
+                    full.replay()
+                for g in singles:
+                    g.replay()
+        stream = torch.cuda.current_stream()
     else:
-        def run(n):
-            for i in range(n):
+        def run_region():
+            for i in range(steps):
                 fn(i % copies)
 
-    run(max(warmup, copies))
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    def run_warm():   # warm-up: at least `warmup` steps, in whole regions, so that clocks are up
+        for _ in range(max(1, -(-warmup // steps))):
+            run_region()
+
+    run_warm()
     torch.cuda.synchronize()
-    run(max(warmup, copies))          # keep clocks up right before the timed region
-    start.record(stream)
-    run(steps)
-    stop.record(stream)
-    torch.cuda.synchronize()
-    return start.elapsed_time(stop) / steps
+    times = []
+    for _ in range(repeats):
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        run_warm()          # keeps clocks up right before the timed region
+        start.record(stream)
+        run_region()
+        stop.record(stream)
+        torch.cuda.synchronize()
+        times.append(start.elapsed_time(stop) / steps)
+    times.sort()
+    if stats is not None:
+        stats.update({"median_ms": percentile(times, 0.5), "p10_ms": percentile(times, 0.1), "p90_ms": percentile(times, 0.9),
+                      "min_ms": times[0], "repeats": repeats, "steps_per_region": steps})
+    return percentile(times, 0.5)
+
+
+def gpu_clocks():
+    """Clock readings of the GPU from rocm-smi (clocks cannot be fixed from user space: recorded, not set);
+    None when the tool is not there or prints nothing usable."""
+    import re
+    import shutil
+    import subprocess
+    tool = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    try:
+        out = subprocess.run([tool, "--showclocks"], capture_output=True, text=True, timeout=20).stdout
+    except (OSError, subprocess.SubprocessError):
+        return None
+    clocks = {}
+    for line in out.splitlines():
+        m = re.search(r"GPU\[(\d+)\]\s*:\s*(\w+) clock level:\s*\S+\s*\((\d+)\s*Mhz\)", line, flags=re.I)
+        if m and m.group(1) == "0":
+            clocks[m.group(2).lower() + "_mhz"] = int(m.group(3))
+    return clocks or None
 
 
 def measured_traffic():
@@ -374,33 +428,54 @@ def measured_traffic():
         return None
 
 
-def cpu_baseline(shapes, label: str):
-    """The CPU oracle, as it stands, on the same layer at M = 1: every GEMM once with all host
-    threads, and the two small GEMMs once more on a single thread (to bound the run)."""
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline():
+    """The CPU oracle, as it stands, timed on this machine's host cores on a bounded sample of the benchmark's
+    workload: the Llama-3-70B layer's four GEMMs at M = 1 (all threads: the headline figure; one thread:
+    each GEMM once), and at M = 64 the Llama-3-8B layer and the 70B o_proj (all threads).  One pass each."""
     from oracle import reference as R
     threads = R.set_threads(0)
-    total_b, t_all, one_b, t_one = 0, 0.0, 0, 0.0
-    for gi, (name, K, N) in enumerate(shapes):
-        inp = I.make_linear(I.seed_for(4, gi), 1, K, N)
-        R.set_threads(threads)
+
+    def timed(inp, M, nthreads):
+        R.set_threads(nthreads)
         t0 = time.perf_counter()
-        R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, G, want64=False)
-        t_all += time.perf_counter() - t0
+        R.w4a16_gemm(inp.x[:M], inp.qweight, inp.scales, inp.qzeros, G, want64=False)
+        return time.perf_counter() - t0
+
+    per = {"llama3_70b_M1": {}, "llama3_70b_M1_one_thread": {}, "llama3_8b_M64": {}, "llama3_70b_M64": {}}
+    total_b, t_all = 0, 0.0
+    for gi, (name, K, N) in enumerate(I.LLAMA3_70B):
+        inp = I.make_linear(I.seed_for(4, gi), 64 if name == "o_proj" else 1, K, N)
+        t = timed(inp, 1, threads)
+        t_all += t
         total_b += weight_bytes(K, N)
-        if gi < 2:
-            R.set_threads(1)
-            t0 = time.perf_counter()
-            R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, G, want64=False)
-            t_one += time.perf_counter() - t0
-            one_b += weight_bytes(K, N)
+        per["llama3_70b_M1"][name] = t * 1e6
+        per["llama3_70b_M1_one_thread"][name] = timed(inp, 1, 1) * 1e6
+        if name == "o_proj":
+            per["llama3_70b_M64"][name] = timed(inp, 64, threads) * 1e6
+        del inp
+    for gi, (name, K, N) in enumerate(I.LLAMA3_8B):
+        inp = I.make_linear(I.seed_for(3, gi), 64, K, N)
+        per["llama3_8b_M64"][name] = timed(inp, 64, threads) * 1e6
         del inp
     R.set_threads(threads)
+    one = sum(per["llama3_70b_M1_one_thread"].values())
     return {
         "value": total_b / t_all / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-        "sample": f"{label}: all four GEMMs at M=1, one pass each, {threads} OpenMP threads "
-                  f"({t_all * 1e6:.0f} us per layer); single thread on qkv+o_proj: "
-                  f"{one_b / t_one / 1e9:.3f} GB/s",
-        "us_per_layer": t_all * 1e6,
+        "sample": f"Llama-3-70B layer: all four GEMMs at M=1, one pass each, {threads} OpenMP threads "
+                  f"({t_all * 1e6:.0f} us per layer); one thread: {one:.0f} us per layer ({total_b / one / 1e3:.3f} GB/s); "
+                  f"M=64, {threads} threads: 8B layer {sum(per['llama3_8b_M64'].values()):.0f} us, 70B o_proj "
+                  f"{per['llama3_70b_M64']['o_proj']:.0f} us",
+        "us_per_layer": t_all * 1e6, "us_per_gemm": per, "nproc": os.cpu_count(), "cpu_model": cpu_model(),
     }
 
 
@@ -439,12 +514,15 @@ def main():
         ms = time_steps(layer.step, args.steps, args.warmup, use_graph, 12)
         print(json.dumps({"metric": "us per Llama-3-70B decoder layer (prefix 2048)", "M": M, "value": ms * 1e3, "unit": "us"}))
         return
-    sweep = {}
+    clocks_before = gpu_clocks()
+    sweep, sweep_stats = {}, {}
     quick_ms = (args.quick_m,)
     for M in (quick_ms if args.quick else I.M_SWEEP_70B):
-        ms = time_steps(lambda c, M=M: big.step(M, c), args.steps, args.warmup, use_graph, args.copies)
+        sweep_stats[M] = {}
+        ms = time_steps(lambda c, M=M: big.step(M, c), args.steps, args.warmup, use_graph, args.copies, sweep_stats[M])
         sweep[M] = ms
-        log(f"70B M={M}: {ms * 1e3:.1f} us/layer  {big.bytes / ms / 1e6:.0f} GB/s")
+        st = sweep_stats[M]
+        log(f"70B M={M}: {ms * 1e3:.1f} us/layer (p10 {st['p10_ms'] * 1e3:.1f}, p90 {st['p90_ms'] * 1e3:.1f})  {big.bytes / ms / 1e6:.0f} GB/s")
     hm = args.quick_m if args.quick else 1   # M of the headline (1 except under --quick --quick-m)
     ms1 = sweep[hm]
     value = big.bytes / ms1 / 1e6   # GB/s
@@ -457,8 +535,10 @@ def main():
             if args.quick and gi != 2:
                 continue
             nc = big.solo_copies(gi)
-            ms = time_steps(lambda c, M=M, gi=gi: big.step(M, c, only=gi), args.steps, args.warmup, use_graph, nc)
-            per_gemm[M][name] = {"us": ms * 1e3, "GBps": weight_bytes(K, N) / ms / 1e6}
+            st = {}
+            ms = time_steps(lambda c, M=M, gi=gi: big.step(M, c, only=gi), args.steps, args.warmup, use_graph, nc, st)
+            per_gemm[M][name] = {"us": ms * 1e3, "GBps": weight_bytes(K, N) / ms / 1e6, "p10_us": st["p10_ms"] * 1e3,
+                                 "p90_us": st["p90_ms"] * 1e3, "plan": dict(zip(B.PLAN_FIELDS, B.w4a16_plan_describe(M, N, K)))}
             log(f"70B {name} M={M}: {ms * 1e3:.2f} us  {weight_bytes(K, N) / ms / 1e6:.0f} GB/s")
     gu = per_gemm[hm]["gate_up"]
     # the same buffers through the plain streaming-read probe: the bandwidth this GPU reaches at each size
@@ -563,7 +643,8 @@ def main():
         extra["llama3_8b_layer"] = {str(M): {"us_per_layer": ms * 1e3, "weight_GBps": bytes8 / ms / 1e6,
                                             "ratio_vs_M1": ms / s8[1]} for M, ms in s8.items()}
         bytes70 = sum(weight_bytes(K, N) for (_, K, N) in I.LLAMA3_70B)
-        extra["llama3_70b_layer"] = {str(M): {"us_per_layer": ms * 1e3, "weight_GBps": bytes70 / ms / 1e6,
+        extra["llama3_70b_layer"] = {str(M): {"us_per_layer": ms * 1e3, "p10_us": sweep_stats[M]["p10_ms"] * 1e3,
+                                             "p90_us": sweep_stats[M]["p90_ms"] * 1e3, "weight_GBps": bytes70 / ms / 1e6,
                                              "frac_of_hbm_peak": bytes70 / ms / 1e6 / HBM_PEAK_GBPS,
                                              "ratio_vs_M1": ms / ms1} for M, ms in sweep.items()}
         extra["llama3_70b_per_gemm"] = {str(M): d for M, d in per_gemm.items()}
@@ -585,11 +666,13 @@ def main():
                                "gate_up 8192->57344, down 28672->8192), W4A16 G=128, M=" + str(hm) + "; sweep M in {1,4,8,16,32,64}",
                    "weight_copies_rotated": args.copies, "hip_graph": use_graph, "device": dev},
         "frac_of_hbm_peak": value / HBM_PEAK_GBPS,
+        "timing": dict(sweep_stats[hm], note=f"median of {REPEATS} timed regions of exactly --steps steps each, HIP events on the launch stream"),
+        "gpu_clocks": {"before": clocks_before, "after": gpu_clocks()},
         "roofline": roofline,
     }
     if not args.no_cpu and not args.quick:
         log("timing the CPU oracle ...")
-        result["cpu_baseline"] = cpu_baseline(I.LLAMA3_70B, "Llama-3-70B layer")
+        result["cpu_baseline"] = cpu_baseline()
     else:
         result["cpu_baseline"] = None
     result.update(extra)
