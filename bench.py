@@ -48,17 +48,22 @@ class Layer:
     """Packed weights of one decoder layer's four linears, `copies` times, built on the device
     from seeded uniform codes / zero-points and U[1e-3, 1e-2] fp16 scales."""
 
-    def __init__(self, shapes, copies: int, seed: int):
+    def __init__(self, shapes, copies: int, seed: int, symmetric: bool = False):
+        """symmetric: every zero-point is 8 (the paper's GPTQ scheme is symmetric) and the linears are called with
+        W4A16_SYMMETRIC; otherwise zero-points are uniform in 0..15 as the benchmark configurations state"""
         gen = torch.Generator(device="cuda")
         gen.manual_seed(seed)
         self.shapes = shapes
         self.copies = copies
+        self.symmetric = symmetric
         self.packed = []   # [copy][gemm]
         first = []
         for (name, K, N) in shapes:
             qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (K // 8, N), dtype=torch.int32, device="cuda", generator=gen)
             sc = (torch.rand((K // G, N), device="cuda", generator=gen) * 9e-3 + 1e-3).to(torch.float16)
             qz = torch.randint(-2 ** 31, 2 ** 31 - 1, (K // G, N // 8), dtype=torch.int32, device="cuda", generator=gen)
+            if symmetric:
+                qz.fill_(-0x77777778)   # 0x88888888: eight zero-points of 8 per word
             p = torch.empty(B.w4a16_packed_bytes(N, K, G), dtype=torch.uint8, device="cuda")
             # gate_up in the paired tile order the fused SiLU-gate epilogue reads, qkv with the halves of every head
             # paired for the rotary epilogue (same bytes, same cost for the plain GEMM)
@@ -93,7 +98,10 @@ class Layer:
         for gi, (_, K, N) in enumerate(self.shapes):
             if only is not None and gi != only:
                 continue
-            B.w4a16_gemm(xs[gi], self.packed[copy][gi], ys[gi], M, N, K, G, self.ws)
+            if self.symmetric:
+                B.w4a16_gemm_fused(xs[gi], self.packed[copy][gi], ys[gi], M, N, K, G, B.EPI_NONE | B.SYMMETRIC, None, self.ws)
+            else:
+                B.w4a16_gemm(xs[gi], self.packed[copy][gi], ys[gi], M, N, K, G, self.ws)
 
     def solo_copies(self, gi: int, min_bytes: int = 700_000_000):
         """Enough distinct copies of one GEMM's weights that a loop over it alone never re-reads
@@ -608,6 +616,25 @@ def main():
         extra["llama3_70b_decoder_layer_P2048"] = {
             str(M): {"us_per_layer": ms * 1e3, "ratio_vs_M1": ms / dl[1], "ms_per_80_layers": ms * 80} for M, ms in dl.items()}
         del big
+        torch.cuda.empty_cache()
+        # the paper's own weight format: symmetric quantisation, every zero-point 8.  Same layer, zero-points 8, every
+        # linear called with W4A16_SYMMETRIC (the kernels then never read them), beside the general-format figures
+        # above; M = 1 plain decoding, 7 and 8 the sequence drafts of length 6 and 7, 64 a full tree
+        symw = Layer(I.LLAMA3_70B, args.copies, seed=71, symmetric=True)
+        flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+        B.w4a16_weight_is_symmetric(symw.packed[0][2], I.LLAMA3_70B[2][2], I.LLAMA3_70B[2][1], flag)
+        torch.cuda.synchronize()
+        assert int(flag[0]) == 1
+        sym = {}
+        for M in (1, 7, 8, 64):
+            st = {}
+            ms = time_steps(lambda c, M=M: symw.step(M, c), args.steps, args.warmup, use_graph, args.copies, st)
+            sym[str(M)] = {"us_per_layer_symmetric": ms * 1e3, "p10_us": st["p10_ms"] * 1e3, "p90_us": st["p90_ms"] * 1e3}
+            if M in sweep:
+                sym[str(M)]["us_per_layer_general_format"] = sweep[M] * 1e3
+            log(f"70B symmetric weights M={M}: {ms * 1e3:.1f} us/layer")
+        extra["llama3_70b_layer_symmetric_weights"] = sym
+        del symw
         torch.cuda.empty_cache()
         lm = lm_head_leg(args, use_graph)
         extra["lm_head_topk_V128256"] = lm

@@ -114,12 +114,27 @@ int w4a16_gemm_static(const void *x, const void *packed, void *y, int M, int N, 
  *                                  must come from w4a16_pack_gate_up, N % 32 == 0
  * The sum, the residual add and the gate are evaluated in fp32 and rounded to fp16 once.
  * `residual` must be NULL unless the epilogue is W4A16_EPI_RESIDUAL.  Everything else as for
- * w4a16_gemm (same workspace size). */
+ * w4a16_gemm (same workspace size).
+ *
+ * W4A16_SYMMETRIC may be OR-ed into `epilogue`: the caller vouches that every zero-point of this weight is 8,
+ * i.e. that the weight is symmetrically quantised (the scheme of paper section 2.2: GPTQ, symmetric, group size
+ * 128).  The kernels then use w = (q - 8) * s without reading the zero-points -- fewer bytes and instructions;
+ * for such a weight the result is that of the call without the flag (bit for bit for M > 16; for M <= 16 the
+ * fp32 sums are formed in another order, and exact-arithmetic inputs still give identical bits).  Kernel families
+ * without a symmetric instantiation ignore the flag, so for a weight that has other zero-points the result is
+ * unspecified: either the correct one or that of zero-points 8.  w4a16_weight_is_symmetric tests a packed weight. */
 #define W4A16_EPI_NONE 0
 #define W4A16_EPI_RESIDUAL 1
 #define W4A16_EPI_SILU_MUL 2
+#define W4A16_SYMMETRIC 0x100
 int w4a16_gemm_fused(const void *x, const void *packed, void *y, int M, int N, int K, int G, int epilogue,
                      const void *residual, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Writes 1 to *flag (device int32, 4-byte aligned) if every zero-point of the N columns of a packed weight is 8,
+ * else 0 -- what a loader checks once before it passes W4A16_SYMMETRIC for that weight (padding columns inside
+ * the buffer do not count; the paired packings of w4a16_pack_gate_up / w4a16_pack_heads only permute columns).
+ * Enqueued on `stream`; read the flag after synchronising. */
+int w4a16_weight_is_symmetric(const void *packed, int N, int K, int G, int32_t *flag, void *stream);
 
 /* w4a16_pack for a weight whose columns 0..N/2-1 are a gate projection and N/2..N-1 the matching up
  * projection: the packed buffer holds the 16-column tiles alternately, gate tile j, up tile j, gate
@@ -229,6 +244,8 @@ typedef struct {
     int hidden, n_q_heads, n_kv_heads, head_dim, ffn;
     float eps;
     int qkv_heads_packed; /* nonzero: qkv_packed comes from w4a16_pack_heads and the layer uses w4a16_gemm_rope */
+    int symmetric;        /* nonzero: all four weights have zero-points 8 throughout (W4A16_SYMMETRIC on every linear that
+                             takes the flag: o, gate_up, down, and qkv when it is not the fused-rotary projection) */
 } w4a16_layer_weights;
 typedef struct {
     void *norm, *qkv, *q, *attn, *act;
@@ -314,7 +331,7 @@ int w4a16_get_param(const char *name);
  *   [3] wavefronts per workgroup (families 0, 1; 1 for family 2) or K sets (family 3)
  *   [4] groups of codes in flight per wavefront, or groups per wavefront (family 1)
  *   [5] K splits across workgroups (0 = even split)   [6] 1 if the last workgroup of a unit sums the splits
- *   [7] 1 if every zero-point of the weight is taken to be 8 (symmetric fast path), else 0
+ *   [7] 1 if this kernel family has a symmetric instantiation, i.e. W4A16_SYMMETRIC would take effect, else 0
  * Host only: touches no GPU.  Errors as w4a16_gemm's shape checks; W4A16_EUNSUP if the knobs name a
  * variant that is not compiled. */
 int w4a16_plan_describe(int M, int N, int K, int G, int *out);

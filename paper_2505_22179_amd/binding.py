@@ -17,10 +17,11 @@ EXPORTS = (
     "w4a16_workspace_bytes", "w4a16_workspace_init", "w4a16_pack", "w4a16_unpack", "w4a16_dequant",
     "w4a16_gemm", "w4a16_gemm_fused", "w4a16_gemm_rope", "w4a16_pack_heads", "w4a16_pack_gate_up", "w4a16_read_probe", "tree_verify_attn_workspace_bytes",
     "tree_verify_attn", "tree_accept", "rms_norm", "rope_append", "lm_head_workspace_bytes", "lm_head_topk",
-    "lm_head_packed_bytes", "lm_head_pack", "w4a16_decoder_layer", "w4a16_plan_describe", "w4a16_gemm_static",
+    "lm_head_packed_bytes", "lm_head_pack", "w4a16_decoder_layer", "w4a16_plan_describe", "w4a16_gemm_static", "w4a16_weight_is_symmetric",
 )
 
 EPI_NONE, EPI_RESIDUAL, EPI_SILU_MUL = 0, 1, 2
+SYMMETRIC = 0x100   # OR-ed into an epilogue code: every zero-point of the weight is 8
 
 _lib = None
 
@@ -31,7 +32,7 @@ class LayerWeights(ctypes.Structure):
                 ("down_packed", ctypes.c_void_p), ("norm1_gamma", ctypes.c_void_p), ("norm2_gamma", ctypes.c_void_p),
                 ("hidden", ctypes.c_int), ("n_q_heads", ctypes.c_int), ("n_kv_heads", ctypes.c_int),
                 ("head_dim", ctypes.c_int), ("ffn", ctypes.c_int), ("eps", ctypes.c_float),
-                ("qkv_heads_packed", ctypes.c_int)]
+                ("qkv_heads_packed", ctypes.c_int), ("symmetric", ctypes.c_int)]
 
 
 class LayerScratch(ctypes.Structure):
@@ -71,6 +72,7 @@ def load() -> ctypes.CDLL:
     L.w4a16_gemm.argtypes = [vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.w4a16_read_probe.argtypes = [vp, sz, vp, vp]
     L.w4a16_gemm_static.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    L.w4a16_weight_is_symmetric.argtypes = [vp, i, i, i, vp, vp]
     L.w4a16_plan_describe.argtypes = [i, i, i, i, ctypes.POINTER(ctypes.c_int)]
     L.tree_verify_attn_workspace_bytes.restype = sz
     L.tree_verify_attn_workspace_bytes.argtypes = [i, i, i, i, i]
@@ -174,6 +176,10 @@ def w4a16_gemm_fused(x, packed, y, M: int, N: int, K: int, G: int, epilogue: int
                                    _ptr(workspace), nbytes, _stream()), "w4a16_gemm_fused")
 
 
+def w4a16_weight_is_symmetric(packed, N: int, K: int, flag, G: int = 128) -> None:
+    _check(load().w4a16_weight_is_symmetric(_ptr(packed), N, K, G, _ptr(flag), _stream()), "w4a16_weight_is_symmetric")
+
+
 def w4a16_pack_gate_up(qweight, scales, qzeros, packed, N: int, K: int, G: int = 128) -> None:
     _check(load().w4a16_pack_gate_up(_ptr(qweight), _ptr(scales), _ptr(qzeros), _ptr(packed), N, K, G, _stream()),
            "w4a16_pack_gate_up")
@@ -204,9 +210,10 @@ def rope_append(qkv, pos, cos_table, sin_table, n_pos: int, q, k_cache, v_cache,
 
 def layer_weights(qkv_packed, o_packed, gate_up_packed, down_packed, norm1_gamma, norm2_gamma, hidden: int,
                   n_q_heads: int, n_kv_heads: int, head_dim: int, ffn: int, eps: float,
-                  qkv_heads_packed: bool = False) -> LayerWeights:
+                  qkv_heads_packed: bool = False, symmetric: bool = False) -> LayerWeights:
     return LayerWeights(_ptr(qkv_packed), _ptr(o_packed), _ptr(gate_up_packed), _ptr(down_packed), _ptr(norm1_gamma),
-                        _ptr(norm2_gamma), hidden, n_q_heads, n_kv_heads, head_dim, ffn, float(eps), int(qkv_heads_packed))
+                        _ptr(norm2_gamma), hidden, n_q_heads, n_kv_heads, head_dim, ffn, float(eps), int(qkv_heads_packed),
+                        int(symmetric))
 
 
 def layer_scratch(norm, qkv, q, attn, act, gemm_workspace, attn_workspace) -> LayerScratch:

@@ -92,12 +92,19 @@ __device__ __forceinline__ T load_global(global_bytes p)
     return *(const __attribute__((address_space(1))) T *)p;
 }
 
-template <int MT>
+// Symmetric weights (paper section 2.2: GPTQ quantises symmetrically, so every zero-point is the mid-code 8):
+// kernels instantiated with SYM never read the zero-points and use the constants below instead.
+constexpr uint32_t kSymZeros = 0x88888888u;      // the zero-point word such a weight holds
+constexpr uint32_t kSymZneg = 0xE408E408u;       // fp16 pair -(1024 + 8)
+constexpr uint32_t kSymZneg16 = 0xD480D480u;     // fp16 pair -(64 + 8)
+
+template <int MT, bool SYM = false>
 __device__ __forceinline__ void load_operands(GroupOperands<MT> &f, const uint8_t *rec,
                                               const _Float16 *const (&xp)[MT], int g, int c)
 {
     f.q.s = *reinterpret_cast<const u32x4 *>(rec + kScalesOff + c * 16);
-    f.q.z = *reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4);
+    if constexpr (SYM) f.q.z = kSymZeros;
+    else f.q.z = *reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -131,14 +138,14 @@ __device__ __forceinline__ TileQuant<TW> tile_quant(const QuantWords &f, int t0)
 }
 
 // the four second operands (k steps) of one tile: exact fp16 (q - z)
-template <int TW>
+template <int TW, bool SYM = false>
 __device__ __forceinline__ void dequant_tile(half8v (&b)[4], const u32x4 &w, const TileQuant<TW> &q, int t,
                                              const DequantConsts &magic)
 {
     uint32_t z = (q.zbits >> (4 * t)) & 0xFu;
     uint32_t zz = z | (z << 16);
-    half2v zneg = as_h2(zz | 0xE400E400u);            // -(1024 + z)
-    half2v zneg16 = as_h2((zz << 4) | 0xD400D400u);   // -(64 + z)
+    half2v zneg = as_h2(SYM ? kSymZneg : (zz | 0xE400E400u));              // -(1024 + z)
+    half2v zneg16 = as_h2(SYM ? kSymZneg16 : ((zz << 4) | 0xD400D400u));   // -(64 + z)
 #pragma unroll
     for (int j = 0; j < 4; ++j) b[j] = dequant8(w[j], zneg, zneg16, magic);
 }
@@ -201,6 +208,34 @@ __device__ __forceinline__ void group_sums(const u32x4 (&a)[MT][4], float4v (&ne
     }
 }
 
+// Symmetric weights: z = 8 everywhere, so -C and -8 X are one sum over the same fragment, with -(1024 + 8) where
+// the fragment carries x and -(1024 + 128) where it carries x / 16 (both exact in fp16).  Started from it, the
+// matrix pipe leaves sum_k x_k (q_k - 8) and the fold is a plain multiply-add: four constant products per group
+// instead of eight, one fused multiply-add per live accumulator register instead of two.
+template <int MT>
+__device__ __forceinline__ void group_sums_symmetric(const u32x4 (&a)[MT][4], float4v (&negc)[MT])
+{
+    const u32x4 bias = {0xE408E408u, 0xE480E480u, 0xE408E408u, 0xE480E480u};     // -1032 or -1152
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        negc[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            negc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a[mt][j]),
+                                                               __builtin_bit_cast(half8v, bias), negc[mt], 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void fold_symmetric(float4v &acc, const float4v &part, float s, bool more_rows)
+{
+    acc[0] += s * part[0];
+    if (more_rows) {   // uniform: M > 1
+        asm volatile("");   // keeps this a branch, as in fold_offset
+#pragma unroll
+        for (int i = 1; i < 4; ++i) acc[i] += s * part[i];
+    }
+}
+
 // acc += s (part - z X) for the rows that exist: register i of a lane is row 4 * (lane / 16) + i
 __device__ __forceinline__ void fold_offset(float4v &acc, const float4v &part, const float4v &xs, float s, float zf,
                                             bool more_rows)
@@ -220,7 +255,7 @@ __device__ __forceinline__ void fold_offset(float4v &acc, const float4v &part, c
 // so the code stream never stalls on its own arithmetic.
 //   f, w      operands and codes of this group;  fn, wn  those of the next group (ring neighbour)
 //   bc        in: expanded tile 0 of this group; out: expanded tile 0 of the next group
-template <int MT, int TW, bool ALWAYS_REFILL, bool OFF = false>
+template <int MT, int TW, bool ALWAYS_REFILL, bool OFF = false, bool SYM = false>
 __device__ __forceinline__ void compute_group(u32x4 (&a)[MT][4], const QuantWords &f, const QuantWords &fn,
                                               u32x4 (&w)[TW], u32x4 (&wn)[TW], half8v (&bc)[4],
                                               float4v (&acc)[TW][MT], const uint8_t *refill_rec, bool refill,
@@ -235,7 +270,8 @@ __device__ __forceinline__ void compute_group(u32x4 (&a)[MT][4], const QuantWord
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int j = 0; j < 4; ++j) prescale_fragment(a[mt][j]);
-        group_sums<MT>(a, negc, xs);
+        if constexpr (SYM) group_sums_symmetric<MT>(a, negc);
+        else group_sums<MT>(a, negc, xs);
     }
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
@@ -247,8 +283,8 @@ __device__ __forceinline__ void compute_group(u32x4 (&a)[MT][4], const QuantWord
             if (t + 1 < TW) offset_tile(bn, w[t + 1 < TW ? t + 1 : 0], magic);
             else if (ALWAYS_REFILL || next_group) offset_tile(bn, wn[0], magic);
         } else {
-            if (t + 1 < TW) dequant_tile<TW>(bn, w[t + 1 < TW ? t + 1 : 0], q, t + 1, magic);
-            else if (ALWAYS_REFILL || next_group) dequant_tile<TW>(bn, wn[0], qn, 0, magic);
+            if (t + 1 < TW) dequant_tile<TW, SYM>(bn, w[t + 1 < TW ? t + 1 : 0], q, t + 1, magic);
+            else if (ALWAYS_REFILL || next_group) dequant_tile<TW, SYM>(bn, wn[0], qn, 0, magic);
         }
         float4v part[MT];
 #pragma unroll
@@ -262,7 +298,10 @@ __device__ __forceinline__ void compute_group(u32x4 (&a)[MT][4], const QuantWord
         uint32_t s2 = q.sw[t >> 1];
         _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (s2 >> 16) : (s2 & 0xFFFFu)));
         float s = (float)sh;
-        if constexpr (OFF) {
+        if constexpr (OFF && SYM) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) fold_symmetric(acc[t][mt], part[mt], s, more_rows);
+        } else if constexpr (OFF) {
             const float zf = (float)((q.zbits >> (4 * t)) & 0xFu);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) fold_offset(acc[t][mt], part[mt], xs[mt], s, zf, more_rows);
@@ -274,7 +313,7 @@ __device__ __forceinline__ void compute_group(u32x4 (&a)[MT][4], const QuantWord
 #pragma unroll
         for (int i = 0; i < 4 * MT; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, ((OFF ? 24 : 40) + 4 * MT - 1) / (4 * MT), 0);   // VALU
+            __builtin_amdgcn_sched_group_barrier(0x002, ((OFF ? 24 : SYM ? 36 : 40) + 4 * MT - 1) / (4 * MT), 0);   // VALU
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -313,6 +352,7 @@ struct Out {
     const _Float16 *residual;
     int epi;
     RopeOut rope;
+    int sym;   // host side only: the caller vouches that every zero-point of the weight is 8
 };
 __device__ __forceinline__ bool paired_epilogue(const Out &o) { return o.epi >= kEpiSiluMul; }
 
@@ -621,7 +661,7 @@ __device__ __forceinline__ void finish_unit(const float4v (&acc)[TW][MT], float4
 
 // MT row tiles of 16, TW column tiles per wavefront, NW wavefronts per workgroup (all on the same
 // columns, each on its own quantisation groups), DEPTH groups of codes in flight per wavefront.
-template <int MT, int TW, int NW, int DEPTH>
+template <int MT, int TW, int NW, int DEPTH, bool SYM>
 __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) void gemm_kernel(
     const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, const Out y,
     float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused,
@@ -671,9 +711,9 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
     }
     half8v bc[4];
     if (n_w > 0) {
-        load_operands<MT>(fa, recw, xp, g0, c);
+        load_operands<MT, SYM>(fa, recw, xp, g0, c);
         if constexpr (kOff) offset_tile(bc, w[0][0], magic);
-        else dequant_tile<TW>(bc, w[0][0], tile_quant<TW>(fa.q, t0), 0, magic);
+        else dequant_tile<TW, SYM>(bc, w[0][0], tile_quant<TW>(fa.q, t0), 0, magic);
     }
     int i = 0;
     // steady state: every group handled here has a successor DEPTH groups ahead, so all loads are
@@ -682,8 +722,8 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int gi = i + u;
-            load_operands<MT>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
-            compute_group<MT, TW, true, kOff>(((u & 1) ? fb : fa).a, ((u & 1) ? fb : fa).q, ((u & 1) ? fa : fb).q,
+            load_operands<MT, SYM>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
+            compute_group<MT, TW, true, kOff, SYM>(((u & 1) ? fb : fa).a, ((u & 1) ? fb : fa).q, ((u & 1) ? fa : fb).q,
                                               w[u % DEPTH], w[(u + 1) % DEPTH], bc, acc,
                                               recw + (size_t)(gi + DEPTH) * kStep, true, true, t0, lane, magic, M > 1);
         }
@@ -694,8 +734,8 @@ __global__ __launch_bounds__(NW * 64, min_waves_per_simd(MT, TW, NW, DEPTH)) voi
         const int gi = i + u;
         if (gi < n_w) {   // uniform
             if (gi + 1 < n_w)
-                load_operands<MT>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
-            compute_group<MT, TW, false, kOff>(((u & 1) ? fb : fa).a, ((u & 1) ? fb : fa).q, ((u & 1) ? fa : fb).q,
+                load_operands<MT, SYM>((u & 1) ? fa : fb, recw + (size_t)(gi + 1) * kStep, xp, g0 + (gi + 1) * NW, c);
+            compute_group<MT, TW, false, kOff, SYM>(((u & 1) ? fb : fa).a, ((u & 1) ? fb : fa).q, ((u & 1) ? fa : fb).q,
                                                w[u % DEPTH], w[(u + 1) % DEPTH], bc, acc,
                                                recw + (size_t)(gi + DEPTH) * kStep, gi + DEPTH < n_w, gi + 1 < n_w, t0,
                                                lane, magic, M > 1);
@@ -831,13 +871,23 @@ __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW
     const int g_begin = kr.begin, g_end = kr.end;
     const int n = g_end - g_begin;
 
-    // x fragment this lane fetches for the workgroup: k step = wave, row tile mt
+    // what this lane fetches of a group's x tile: MT of its MT * 4 blocks of eight rows x two k steps, whole cache
+    // lines, swizzled in LDS (the layout cs_segment describes)
     const _Float16 *xs[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        int row = mt * 16 + c;
+    for (int i = 0; i < MT; ++i) {
+        const int blk = wave * MT + i;
+        const int mt = blk >> 2, jp = (blk >> 1) & 1, h = blk & 1, row8 = lane >> 3;
+        const int chunk = (lane & 7) ^ (4 * h + (row8 >> 1));
+        int row = mt * 16 + h * 8 + row8;
         row = row < M ? row : M - 1;   // rows >= M are never read; their products are never stored
-        xs[mt] = x + (size_t)row * K + wave * 32 + r * 8;
+        xs[i] = x + (size_t)row * K + jp * 64 + chunk * 8;
+    }
+    uint32_t xfrag[2];   // this lane's byte offset in a block pair for even and odd k steps
+    {
+        const int h = c >> 3, row8 = c & 7, sw = 4 * h + (row8 >> 1);
+        xfrag[0] = (uint32_t)(h * 1024 + (row8 * 8 + (r ^ sw)) * 16);
+        xfrag[1] = (uint32_t)(h * 1024 + (row8 * 8 + ((4 + r) ^ sw)) * 16);
     }
     const uint8_t *recw = packed + record_offset(nb, g_begin, groups);   // record of group 0 of the range
 
@@ -864,13 +914,15 @@ __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW
     };
     auto park_x = [&](int buf) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) xa[buf * kFragQuads + (mt * 4 + wave) * 64 + lane] = xreg[mt];
+        for (int i = 0; i < MT; ++i) xa[buf * kFragQuads + (wave * MT + i) * 64 + lane] = xreg[i];
     };
     auto fetch_a = [&](int buf) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a[mt][j] = xa[buf * kFragQuads + (mt * 4 + j) * 64 + lane];
+            for (int j = 0; j < 4; ++j)
+                a[mt][j] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint8_t *>(xa + buf * kFragQuads) +
+                                                           (mt * 2 + (j >> 1)) * 2048 + xfrag[j & 1]);
     };
 
     half8v bc[4];
@@ -958,7 +1010,7 @@ __global__ __launch_bounds__(256, ((MT == 1 || (MT * TW <= 12 && !(MT == 3 && TW
 // pipelining: few live registers, so that several wavefronts share a SIMD and the hardware overlaps
 // one wavefront's code expansion (vector ALU) with another's matrix instructions.  The code
 // registers of a tile are refilled, REFILL permitting, as soon as the tile is expanded.
-template <int MT, int TW, bool ALWAYS_REFILL>
+template <int MT, int TW, bool ALWAYS_REFILL, bool SYM>
 __device__ __forceinline__ void compute_group_lean(const u32x4 (&a)[MT][4], QuantWords &f, u32x4 (&w)[TW],
                                                    float4v (&acc)[TW][MT], const uint8_t *refill_rec, bool refill,
                                                    int t0, int c, int lane, const DequantConsts &magic)
@@ -968,14 +1020,14 @@ __device__ __forceinline__ void compute_group_lean(const u32x4 (&a)[MT][4], Quan
     const uint32_t tile_off = (uint32_t)(t0 * 1024 + lane * 16);
     if (ALWAYS_REFILL || refill) {
         f.s = load_global<u32x4>(rec + (uint32_t)(kScalesOff + c * 16));
-        f.z = load_global<uint32_t>(rec + (uint32_t)(kZerosOff + c * 4));
+        if constexpr (!SYM) f.z = load_global<uint32_t>(rec + (uint32_t)(kZerosOff + c * 4));
     }
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
         const uint32_t z = (q.zbits >> (4 * t)) & 0xFu;
         const uint32_t zz = z | (z << 16);
-        const half2v zneg = as_h2(zz | 0xE400E400u);            // -(1024 + z)
-        const half2v zneg16 = as_h2((zz << 4) | 0xD400D400u);   // -(64 + z)
+        const half2v zneg = as_h2(SYM ? kSymZneg : (zz | 0xE400E400u));              // -(1024 + z)
+        const half2v zneg16 = as_h2(SYM ? kSymZneg16 : ((zz << 4) | 0xD400D400u));   // -(64 + z)
         float4v part[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) part[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
@@ -1010,7 +1062,7 @@ __device__ __forceinline__ void compute_group_lean(const u32x4 (&a)[MT][4], Quan
 // stride `sstride` per wavefront unit; in last-arriver mode (fused) the contributor that takes the
 // last ticket adds all of them in slot order and stores.  Every wavefront of the workgroup passes the
 // same barriers whatever it returns through.
-template <int MT, int TW, int KS, int DEPTH>
+template <int MT, int TW, int KS, int DEPTH, bool SYM>
 __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed,
                                            const Out &y, float *__restrict__ partial, uint32_t *__restrict__ tickets,
                                            float4v *lds4, uint32_t &ticket_sh, int M, int N, int K, int groups,
@@ -1100,7 +1152,8 @@ __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const
         if (d < mine) {
             const uint8_t *rec = rec_of(d);
             qw[d].s = *reinterpret_cast<const u32x4 *>(rec + kScalesOff + c * 16);
-            qw[d].z = *reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4);
+            if constexpr (SYM) qw[d].z = kSymZeros;
+            else qw[d].z = *reinterpret_cast<const uint32_t *>(rec + kZerosOff + c * 4);
 #pragma unroll
             for (int t = 0; t < TW; ++t) w[d][t] = load_tile(rec, t0 + t, lane);
         }
@@ -1118,7 +1171,7 @@ __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const
             load_x(gi + 1);
             fetch_a(gi & 1);
             __builtin_amdgcn_sched_barrier(0);
-            compute_group_lean<MT, TW, true>(a, qw[u], w[u], acc, rec_of(gi + DEPTH), true, t0, c, lane, magic);
+            compute_group_lean<MT, TW, true, SYM>(a, qw[u], w[u], acc, rec_of(gi + DEPTH), true, t0, c, lane, magic);
             park_x((gi & 1) ^ 1);
         }
     }
@@ -1132,7 +1185,7 @@ __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const
             if (more) load_x(gi + 1);
             if (gi < mine) {
                 fetch_a(gi & 1);
-                compute_group_lean<MT, TW, false>(a, qw[u % DEPTH], w[u % DEPTH], acc, rec_of(gi + DEPTH),
+                compute_group_lean<MT, TW, false, SYM>(a, qw[u % DEPTH], w[u % DEPTH], acc, rec_of(gi + DEPTH),
                                                   gi + DEPTH < mine, t0, c, lane, magic);
             }
             if (more) park_x((gi & 1) ^ 1);
@@ -1238,7 +1291,7 @@ __device__ __forceinline__ void cs_segment(const _Float16 *__restrict__ x, const
 // runs of `per` to a 1-D grid, so every workgroup gets the same number of groups even when the units
 // alone do not fill the chip; a run that crosses a unit boundary is handled as two segments, and a
 // unit shared by several runs is summed by its last arriver.
-template <int MT, int TW, int KS, int DEPTH>
+template <int MT, int TW, int KS, int DEPTH, bool SYM>
 __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
     const _Float16 *__restrict__ x, const uint8_t *__restrict__ packed, const Out y,
     float *__restrict__ partial, uint32_t *__restrict__ tickets, int M, int N, int K, int groups, int S, int fused,
@@ -1248,7 +1301,7 @@ __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
     __shared__ uint32_t ticket_sh;
     if (per == 0) {
         const KRange kr = k_range(blockIdx.x, gq, grem);
-        cs_segment<MT, TW, KS, DEPTH>(x, packed, y, partial, tickets, lds4, ticket_sh, M, N, K, groups, blockIdx.y,
+        cs_segment<MT, TW, KS, DEPTH, SYM>(x, packed, y, partial, tickets, lds4, ticket_sh, M, N, K, groups, blockIdx.y,
                                       kr.begin, kr.end, S, blockIdx.x, S, fused);
         return;
     }
@@ -1261,7 +1314,7 @@ __global__ __launch_bounds__(256 * KS) void gemm_cs_kernel(
         const int g1 = min(groups, g0 + (end - item));
         const int first = (u * groups) / per, last = ((u + 1) * groups - 1) / per;   // runs that touch unit u
         if (again) __syncthreads();   // the previous segment's epilogue has left LDS
-        cs_segment<MT, TW, KS, DEPTH>(x, packed, y, partial, tickets, lds4, ticket_sh, M, N, K, groups, u, g0, g1,
+        cs_segment<MT, TW, KS, DEPTH, SYM>(x, packed, y, partial, tickets, lds4, ticket_sh, M, N, K, groups, u, g0, g1,
                                       last - first + 1, (int)blockIdx.x - first, S, 1);
         item += g1 - g0;
         again = true;
@@ -1492,15 +1545,17 @@ static size_t partial_bytes(int mt, int nblocks, const Plan &pl, int groups)
     return slots > 1 ? units * slots * (4 * pl.tw * mt * 64) * sizeof(float) : 0;
 }
 
-template <int MT, int TW, int NW, int DEPTH>
-static int launch(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, int fused,
-                  void *workspace, hipStream_t stream)
+// symmetric-weight instantiations exist for the K-split and the high-occupancy column-split kernels; the other
+// two families (and any call without the caller's word for it) read the zero-points, which is always correct
+template <int MT, int TW, int NW, int DEPTH, bool SYM>
+static int launch_sym(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, int fused,
+                      void *workspace, hipStream_t stream)
 {
     static bool lds_ok = false;   // LDS above 64 KB needs an opt-in, once per kernel
     const size_t lds_bytes = (size_t)NW * 4 * TW * MT * 64 * sizeof(float);
     if (lds_bytes > 160 * 1024) return W4A16_EUNSUP;
     if (!lds_ok && lds_bytes > 48 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<MT, TW, NW, DEPTH>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<MT, TW, NW, DEPTH, SYM>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
             return W4A16_EHIP;
         lds_ok = true;
@@ -1509,13 +1564,21 @@ static int launch(const void *x, const void *packed, const Out &y, int M, int N,
     const int units = nblocks * kTiles / TW;
     uint32_t *tickets = reinterpret_cast<uint32_t *>(workspace);
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
-    hipLaunchKernelGGL((gemm_kernel<MT, TW, NW, DEPTH>), dim3((unsigned)S, (unsigned)units), dim3(NW * 64), lds_bytes,
+    hipLaunchKernelGGL((gemm_kernel<MT, TW, NW, DEPTH, SYM>), dim3((unsigned)S, (unsigned)units), dim3(NW * 64), lds_bytes,
                        stream, (const _Float16 *)x, (const uint8_t *)packed, y, partial, tickets, M, N,
                        K, groups, S, fused, groups / S, groups % S);
     if (S > 1 && !fused)
         hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
                            (const float *)partial, y, M, N, S);
     return launch_status();
+}
+
+template <int MT, int TW, int NW, int DEPTH>
+static int launch(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, int fused,
+                  void *workspace, hipStream_t stream)
+{
+    return y.sym ? launch_sym<MT, TW, NW, DEPTH, true>(x, packed, y, M, N, K, S, fused, workspace, stream)
+                 : launch_sym<MT, TW, NW, DEPTH, false>(x, packed, y, M, N, K, S, fused, workspace, stream);
 }
 
 template <int MT, int TW, int DEPTH>
@@ -1541,15 +1604,15 @@ static int launch_ns(const void *x, const void *packed, const Out &y, int M, int
     return launch_status();
 }
 
-template <int MT, int TW, int KS, int DEPTH>
-static int launch_cs(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, int fused,
-                     void *workspace, hipStream_t stream)
+template <int MT, int TW, int KS, int DEPTH, bool SYM>
+static int launch_cs_sym(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, int fused,
+                         void *workspace, hipStream_t stream)
 {
     static bool lds_ok = false;
     const size_t lds_bytes = (size_t)KS * TW * MT * 4096;   // 4*KS wavefronts' results; the x tiles (KS * MT * 8 KB) fit inside
     if (lds_bytes > 160 * 1024) return W4A16_EUNSUP;
     if (!lds_ok && lds_bytes > 48 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_cs_kernel<MT, TW, KS, DEPTH>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_cs_kernel<MT, TW, KS, DEPTH, SYM>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess)
             return W4A16_EHIP;
         lds_ok = true;
@@ -1559,18 +1622,26 @@ static int launch_cs(const void *x, const void *packed, const Out &y, int M, int
     float *partial = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + kTicketBytes);
     if (S == 0) {   // even split of (unit, group) pairs over the compute units, summed by last arrivers
         const EvenSplit e = even_split((units + 3) / 4, groups);
-        hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH>), dim3((unsigned)e.runs), dim3(256 * KS), lds_bytes, stream,
+        hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH, SYM>), dim3((unsigned)e.runs), dim3(256 * KS), lds_bytes, stream,
                            (const _Float16 *)x, (const uint8_t *)packed, y, partial, tickets, M, N, K, groups,
                            e.max_slots, 1, 0, 0, e.per, (units + 3) / 4);
         return launch_status();
     }
-    hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH>), dim3((unsigned)S, (unsigned)((units + 3) / 4)), dim3(256 * KS),
+    hipLaunchKernelGGL((gemm_cs_kernel<MT, TW, KS, DEPTH, SYM>), dim3((unsigned)S, (unsigned)((units + 3) / 4)), dim3(256 * KS),
                        lds_bytes, stream, (const _Float16 *)x, (const uint8_t *)packed, y, partial, tickets, M, N, K,
                        groups, S, fused, groups / S, groups % S, 0, 0);
     if (S > 1 && !fused)
         hipLaunchKernelGGL((splitk_reduce_kernel<MT, TW>), dim3((unsigned)units), dim3(kReduceThreads), 0, stream,
                            (const float *)partial, y, M, N, S);
     return launch_status();
+}
+
+template <int MT, int TW, int KS, int DEPTH>
+static int launch_cs(const void *x, const void *packed, const Out &y, int M, int N, int K, int S, int fused,
+                     void *workspace, hipStream_t stream)
+{
+    return y.sym ? launch_cs_sym<MT, TW, KS, DEPTH, true>(x, packed, y, M, N, K, S, fused, workspace, stream)
+                 : launch_cs_sym<MT, TW, KS, DEPTH, false>(x, packed, y, M, N, K, S, fused, workspace, stream);
 }
 
 template <int TW, int NW, int NG>
@@ -1735,7 +1806,7 @@ int w4a16_plan_describe(int M, int N, int K, int G, int *out)
     if (pl.tw == 0) return W4A16_EUNSUP;
     const int family = pl.ng > 0 ? 1 : pl.ks > 0 ? 3 : pl.nw == 1 ? 2 : 0;
     const int plan[8] = {family, (M + 15) / 16, pl.tw, family == 3 ? pl.ks : pl.nw, family == 1 ? pl.ng : pl.depth,
-                         pl.S, pl.S > 1 ? pl.fused : 0, 0};
+                         pl.S, pl.S > 1 ? pl.fused : 0, (family == 0 || family == 3) ? 1 : 0};
     for (int i = 0; i < 8; ++i) out[i] = plan[i];
     return W4A16_OK;
 }
@@ -1749,6 +1820,8 @@ int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, 
 int w4a16_gemm_fused(const void *x, const void *packed, void *y, int M, int N, int K, int G, int epilogue,
                      const void *residual, void *workspace, size_t workspace_bytes, void *stream)
 {
+    const int sym = (epilogue & W4A16_SYMMETRIC) ? 1 : 0;
+    epilogue &= ~W4A16_SYMMETRIC;
     if (epilogue != W4A16_EPI_NONE && epilogue != W4A16_EPI_RESIDUAL && epilogue != W4A16_EPI_SILU_MUL)
         return W4A16_EINVAL;
     if (epilogue == W4A16_EPI_RESIDUAL) {
@@ -1760,14 +1833,25 @@ int w4a16_gemm_fused(const void *x, const void *packed, void *y, int M, int N, i
     if (epilogue == W4A16_EPI_SILU_MUL && (N <= 0 || N % 32 != 0)) return W4A16_EINVAL;
     static_assert(W4A16_EPI_NONE == kEpiNone && W4A16_EPI_RESIDUAL == kEpiResidual && W4A16_EPI_SILU_MUL == kEpiSiluMul,
                   "public and internal epilogue codes agree");
-    return gemm_entry(x, packed, Out{(_Float16 *)y, (const _Float16 *)residual, epilogue}, M, N, K, G, workspace,
-                      workspace_bytes, stream);
+    Out out = {(_Float16 *)y, (const _Float16 *)residual, epilogue};
+    out.sym = sym;
+    return gemm_entry(x, packed, out, M, N, K, G, workspace, workspace_bytes, stream);
 }
 
 
 int w4a16_gemm_rope(const void *x, const void *packed, int M, int K, int G, const int32_t *pos, const float *cos_table,
                     const float *sin_table, int n_pos, void *q, void *k_cache, void *v_cache, int P, int Hq, int Hkv, int D,
                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    return w4::gemm_rope(x, packed, M, K, G, pos, cos_table, sin_table, n_pos, q, k_cache, v_cache, P, Hq, Hkv, D, workspace,
+                         workspace_bytes, stream, 0);
+}
+
+}  // extern "C"
+
+int w4::gemm_rope(const void *x, const void *packed, int M, int K, int G, const int32_t *pos, const float *cos_table,
+                  const float *sin_table, int n_pos, void *q, void *k_cache, void *v_cache, int P, int Hq, int Hkv, int D,
+                  void *workspace, size_t workspace_bytes, void *stream, int symmetric)
 {
     if (P < 0 || Hq < 1 || Hkv < 1 || D < 32 || D % 32 != 0 || n_pos < 1) return W4A16_EINVAL;
     if ((long long)(Hq + 2 * Hkv) * D > 0x7fffffff) return W4A16_EUNSUP;
@@ -1777,7 +1861,6 @@ int w4a16_gemm_rope(const void *x, const void *packed, int M, int K, int G, cons
         return W4A16_EALIGN;
     Out out = {(_Float16 *)q, nullptr, kEpiRope,
                {pos, cos_table, sin_table, (_Float16 *)q, (_Float16 *)k_cache, (_Float16 *)v_cache, n_pos, P, Hq, Hkv, D}};
+    out.sym = symmetric ? 1 : 0;
     return gemm_entry(x, packed, out, M, (Hq + 2 * Hkv) * D, K, G, workspace, workspace_bytes, stream);
 }
-
-}  // extern "C"

@@ -63,6 +63,11 @@ struct Params {
 };
 Params &params();
 
+// w4a16_gemm_rope with the caller's word that the weight is symmetric (the exported entry point passes 0)
+int gemm_rope(const void *x, const void *packed, int M, int K, int G, const int32_t *pos, const float *cos_table,
+              const float *sin_table, int n_pos, void *q, void *k_cache, void *v_cache, int P, int Hq, int Hkv, int D,
+              void *workspace, size_t workspace_bytes, void *stream, int symmetric);
+
 // number of 256-byte-aligned bytes reserved for tickets at the start of a workspace
 constexpr size_t kTicketBytes = 16384;   // 4096 tickets
 constexpr int kMaxTickets = 4096;

@@ -207,16 +207,17 @@ extern "C" int w4a16_decoder_layer(const w4a16_layer_weights *w, void *h, int M,
     if (!h || !s->norm || (!s->qkv && !w->qkv_heads_packed) || !s->q || !s->attn || !s->act) return W4A16_ENULL;
     const int Nqkv = (Hq + 2 * Hkv) * D;
     const float scale = 1.0f / sqrtf((float)D);
+    const int sym = w->symmetric ? W4A16_SYMMETRIC : 0;
     int rc;
     // attention block: h += Wo . attn(rope(Wqkv . norm(h)))
     if ((rc = rms_norm(h, w->norm1_gamma, s->norm, M, H, w->eps, stream)) != W4A16_OK) return rc;
     if (w->qkv_heads_packed) {   // projection, rotary embedding and K/V append in one kernel
-        if ((rc = w4a16_gemm_rope(s->norm, w->qkv_packed, M, H, kGroup, pos, cos_table, sin_table, n_pos, s->q, k_cache,
-                                  v_cache, P, Hq, Hkv, D, s->gemm_workspace, s->gemm_workspace_bytes, stream)) != W4A16_OK)
+        if ((rc = w4::gemm_rope(s->norm, w->qkv_packed, M, H, kGroup, pos, cos_table, sin_table, n_pos, s->q, k_cache, v_cache,
+                                P, Hq, Hkv, D, s->gemm_workspace, s->gemm_workspace_bytes, stream, w->symmetric)) != W4A16_OK)
             return rc;
     } else {
-        if ((rc = w4a16_gemm(s->norm, w->qkv_packed, s->qkv, M, Nqkv, H, kGroup, s->gemm_workspace, s->gemm_workspace_bytes,
-                             stream)) != W4A16_OK)
+        if ((rc = w4a16_gemm_fused(s->norm, w->qkv_packed, s->qkv, M, Nqkv, H, kGroup, W4A16_EPI_NONE | sym, nullptr,
+                                   s->gemm_workspace, s->gemm_workspace_bytes, stream)) != W4A16_OK)
             return rc;
         if ((rc = rope_append(s->qkv, pos, cos_table, sin_table, n_pos, s->q, k_cache, v_cache, M, P, Hq, Hkv, D, stream)) !=
             W4A16_OK)
@@ -225,14 +226,14 @@ extern "C" int w4a16_decoder_layer(const w4a16_layer_weights *w, void *h, int M,
     if ((rc = tree_verify_attn(s->q, k_cache, v_cache, mask, s->attn, M, P, Hq, Hkv, D, scale, s->attn_workspace,
                                s->attn_workspace_bytes, stream)) != W4A16_OK)
         return rc;
-    if ((rc = w4a16_gemm_fused(s->attn, w->o_packed, h, M, H, Hq * D, kGroup, W4A16_EPI_RESIDUAL, h, s->gemm_workspace,
+    if ((rc = w4a16_gemm_fused(s->attn, w->o_packed, h, M, H, Hq * D, kGroup, W4A16_EPI_RESIDUAL | sym, h, s->gemm_workspace,
                                s->gemm_workspace_bytes, stream)) != W4A16_OK)
         return rc;
     // feed-forward block: h += Wdown . (silu(Wgate . n) * (Wup . n)),  n = norm(h)
     if ((rc = rms_norm(h, w->norm2_gamma, s->norm, M, H, w->eps, stream)) != W4A16_OK) return rc;
-    if ((rc = w4a16_gemm_fused(s->norm, w->gate_up_packed, s->act, M, 2 * F, H, kGroup, W4A16_EPI_SILU_MUL, nullptr,
+    if ((rc = w4a16_gemm_fused(s->norm, w->gate_up_packed, s->act, M, 2 * F, H, kGroup, W4A16_EPI_SILU_MUL | sym, nullptr,
                                s->gemm_workspace, s->gemm_workspace_bytes, stream)) != W4A16_OK)
         return rc;
-    return w4a16_gemm_fused(s->act, w->down_packed, h, M, H, F, kGroup, W4A16_EPI_RESIDUAL, h, s->gemm_workspace,
+    return w4a16_gemm_fused(s->act, w->down_packed, h, M, H, F, kGroup, W4A16_EPI_RESIDUAL | sym, h, s->gemm_workspace,
                             s->gemm_workspace_bytes, stream);
 }

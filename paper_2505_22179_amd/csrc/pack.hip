@@ -135,6 +135,24 @@ __global__ void dequant_kernel(const uint8_t *__restrict__ packed, float *__rest
     W[idx] = (float)(q - z) * __half2float(s);
 }
 
+// *flag = 1 unless some zero-point of a real column differs from 8 (thread = one zero-point word: the eight
+// tiles of one column position of one record).  Threads that find a difference all store the same 0.
+__global__ void symmetric_begin_kernel(int32_t *flag) { *flag = 1; }
+__global__ __launch_bounds__(256) void symmetric_check_kernel(const uint8_t *__restrict__ packed, int32_t *flag, int N,
+                                                              int groups, size_t words)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= words) return;
+    const size_t record = i >> 4;
+    const int c = (int)(i & 15), nb = (int)(record / (size_t)groups);
+    const uint32_t z = *reinterpret_cast<const uint32_t *>(packed + record * kRecordBytes + kZerosOff + c * 4);
+    bool all8 = true;
+#pragma unroll
+    for (int t = 0; t < kTiles; ++t)
+        if (nb * kBlockCols + t * 16 + c < N && ((z >> (4 * t)) & 0xFu) != 8u) all8 = false;
+    if (!all8) *flag = 0;
+}
+
 __global__ void fill_zero_kernel(uint32_t *p, size_t words)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -239,6 +257,20 @@ int w4a16_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
     size_t words = kTicketBytes / 4;
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0,
                        (hipStream_t)stream, (uint32_t *)workspace, words);
+    return launch_status();
+}
+
+int w4a16_weight_is_symmetric(const void *packed, int N, int K, int G, int32_t *flag, void *stream)
+{
+    int rc = check_weight_shape(N, K, G);
+    if (rc != W4A16_OK) return rc;
+    if (!packed || !flag) return W4A16_ENULL;
+    if (misaligned(packed) || (reinterpret_cast<uintptr_t>(flag) & 3u)) return W4A16_EALIGN;
+    const int groups = K / kGroup;
+    const size_t words = (size_t)(pad_cols(N) / kBlockCols) * groups * 16;
+    hipLaunchKernelGGL(symmetric_begin_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, flag);
+    hipLaunchKernelGGL(symmetric_check_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint8_t *)packed, flag, N, groups, words);
     return launch_status();
 }
 

@@ -71,11 +71,13 @@ class LinearInputs:
 
 
 def make_linear(seed: int, M: int, K: int, N: int, G: int = 128, *, x_kind: str = "normal",
-                scale_kind: str = "uniform", m_max: int | None = None) -> LinearInputs:
+                scale_kind: str = "uniform", m_max: int | None = None, zero_kind: str = "uniform") -> LinearInputs:
     """Draw order: x [m_max, K], codes [K, N], scales [K/G, N], zeros [K/G, N].
 
     x_kind:     "normal"  fp16(N(0,1))            | "small_int" uniform in {-2,-1,0,1,2}
     scale_kind: "uniform" fp16(U[1e-3, 1e-2])     | "pow2" the constant 2**-7
+    zero_kind:  "uniform" integers in 0..15       | "eight" the constant 8 (a symmetrically quantised weight,
+                the scheme of paper section 2.2)
     Rows 0..M-1 of the x draw are returned, so a smaller M sees a prefix of the same matrix.
     """
     assert K % G == 0 and K % 8 == 0 and N % 8 == 0
@@ -96,6 +98,10 @@ def make_linear(seed: int, M: int, K: int, N: int, G: int = 128, *, x_kind: str 
     else:
         raise ValueError(scale_kind)
     zeros = rng.integers(0, 16, size=(K // G, N), dtype=np.uint8)
+    if zero_kind == "eight":
+        zeros = np.full((K // G, N), 8, dtype=np.uint8)   # drawn all the same: the stream position stays identical
+    elif zero_kind != "uniform":
+        raise ValueError(zero_kind)
     return LinearInputs(M, K, N, G, np.ascontiguousarray(x[:M]), codes, zeros,
                         pack_rows(codes), scales, pack_cols(zeros))
 

@@ -206,3 +206,26 @@ def test_generator_statistics():
         inp = I.make_linear(I.seed_for(1, 0), 8, K, 512)
         y32, _, _ = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, G, want64=False)
         assert abs(y32.std() / sigma - 1) < 0.05
+
+
+def test_symmetric_weight_is_the_mid_code_special_case():
+    """A symmetrically quantised weight (paper section 2.2) is the special case zero-point = 8 of the oracle's
+    formula: with codes read as signed values q - 8 in -8..7 the weight is (q - 8) * s and the layer is an
+    ordinary matmul with that matrix; the mid-code 8 itself is weight 0 whatever the scale."""
+    M, K, N = 3, 256, 24
+    inp = I.make_linear(4242, M, K, N, zero_kind="eight")
+    assert (inp.zeros == 8).all() and (R.unpack_zeros(inp.qzeros) == 8).all()
+    W = R.dequant(inp.qweight, inp.scales, inp.qzeros, G)
+    signed = inp.codes.astype(np.int64) - 8                       # two's-complement reading of the 4-bit code
+    assert signed.min() == -8 and signed.max() == 7
+    s64 = np.repeat(inp.scales.astype(np.float64), G, axis=0)
+    assert np.array_equal(W.astype(np.float64), signed * s64)     # exact: 4 + 11 significant bits
+    assert (W[inp.codes == 8] == 0).all() and (inp.codes == 8).any()
+    y32, y64, _ = R.w4a16_gemm(inp.x, inp.qweight, inp.scales, inp.qzeros, G)
+    want = inp.x.astype(np.float64) @ (signed * s64)
+    assert np.allclose(y64, want, rtol=0, atol=1e-12 * np.abs(want).max())
+    assert np.abs(y32 - want).max() <= K * 2.0 ** -24 * (np.abs(inp.x.astype(np.float64)) @ np.abs(signed * s64)).max()
+    # the same codes and scales under other zero-points give another answer: the special case is not vacuous
+    other = I.make_linear(4242, M, K, N)
+    assert np.array_equal(other.qweight, inp.qweight) and np.array_equal(other.scales.view(np.uint16), inp.scales.view(np.uint16))
+    assert not np.array_equal(R.w4a16_gemm(other.x, other.qweight, other.scales, other.qzeros, G)[0], y32)
