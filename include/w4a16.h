@@ -154,7 +154,8 @@ size_t tree_verify_attn_workspace_bytes(int M, int P, int Hq, int Hkv, int D);
  *   out[i,h,:] = sum_j softmax_j(scale * q[i,h,:].k[j,kvh,:]) * v[j,kvh,:]
  * q, out fp16 [M, Hq, D]; k, v fp16 [P+M, Hkv, D] (draft keys at rows P..P+M-1); mask uint8 [M, M]
  * row-major.  Softmax and accumulation in fp32.  Requires D == 128, 1 <= M <= 64, Hq % Hkv == 0,
- * Hq/Hkv <= 8, P >= 0, and every row must see at least one key.  `workspace` as for w4a16_gemm,
+ * Hq/Hkv <= 8, P >= 0, a finite scale > 0 (W4A16_EINVAL otherwise), and every row must see at least
+ * one key.  `workspace` as for w4a16_gemm,
  * sized by tree_verify_attn_workspace_bytes and initialised by w4a16_workspace_init. */
 int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t *mask, void *out,
                      int M, int P, int Hq, int Hkv, int D, float scale,

@@ -3,10 +3,15 @@
 // Scores are computed transposed, S^T = K . Q^T, with 16x16x32 fp16 MFMA steps over the head
 // dimension, so that a lane ends up with eight scores of ONE query row: exactly the operand
 // fragment the P.V product needs, with no shuffle in between.  The tree mask is applied to the
-// draft keys only, softmax runs online in fp32 (base-2 exponentials), and V reaches its MFMA
-// operand through a transposed LDS tile, because the contraction there runs over keys while V is
-// stored with the head dimension contiguous.  Key ranges of different workgroups are combined by
-// a second small kernel, in range order, so the result does not depend on scheduling.
+// draft keys only, softmax runs online in fp32 (base-2 exponentials), and V enters its product
+// transposed (the contraction there runs over keys while V is stored with the head dimension
+// contiguous).  Key ranges of different workgroups are combined in range order, by the last
+// workgroup of a tile to finish or by a second small kernel, so the result does not depend on
+// scheduling.  Two kernels: tree_attn_shared_kernel, which every call runs by default (eight
+// wavefronts, K and V tiles brought to LDS once per workgroup and shared), and the older
+// tree_attn_kernel (every wavefront fetches its own K fragments and V rows), kept selectable.
+#include <type_traits>
+
 #include "internal.h"
 #include "devscope.h"
 
@@ -25,6 +30,22 @@ constexpr int kRowsPad = 64;
 constexpr int attn_lds_bytes(int rt, int rg) { return 4 * rg * (8 * rt * 4 + 2 * rt) * 64 * 4; }
 constexpr int kMaxSplits = 16;   // key ranges per head (the merge keeps one value per range in registers)
 
+// v_max3_f32 and v_max_f32 as they stand: fmaxf chains are compiled with a canonicalising v_max x, x per
+// operand, which doubles the instruction count of a row maximum; no score here is a NaN.
+__device__ __forceinline__ float max_of_three(float a, float b, float c)
+{
+    float d;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+
+__device__ __forceinline__ float max_of_two(float a, float b)
+{
+    float d;
+    asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+
 // Maximum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (the lanes that share a query row), returned to
 // all four.  v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of
 // its second, v_permlane32_swap the upper half of the first with the lower half of the second; applied
@@ -35,10 +56,10 @@ __device__ __forceinline__ float row_group_max(float v)
 {
     float a = v, b = v;
     asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-    a = fmaxf(a, b);
+    a = max_of_two(a, b);
     b = a;
     asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-    return fmaxf(a, b);
+    return max_of_two(a, b);
 }
 
 constexpr float kLowest = -1.0e30f;   // "no key seen yet": finite, so differences of two of them are 0, not NaN
@@ -428,6 +449,371 @@ __global__ __launch_bounds__(256 * RG) void tree_attn_kernel(
         merge_ranges<kMaxSplits, 1>(unit_o, unit_ml, out, tid, 256 * RG, items, M, Hq, nsplit, rep, unit);
 }
 
+// ---- Row tiles of 33..64 rows: K and V tiles shared through LDS -------------------------------------
+// The kernel above lets every wavefront fetch its own K fragments and V rows from global memory.  With
+// a full tile that costs twice: a K fragment load touches sixteen key rows with 64 bytes each, the
+// costliest pattern for the address path of a compute unit (about four times the time of a load of
+// whole cache lines), and 64 rows of accumulators and Q fragments fill the register file of a SIMD
+// with one wavefront, so nothing overlaps that wavefront's softmax arithmetic, its matrix products
+// and its memory waits.  Here a workgroup has eight wavefronts, two per SIMD: wavefront (kw, rh)
+// holds tile rows 32 rh .. 32 rh + 31 and takes key step 4 t + kw of the workgroup's range in round t.
+// All K and V tiles of a round (four steps of 32 keys, 8 KB each for K and for V) are brought in one
+// round ahead by direct global -> LDS loads of whole key rows (one instruction: four rows of 256 B),
+// the K tile of a step by wavefront (kw, 0) and the V tile by (kw, 1), double-buffered, one workgroup
+// barrier per round.  Both wavefronts of a pair read the same tiles:
+//   K fragments   one 16-byte LDS read per fragment; the 16-byte chunks of a key row are stored at
+//                 chunk ^ (key % 8), the permutation being applied to the SOURCE address of the
+//                 transfer (its destination is fixed: lane l of a transfer fills bytes 16 l ..)
+//   V^T fragments the transposing LDS read (ds_read_b64_tr_b16): in each block of 16 lanes, lane s
+//                 points at four consecutive head-dim elements 4 (s % 4) .. of key row s / 4, and
+//                 lane c receives element c of the four rows -- four keys at one head-dim index,
+//                 which is the operand layout, with no pass through registers.  Chunks of a V row
+//                 are stored at chunk ^ (2 key % 16).
+// Q reaches its fragments the same way (once, through the second round buffer).  The softmax is that
+// of the kernel above with the scale folded into the exponent's multiply-add; the states of the four
+// key wavefronts of a row half meet in LDS at the end, in a row-major layout (rows padded to 528 B)
+// from which thread t then reads, merges and stores whole 512-byte output rows.
+constexpr int kSharedWaves = 8;
+constexpr int kTileBytes = kKeyBlock * kHeadDim * 2;         // one K or V tile: 32 keys x 256 B
+constexpr int kStepBytes = 2 * kTileBytes;                   // K tile, then V tile
+constexpr int kRoundBytes = 4 * kStepBytes;                  // the four key steps of a round
+constexpr int kExRow = kHeadDim * 4 + 16;                    // exchange row: 128 fp32 + 16 B of padding
+constexpr int kExWave = 32 * kExRow;                         // per wavefront: its 32 rows
+constexpr int kExState = kSharedWaves * kExWave;             // then [8 wavefronts][32 rows] (max, sum)
+constexpr int kSharedLds = kExState + kSharedWaves * 32 * 8 > 2 * kRoundBytes ? kExState + kSharedWaves * 32 * 8 : 2 * kRoundBytes;
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v lds_short4v;
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(size_t)(lds_void *)p;
+}
+// The transposing read of the rows at lds_addr and 16 key rows (4 KB) further on.  Written in assembly: through
+// the builtin the compiler waits, before every such read, for ALL outstanding global -> LDS transfers -- the
+// next round's, requested a moment earlier precisely so that they overlap this round's arithmetic.  The
+// compiler therefore does not know of these reads; wait_lds_reads says when their results may be used.
+template <int OFFSET>
+__device__ __forceinline__ void read_transposed_pair(short4v &lo, short4v &hi, uint32_t lds_addr)
+{
+    asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
+                 : "=&v"(lo), "=&v"(hi)
+                 : "v"(lds_addr), "n"(OFFSET), "n"(OFFSET + 16 * 256));
+}
+// returns once at most N LDS operations of this wavefront (the N most recent) are still under way; `first` is
+// the first result of the oldest pair still awaited, so that its use cannot be moved above the wait
+template <int N>
+__device__ __forceinline__ void wait_lds_reads(short4v &first)
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(first) : "n"(N));
+}
+// lane l's 16 bytes at src land at lds_base + 16 l (lds_base wavefront-uniform); counted by vmcnt
+__device__ __forceinline__ void row_to_lds(const uint8_t *src, uint8_t *lds_base)
+{
+    __builtin_amdgcn_global_load_lds((global_void *)src, (lds_void *)lds_base, 16, 0, 0);
+}
+
+__global__ __launch_bounds__(64 * kSharedWaves) void tree_attn_shared_kernel(
+    const _Float16 *__restrict__ q, const _Float16 *__restrict__ k, const _Float16 *__restrict__ v,
+    const uint8_t *__restrict__ mask, _Float16 *__restrict__ out, float *__restrict__ part_o,
+    float *__restrict__ part_ml, uint32_t *__restrict__ tickets, int M, int P, int Hq, int Hkv,
+    float scale_log2e, int nsplit, int bq, int brem, int rep, int fused)
+{
+    extern __shared__ float4v smem4[];
+    uint8_t *lds = reinterpret_cast<uint8_t *>(smem4);
+    const unsigned grid = gridDim.x;
+    fetch_arguments_together(q, k, v, mask, out, part_o, part_ml, tickets, M, P, Hq, Hkv, scale_log2e, nsplit, bq, brem, rep,
+                             fused, grid);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kw = wave >> 1, rh = wave & 1;   // key wavefront, row half
+    const int r = lane >> 4, c = lane & 15;
+    int lid = blockIdx.x;   // workgroups of one KV head on one XCD (see tree_attn_kernel)
+    if ((grid & 7) == 0) lid = (blockIdx.x & 7) * (grid >> 3) + (blockIdx.x >> 3);
+    const int unit = lid / nsplit, sp = lid % nsplit;
+    const int kvh = (rep ? unit * rep : unit) / (Hq / Hkv);
+    const int R = rep ? M * rep : M;   // valid rows of the tile
+    const int T = P + M;
+    const int b0 = sp * bq + (sp < brem ? sp : brem), b1 = b0 + bq + (sp < brem ? 1 : 0);
+    const int rounds = (b1 - b0 + 3) >> 2;
+    const size_t kv_row_bytes = (size_t)Hkv * kHeadDim * 2;
+
+    // tile row -> its query row and the element offset of its (query row, head) in q and out; rows >= R repeat
+    // row R - 1 and are never stored
+    auto locate = [&](int rho, int &qrow) {
+        rho = min(rho, R - 1);
+        const int j = rep ? rho / M : 0;
+        qrow = rho - j * M;
+        return (uint32_t)(qrow * Hq + (rep ? unit * rep + j : unit)) * kHeadDim;
+    };
+    // tree mask of the draft keys, one 64-bit word per query row, in the workgroups that reach them:
+    // wavefront w asks for the bytes of rows 8 w .. 8 w + 7 first (lane = column) and turns them into words
+    // after the transfers below have been requested
+    __shared__ uint64_t row_bits[kRowsPad];
+    const bool reaches_draft = b1 * kKeyBlock > P;   // uniform over the workgroup
+    uint8_t mask_byte[8];
+    if (reaches_draft) {
+        const int mcol = min(lane, M - 1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mask_byte[i] = mask[(size_t)min(wave * 8 + i, M - 1) * M + mcol];
+    }
+
+    // transfers: lane l of transfer i fills bytes 16 (l % 16) .. of tile row 4 i + l / 16
+    const int trow = lane >> 4, tchunk = lane & 15;
+    // LDS: per key wavefront pair 32 KB = two buffers of (K tile, V tile); Q sits in pair 0's second buffer until
+    // that pair requests its round 1
+    uint8_t *const pair_lds = lds + kw * (2 * kStepBytes);
+    uint8_t *const qtile = lds + kStepBytes;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int rho = 4 * (2 * wave + u) + trow;
+        int qrow;
+        const uint32_t elem = locate(rho, qrow);
+        row_to_lds(reinterpret_cast<const uint8_t *>(q) + (size_t)elem * 2 + ((tchunk ^ (rho & 7)) << 4), qtile + (2 * wave + u) * 1024);
+    }
+    // K (rh = 0) or V (rh = 1) rows of this wavefront's key steps.  Tile row 4 i + trow goes to chunk positions
+    // permuted by key % 8 (K) or 2 key % 16 (V), which depends on i through its parity only: two lane offsets,
+    // added to a wavefront-uniform address that moves with the step and with i.
+    const uint8_t *const kv_src = reinterpret_cast<const uint8_t *>(rh ? v : k) + (size_t)kvh * kHeadDim * 2;
+    uint32_t lane_src[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const int key = 4 * par + trow;
+        lane_src[par] = (uint32_t)trow * (uint32_t)kv_row_bytes + (uint32_t)((tchunk ^ (rh ? (2 * key) & 15 : key & 7)) << 4);
+    }
+    auto request_round = [&](int t, int buf) {
+        const int step = b0 + 4 * t + kw;
+        if (step >= b1) return;   // uniform over the wavefront
+        const int key0 = step * kKeyBlock;
+        uint8_t *dst = pair_lds + buf * kStepBytes + rh * kTileBytes;
+        if (key0 + kKeyBlock <= T) {
+            const uint8_t *from = kv_src + (size_t)key0 * kv_row_bytes;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) row_to_lds(from + (size_t)(4 * i) * kv_row_bytes + lane_src[i & 1], dst + i * 1024);
+        } else {   // the last step of all: rows beyond the last key repeat it (they are masked out below)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int key = 4 * i + trow;
+                const int swz = rh ? (2 * key) & 15 : key & 7;
+                row_to_lds(kv_src + (size_t)min(key0 + key, T - 1) * kv_row_bytes + ((tchunk ^ swz) << 4), dst + i * 1024);
+            }
+        }
+    };
+    request_round(0, 0);
+
+    if (reaches_draft) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint64_t bits = __ballot(mask_byte[i] != 0 && wave * 8 + i < M && lane < M);
+            if (lane == i) row_bits[wave * 8 + i] = bits;
+        }
+    }
+    // Q fragments (second operand of S^T): lane (r, c) holds elements 32 j + 8 r .. + 7 of tile row 32 rh + 16 rt + c
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    half8v qf[2][4];
+    uint64_t mbits[2] = {0, 0};
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+        const int rho = 32 * rh + 16 * rt + c;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            qf[rt][j] = *reinterpret_cast<const half8v *>(qtile + rho * 256 + (((4 * j + r) ^ (rho & 7)) << 4));
+        int qrow;
+        locate(rho, qrow);
+        if (reaches_draft) mbits[rt] = row_bits[qrow];
+    }
+
+    float4v o[8][2];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) o[dt][rt] = (float4v){0.f, 0.f, 0.f, 0.f};
+    float m_run[2] = {kLowest, kLowest}, l_run[2] = {0.f, 0.f};   // l_run: this lane's share (its keys) of the row's sum
+
+    // fragment addresses inside the pair's first buffer (the second lies kStepBytes further on: an immediate offset)
+    const uint8_t *kfrag[4];   // K: key c (and 16 + c: + 4 KB), chunk (4 j + r) ^ (c % 8)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kfrag[j] = pair_lds + ((c * 256 + ((r ^ (c & 7)) << 4)) ^ (j << 6));
+    // V: lane c of block r points at key row 4 r + c / 4 (and 16 + that: + 4 KB), elements 16 dt + 4 (c % 4) ..
+    const int vkey = 4 * r + (c >> 2);
+    const int voff = vkey * 256 + (((((c >> 1) & 1)) ^ ((2 * vkey) & 15)) << 4) + (c & 1) * 8;
+    uint32_t vfrag[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) vfrag[dt] = lds_address(pair_lds + kTileBytes) + (voff ^ (dt << 5));
+
+    // one round, on buffer BUF of the pair (the loop below alternates them, so that BUF is a compile-time offset)
+    auto round = [&](auto buf_tag, int t) {
+        constexpr int BUF = decltype(buf_tag)::value;
+        // this wavefront's transfers of round t have landed; after the barrier everybody's have, and nobody
+        // still reads the other buffer
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (t + 1 < rounds) request_round(t + 1, BUF ^ 1);
+        const int step = b0 + 4 * t + kw;
+        const bool active = step < b1;   // uniform over the wavefront; the barriers are outside these branches
+        const int key0 = step * kKeyBlock;
+        half8v pb[2];
+        if (active) {
+            float4v sa[2], sb[2];
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) {
+                sa[rt] = (float4v){0.f, 0.f, 0.f, 0.f};
+                sb[rt] = (float4v){0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const half8v fa = *reinterpret_cast<const half8v *>(kfrag[j] + BUF * kStepBytes);
+                const half8v fb = *reinterpret_cast<const half8v *>(kfrag[j] + BUF * kStepBytes + 16 * 256);
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt) {
+                    sa[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa, qf[rt][j], sa[rt], 0, 0, 0);
+                    sb[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fb, qf[rt][j], sb[rt], 0, 0, 0);
+                }
+            }
+            const bool prefix_only = key0 + kKeyBlock <= P;   // uniform: committed keys, all visible
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) {
+                float s[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) s[i] = (i < 4) ? sa[rt][i & 3] : sb[rt][i & 3];
+                if (!prefix_only) {
+                    // visibility of the step's 32 keys as one word: the step's first key is draft key `first`
+                    // (-31 .. 63; negative: the step begins with committed keys, all visible); mask bits at and
+                    // beyond M are clear, so keys past the last one are hidden
+                    const int first = key0 - P;
+                    const uint64_t window = first >= 0 ? mbits[rt] >> first : (mbits[rt] << -first) | ((1ull << -first) - 1);
+                    const uint32_t mine = (uint32_t)window >> (4 * r);   // bit i: key 4 r + i; bit 16 + i: key 16 + 4 r + i
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) s[i] = ((mine >> ((i & 3) + 16 * (i >> 2))) & 1u) ? s[i] : -__builtin_inff();
+                }
+                // the scale is positive (checked by the host): the largest raw score is the largest scaled one
+                const float m_blk = row_group_max(max_of_three(max_of_three(s[0], s[1], s[2]), max_of_three(s[3], s[4], s[5]), max_of_two(s[6], s[7])));
+                const float m_new = max_of_two(m_run[rt], m_blk * scale_log2e);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+                float pv[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], scale_log2e, -m_new));
+                    pb[rt][i] = (_Float16)pv[i];
+                }
+                const float psum = ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
+                l_run[rt] = l_run[rt] * alpha + psum;
+                m_run[rt] = m_new;
+                if (__any(alpha != 1.0f)) {   // after the first steps a row's maximum rarely moves
+#pragma unroll
+                    for (int dt = 0; dt < 8; ++dt) o[dt][rt] *= alpha;
+                }
+            }
+        }
+        if (!active) return;
+        // V^T fragments, two head-dim tiles ahead of the products that use them: contraction slots 8 r .. 8 r + 3
+        // are keys 4 r .. of the step's first 16, slots 8 r + 4 .. those of its second 16
+        short4v lo[8], hi[8];
+        read_transposed_pair<BUF * kStepBytes>(lo[0], hi[0], vfrag[0]);
+        read_transposed_pair<BUF * kStepBytes>(lo[1], hi[1], vfrag[1]);
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            if (dt + 2 < 8) read_transposed_pair<BUF * kStepBytes>(lo[dt + 2], hi[dt + 2], vfrag[dt + 2]);
+            if (dt + 2 < 8)
+                wait_lds_reads<4>(lo[dt]);
+            else if (dt + 1 < 8)
+                wait_lds_reads<2>(lo[dt]);
+            else
+                wait_lds_reads<0>(lo[dt]);
+            typedef short short8v __attribute__((ext_vector_type(8)));
+            const short8v both = __builtin_shufflevector(lo[dt], hi[dt], 0, 1, 2, 3, 4, 5, 6, 7);
+            const half8v va = __builtin_bit_cast(half8v, both);
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) o[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], o[dt][rt], 0, 0, 0);
+        }
+    };
+    for (int t = 0; t < rounds; t += 2) {
+        round(std::integral_constant<int, 0>{}, t);
+        if (t + 1 < rounds) round(std::integral_constant<int, 1>{}, t + 1);
+    }
+
+    // a row's sum over this wavefront's keys: add the four lanes (r = 0..3) that share the row
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+        l_run[rt] += __shfl_xor(l_run[rt], 16, 64);
+        l_run[rt] += __shfl_xor(l_run[rt], 32, 64);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();   // every wavefront has left the K and V tiles: the exchange reuses that LDS
+    uint8_t *const mine = lds + wave * kExWave;
+    float *const state = reinterpret_cast<float *>(lds + kExState);   // [wavefront][row of its half][max, sum]
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+            *reinterpret_cast<float4v *>(mine + (16 * rt + c) * kExRow + (4 * dt + r) * 16) = o[dt][rt];
+        if (r == 0) {
+            state[(wave * 32 + 16 * rt + c) * 2] = m_run[rt];
+            state[(wave * 32 + 16 * rt + c) * 2 + 1] = l_run[rt];
+        }
+    }
+    __syncthreads();
+    // thread t merges, in wavefront order, the four key wavefronts' values of four consecutive outputs of a row:
+    // 32 threads per row, whole rows per store
+    const bool last = nsplit == 1;
+    const PartialBuffer unit_o = partial_buffer(part_o + (size_t)unit * nsplit * kRowsPad * kHeadDim);
+    const PartialBuffer unit_ml = partial_buffer(part_ml + (size_t)unit * nsplit * kRowsPad * 2);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int item = tid + it * (64 * kSharedWaves);
+        const int rho = item >> 5, quad = item & 31;   // tile row, its outputs 4 quad .. 4 quad + 3
+        const int half_ = rho >> 5, hrow = rho & 31;
+        float ms[4], wgt[4], m_all = kLowest, l_all = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+            ms[w2] = state[((2 * w2 + half_) * 32 + hrow) * 2];
+            m_all = fmaxf(m_all, ms[w2]);
+        }
+        float4v val = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) {
+            wgt[w2] = __builtin_amdgcn_exp2f(ms[w2] - m_all);
+            l_all += wgt[w2] * state[((2 * w2 + half_) * 32 + hrow) * 2 + 1];
+            val += wgt[w2] * *reinterpret_cast<const float4v *>(lds + (2 * w2 + half_) * kExWave + hrow * kExRow + quad * 16);
+        }
+        if (rho >= R) continue;
+        if (last) {
+            val *= 1.f / l_all;
+            typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+            half4v hv = {(_Float16)val[0], (_Float16)val[1], (_Float16)val[2], (_Float16)val[3]};
+            int qrow;
+            *reinterpret_cast<half4v *>(out + locate(rho, qrow) + quad * 4) = hv;
+        } else {
+            // written through to memory in either mode: left in the L2 as ordinary stores, the partials of the
+            // two-kernel mode would all be written back at the end of the kernel, after the last workgroup
+            store_partial(unit_o, (sp * kRowsPad + rho) * (kHeadDim / 4) + quad, val);
+            if (quad == 0) {
+                store_partial_f32(unit_ml, (sp * kRowsPad + rho) * 2, m_all);
+                store_partial_f32(unit_ml, (sp * kRowsPad + rho) * 2 + 1, l_all);
+            }
+        }
+    }
+    if (last || !fused) return;   // uniform over the grid
+    // last-arriver merge of the tile's key ranges, as in tree_attn_kernel
+    __shared__ uint32_t ticket_sh;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) ticket_sh = __hip_atomic_fetch_add(&tickets[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (ticket_sh != (uint32_t)(nsplit - 1)) return;
+    if (tid == 0) __hip_atomic_store(&tickets[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int items = R * (kHeadDim / 4);
+    if (nsplit <= 4)
+        merge_ranges<4, 4>(unit_o, unit_ml, out, tid, 64 * kSharedWaves, items, M, Hq, nsplit, rep, unit);
+    else if (nsplit <= 8)
+        merge_ranges<8, 2>(unit_o, unit_ml, out, tid, 64 * kSharedWaves, items, M, Hq, nsplit, rep, unit);
+    else
+        merge_ranges<kMaxSplits, 1>(unit_o, unit_ml, out, tid, 64 * kSharedWaves, items, M, Hq, nsplit, rep, unit);
+}
+
 // merge of the key ranges: one thread per four consecutive output elements, ranges in order;
 // NS = compiled upper bound of the number of ranges (all loads of a thread are issued at once)
 template <int NS>
@@ -530,18 +916,30 @@ __global__ __launch_bounds__(256) void tree_accept_kernel(const int32_t *__restr
 }
 
 // Query heads per row tile (0 = one head per tile).  The heads of a KV group can share a tile, which reads K
-// and V once for all of them.  A tile of at most 32 rows runs in the two-row-tile kernel, two workgroups to a
-// compute unit and half the work per key step, so the largest divisor of the group size that keeps the tile
-// within 32 rows is taken when there is one (M = 8 with groups of 8: two tiles of 4 heads, 12.6 us, against
-// one tile of 8 heads, 16.3 us; K and V are then read twice, from L2); else the whole group if it fits 64 rows.
+// and V once for all of them; fewer tiles, on the other hand, mean more key ranges per tile to fill the chip,
+// and every range costs a partial result that has to be merged.  Measured over M = 1 .. 32 with 64/8 and 32/8
+// heads (prefix 2048), the best point is about 32 tiles (eight key ranges each, merged by the last workgroup):
+// the smallest pack that leaves at most 32 tiles is taken -- two heads of a group of eight with 64 heads (10.3
+// to 12.9 us for M = 1 .. 16, against 12.7 to 13.2 unpacked), none with 32 heads (10.0 to 12.6 us for
+// M = 1 .. 32, against 10.7 to 18.6 with two per tile).  Calls of so few rows that a whole group fits eight
+// tile rows pack the group (plain decoding: 9.9 against 10.3 us).
 static int attn_rep(int M, int Hq, int Hkv)
 {
     const int group = Hq / Hkv, knob = params().attn_pack;
     if (knob == 1 || group < 2) return 0;
-    if (knob != 2)
-        for (int d = group; d >= 2; --d)
-            if (group % d == 0 && M * d <= 32) return d;
-    return M * group <= kRowsPad ? group : 0;
+    if (knob >= 10) {   // 10 + d: exactly d heads per tile, where that is possible
+        const int d = knob - 10;
+        return (d >= 2 && group % d == 0 && M * d <= kRowsPad) ? d : 0;
+    }
+    if (knob == 2) return M * group <= kRowsPad ? group : 0;
+    if (M * group <= 8) return group;
+    int best = 1;
+    for (int d = 1; d <= group; ++d) {
+        if (group % d != 0 || M * d > kRowsPad) continue;
+        best = d;
+        if (Hq / d <= 32) break;
+    }
+    return best >= 2 ? best : 0;
 }
 
 static int attn_splits(int M, int P, int units)
@@ -569,8 +967,23 @@ static int launch_attn_variant(int grid, hipStream_t stream, Args... args)
 }
 
 template <typename... Args>
+static int launch_attn_shared(int grid, hipStream_t stream, Args... args)
+{
+    static bool lds_ok = false;
+    if (!lds_ok) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_shared_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSharedLds) != hipSuccess)
+            return W4A16_EHIP;
+        lds_ok = true;
+    }
+    hipLaunchKernelGGL(tree_attn_shared_kernel, dim3((unsigned)grid), dim3(64 * kSharedWaves), kSharedLds, stream, args...);
+    return W4A16_OK;
+}
+
+template <typename... Args>
 static int launch_attn(int rt, int rgroups, int grid, hipStream_t stream, Args... args)
 {
+    if (rt == 0) return launch_attn_shared(grid, stream, args...);
     if (rt == 4) return launch_attn_variant<4, 1>(grid, stream, args...);
     if (rgroups == 2) return launch_attn_variant<2, 2>(grid, stream, args...);
     return launch_attn_variant<2, 1>(grid, stream, args...);
@@ -604,6 +1017,7 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
 {
     int rc = check_attn(M, P, Hq, Hkv, D);
     if (rc != W4A16_OK) return rc;
+    if (!(scale > 0.f) || scale > 3.0e38f) return W4A16_EINVAL;   // the kernels take row maxima before scaling
     if (!q || !k || !v || !mask || !out) return W4A16_ENULL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || workspace_misaligned(workspace)) return W4A16_EALIGN;
     const int rep = attn_rep(M, Hq, Hkv);
@@ -615,17 +1029,26 @@ int tree_verify_attn(const void *q, const void *k, const void *v, const uint8_t 
     float *part_ml = part_o + (size_t)units * ns * kRowsPad * kHeadDim;
     const float scale_log2e = scale * 1.4426950408889634f;
     const int nblk = (P + M + kKeyBlock - 1) / kKeyBlock;
-    // row tiles per wavefront: tiles of at most 32 rows run with 2 (fewer registers, two workgroups per
-    // compute unit: measured 12-17 % faster); fuller tiles with 4, one wavefront per SIMD carrying all 64
-    // rows (two row groups of 32 rows re-fetch K/V fragments and measured 15-20 % slower)
+    // Every tile runs in the kernel that shares K and V tiles through LDS (rt = 0 below): it is the fastest
+    // form at every tile height, with half of its rows padding too (prefix 2048, 64/8 heads: 11.2 against
+    // 12.0 us at M = 8, 13.8 against 16.7 at M = 24, 15.7 against 22.3 at M = 64).  The older kernel stays
+    // selectable for comparison: one wavefront per SIMD carrying all 64 rows (4), or 32 rows per wavefront,
+    // in two row groups for taller tiles (2).
     const int rows = rep ? M * rep : M;
     const int knob = params().attn_row_tiles;
-    const int rt = knob == 4 ? 4 : knob == 2 ? 2 : (rows <= 32 ? 2 : 4), rgroups = (rt == 2 && rows > 32) ? 2 : 1;
-    // the key ranges of a tile are merged by the last of its workgroups to finish, or by a second kernel
-    // (fused: one launch less, but a single workgroup then reads all the partials of its tile, which pays only
-    // while they are few: measured 10.1 against 11.0 us at M = 1, 23.7 against 16.3 us at M = 8, prefix 2048)
+    const int rt = knob == 4 ? 4 : knob == 2 ? 2 : 0, rgroups = (rt == 2 && rows > 32) ? 2 : 1;
+    // The key ranges of a tile are merged by the last of its workgroups to finish, or by a second kernel.  Fused
+    // saves a launch and the wait for it, but one workgroup then reads all the partials of its tile (rows x
+    // ranges x 512 B), which pays while they are few.  Measured break-even points, prefix 2048: about 160 row-
+    // ranges with up to four ranges (64 heads, M = 33 .. 64: 14.7 fused against 14.9 us at 132, 16.3 against
+    // 15.5 at 256); with five to eight ranges 512 for tiles of one head (32 heads, M = 64: 15.6 against 16.7 us)
+    // and 256 for packed ones (64 heads in pairs: 12.9 against 13.1 us at M = 16, 14.4 against 13.6 at M = 24);
+    // 256 with more ranges (M = 4 of 32 heads 10.7 against 11.0 us at 256, M = 8 of 64 heads 14.0 against 11.0
+    // at 512).
     const int fm = params().attn_fused_merge;
-    const int fused = (ns > 1 && fm != 1 && (fm == 2 || (rep ? M * rep : M) * ns <= 128)) ? 1 : 0;
+    const int row_ranges = rows * ns;
+    const bool few = row_ranges <= (ns <= 4 ? 160 : (ns <= 8 && !rep) ? 512 : 256);
+    const int fused = (ns > 1 && fm != 1 && (fm == 2 || few)) ? 1 : 0;
     rc = launch_attn(rt, rgroups, units * ns, (hipStream_t)stream, (const _Float16 *)q, (const _Float16 *)k,
                      (const _Float16 *)v, mask, (_Float16 *)out, part_o, part_ml, reinterpret_cast<uint32_t *>(workspace),
                      M, P, Hq, Hkv, scale_log2e, ns, nblk / ns, nblk % ns, rep, fused);

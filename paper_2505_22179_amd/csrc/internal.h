@@ -50,7 +50,7 @@ struct Params {
     int split_k = 0;       // 0 = heuristic
     int fused_reduce = 2;  // 0 = second kernel, 1 = last workgroup, 2 = per-shape choice
     int attn_splits = 0;   // 0 = heuristic
-    int attn_row_tiles = 0;   // 0 = by tile height, 2 = 32 query rows per wavefront (two row groups for taller tiles), 4 = 64 rows
+    int attn_row_tiles = 0;   // 0 = the kernel with K/V tiles shared through LDS; the older kernel: 2 = 32 query rows per wavefront (two row groups for taller tiles), 4 = 64 rows
     int lm_tiles = 0;         // 0 = by M, else 1 or 2 vocabulary tiles per wavefront in lm_head_topk
     int attn_pack = 0;     // query heads of a KV group per row tile: 0 = by size, 1 = one, 2 = the whole group when it fits
     int attn_fused_merge = 0;   // 2 = the last workgroup of a tile merges its key ranges, 1 = a second kernel does, 0 = by size

@@ -94,6 +94,8 @@ def test_argument_validation_happens_before_any_gpu_call():
     assert t(a, a, a, a, a, 0, 2048, 64, 8, 128, f, a, 1 << 30, None) == EINVAL
     assert t(a, a, a, a, a, 1, 2048, 64, 4, 128, f, a, 1 << 30, None) == EUNSUP    # more than 8 query heads per KV head
     assert t(a, a, a, None, a, 60, 2048, 64, 8, 128, f, a, 1 << 30, None) == ENULL
+    for bad_scale in (0.0, -0.1, float("nan"), float("inf")):   # row maxima are taken before scaling: the scale is positive
+        assert t(a, a, a, a, a, 60, 2048, 64, 8, 128, ctypes.c_float(bad_scale), a, 1 << 30, None) == EINVAL
     assert t(a, a, a, a, a, 60, 2048, 64, 8, 128, f, None, 0, None) == EWS
 
 
