@@ -407,31 +407,48 @@ def time_steps(fn, steps: int, warmup: int, use_graph: bool, copies: int, stats:
 
 
 def gpu_clocks():
-    """Clock readings of the GPU from rocm-smi (clocks cannot be fixed from user space: recorded, not set);
-    None when the tool is not there or prints nothing usable."""
+    """Current clock levels of GPU 0 as the amdgpu driver reports them in sysfs (the starred line of pp_dpm_sclk /
+    pp_dpm_mclk).  Clocks cannot be fixed from user space: recorded, not set.  Plain file reads, no child process
+    (this runs after the GPU has been initialised); None where the files are not there."""
+    import glob
     import re
-    import shutil
-    import subprocess
-    tool = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
-    try:
-        out = subprocess.run([tool, "--showclocks"], capture_output=True, text=True, timeout=20).stdout
-    except (OSError, subprocess.SubprocessError):
-        return None
     clocks = {}
-    for line in out.splitlines():
-        m = re.search(r"GPU\[(\d+)\]\s*:\s*(\w+) clock level:\s*\S+\s*\((\d+)\s*Mhz\)", line, flags=re.I)
-        if m and m.group(1) == "0":
-            clocks[m.group(2).lower() + "_mhz"] = int(m.group(3))
+    for card in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        for key, name in (("sclk_mhz", "pp_dpm_sclk"), ("mclk_mhz", "pp_dpm_mclk")):
+            try:
+                lines = open(os.path.join(card, name)).read().splitlines()
+            except OSError:
+                continue
+            for line in lines:
+                m = re.match(r"\s*\d+:\s*(\d+)\s*mhz\s*\*", line, flags=re.I)
+                if m:
+                    clocks[key] = int(m.group(1))
+        if clocks:
+            break
     return clocks or None
 
 
+TRAFFIC_PROFILE = os.path.join("profiles", "w4a16_gemm_llama70b_hbm_traffic_m1_m8_m64.txt")
+GEMM_SOURCES = ("gemm.hip", "tuned_plans.inc", "tuned_flat.inc", "layout.h")
+
+
 def measured_traffic():
-    """HBM bytes per gate_up launch from the committed rocprofv3 PMC summary (FETCH_SIZE and
-    WRITE_SIZE runs, calibrated against a copy kernel of known size); None if it is not there."""
-    path = os.path.join(ROOT, "profiles", "w4a16_gemm_llama70b_m1_hbm_traffic.txt")
+    """HBM bytes per gate_up launch (fetched + written) at M = 1, 8 and 64 from the committed rocprofv3 PMC summary
+    (FETCH_SIZE and WRITE_SIZE runs, calibrated against the runtime's copy kernel on buffers of known size) --
+    but only while that summary describes the kernels that run: it records a hash of the GEMM sources, and when
+    they have changed since (or the file is not there) there is no measured figure and None is returned."""
+    import hashlib
     try:
-        vals = dict(ln.strip().split("=") for ln in open(path) if "_BYTES_PER_LAUNCH_GATE_UP_M1=" in ln)
-        return int(vals["FETCH_BYTES_PER_LAUNCH_GATE_UP_M1"]) + int(vals["WRITE_BYTES_PER_LAUNCH_GATE_UP_M1"])
+        vals = dict(ln.strip().split("=", 1) for ln in open(os.path.join(ROOT, TRAFFIC_PROFILE)) if "=" in ln and ln[0].isupper())
+        h = hashlib.sha256()
+        for name in GEMM_SOURCES:
+            h.update(open(os.path.join(ROOT, "paper_2505_22179_amd", "csrc", name), "rb").read())
+        if vals["GEMM_SOURCES_SHA256_16"] != h.hexdigest()[:16]:
+            return None
+        out = {f"M{M}": int(vals[f"FETCH_BYTES_PER_LAUNCH_GATE_UP_M{M}"]) + int(vals[f"WRITE_BYTES_PER_LAUNCH_GATE_UP_M{M}"])
+               for M in (1, 8, 64)}
+        out["source"] = {"profile": TRAFFIC_PROFILE, "commit": vals.get("SOURCE_COMMIT")}
+        return out
     except (OSError, KeyError, ValueError):
         return None
 
@@ -499,6 +516,8 @@ def main():
     ap.add_argument("--quick-m", type=int, default=1,
                     help="with --quick: run at this M instead of 1 (profiler runs at other token counts; not the headline)")
     ap.add_argument("--lm-head-only", action="store_true", help="time only the draft-side LM head (profiler runs)")
+    ap.add_argument("--attn-only", type=int, default=0, metavar="M",
+                    help="time only tree_verify_attn at this M (64/8 heads, prefix 2048; profiler runs)")
     ap.add_argument("--decoder-layer-only", type=int, default=0, metavar="M",
                     help="time only the whole decoder layer at this M (profiler runs; prints that one figure)")
     args = ap.parse_args()
@@ -513,6 +532,17 @@ def main():
 
     if args.lm_head_only:
         print(json.dumps({"metric": "draft-side fp16 LM head + top-10, V = 128256", "lm_head_topk_V128256": lm_head_leg(args, use_graph)}))
+        return
+    if args.attn_only:
+        a = I.make_attn(I.seed_for(5, 0), M=args.attn_only, tree="random" if args.attn_only > 6 else "chain")
+        q, mask = torch.from_numpy(a.q).cuda(), torch.from_numpy(a.mask).cuda()
+        out = torch.empty_like(q)
+        k0, v0 = torch.from_numpy(a.k).cuda(), torch.from_numpy(a.v).cuda()
+        ks, vs = [k0.clone() for _ in range(64)], [v0.clone() for _ in range(64)]   # 552 MB: never cache-served
+        aws = B.new_workspace(B.tree_verify_attn_workspace_bytes(a.M, a.P, a.Hq, a.Hkv, a.D))
+        ms = time_steps(lambda c: B.tree_verify_attn(q, ks[c % 64], vs[c % 64], mask, out, a.M, a.P, a.Hq, a.Hkv, a.D, a.scale, aws),
+                        args.steps, args.warmup, use_graph, 64)
+        print(json.dumps({"metric": "us per tree_verify_attn call (64/8 heads, head dim 128, prefix 2048)", "M": a.M, "value": ms * 1e3, "unit": "us"}))
         return
     big = Layer(I.LLAMA3_70B, args.copies, seed=70)
     log("70B layer packed")
@@ -561,8 +591,10 @@ def main():
                         args.steps, args.warmup, use_graph, nc)
         plain[name] = {"us": ms * 1e3, "GBps": nbytes / ms / 1e6}
         log(f"70B {name} plain read of the packed buffer: {ms * 1e3:.2f} us  {nbytes / ms / 1e6:.0f} GB/s")
+    traffic = measured_traffic()
     roofline = {"bound": "hbm", "achieved": gu["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": gu["GBps"] / HBM_PEAK_GBPS, "traffic": measured_traffic(),
+                "frac": gu["GBps"] / HBM_PEAK_GBPS, "traffic": traffic and traffic.get(f"M{hm}"),
+                "traffic_M64": traffic and traffic["M64"], "traffic_source": traffic and traffic["source"],
                 "plain_read_GBps": plain["gate_up"]["GBps"], "frac_of_plain_read": gu["GBps"] / plain["gate_up"]["GBps"],
                 "kernel": f"the GEMM kernel of 70B gate_up (K=8192, N=57344, M={hm})",
                 "algorithmic_bytes_per_launch": weight_bytes(8192, 57344), "us_per_launch": gu["us"]}
