@@ -311,11 +311,13 @@ int lm_head_topk(const void *x, const void *packed, int M, int V, int K, int top
  * K / 128 == split_k * waves_per_wg * flat_groups); a combination that is not compiled, or that
  * does not fit the shape, makes w4a16_gemm return W4A16_EUNSUP,
  * "attn_splits" (0 = heuristic, else the number of key ranges per row tile in tree_verify_attn),
- * "attn_pack" (how many query heads of a KV group share a row tile of tree_verify_attn: 0 = as many as keep
- * the tile within 32 rows when that is two or more, else the whole group if it fits 64 rows, else one;
- * 1 = one tile per query head always; 2 = the whole group whenever it fits 64 rows), "attn_row_tiles" (0 = chosen by the
- * number of rows in a tile; 2 = a wavefront of tree_verify_attn carries 32 query rows, in two row groups
- * for taller tiles; 4 = 64 rows, one wavefront per SIMD), "attn_fused_merge" (how the key ranges of a
+ * "attn_pack" (how many query heads of a KV group share a row tile of tree_verify_attn: 0 = the measured
+ * rule -- the whole group when it fits 8 tile rows, else the fewest heads that leave at most 32 tiles;
+ * 1 = one tile per query head always; 2 = the whole group whenever it fits 64 rows; 10 + d = exactly d heads
+ * where d divides the group and the tile fits 64 rows, else one), "attn_row_tiles" (which kernel of
+ * tree_verify_attn runs: 0 = the one that shares K and V tiles through LDS; the older one, kept for comparison:
+ * 2 = a wavefront carries 32 query rows, in two row groups for taller tiles; 4 = 64 rows, one wavefront
+ * per SIMD), "attn_fused_merge" (how the key ranges of a
  * row tile are merged: 2 = by the last of its workgroups to finish, 1 = by a second kernel, 0 = the former while
  * rows x ranges of a tile stay small), "lm_tiles" (0 = heuristic, else 1, 2 or
  * -- for more than 16 rows -- 4 vocabulary tiles per wavefront in lm_head_topk).

@@ -563,7 +563,7 @@ __global__ __launch_bounds__(64 * kSharedWaves) void tree_attn_shared_kernel(
     // transfers: lane l of transfer i fills bytes 16 (l % 16) .. of tile row 4 i + l / 16
     const int trow = lane >> 4, tchunk = lane & 15;
     // LDS: per key wavefront pair 32 KB = two buffers of (K tile, V tile); Q sits in pair 0's second buffer until
-    // that pair requests its round 1
+    // that pair requests the tiles of its second round
     uint8_t *const pair_lds = lds + kw * (2 * kStepBytes);
     uint8_t *const qtile = lds + kStepBytes;
 #pragma unroll
