@@ -252,7 +252,7 @@ def w4a16_read_probe(buf, nbytes: int, sink) -> None:
 
 
 PLAN_FIELDS = ("family", "row_tiles", "tiles_per_wave", "waves_or_k_sets", "depth_or_groups", "split_k", "fused_reduce",
-               "symmetric")
+               "has_symmetric_variant")
 
 
 def w4a16_plan_describe(M: int, N: int, K: int, G: int = 128) -> tuple:
