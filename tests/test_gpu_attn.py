@@ -109,3 +109,27 @@ def test_masked_draft_keys_have_no_influence():
     for i in range(a.M):
         same = np.array_equal(pert[i].view(np.uint16), base[i].view(np.uint16))
         assert same == (a.mask[i, j] == 0), i
+
+
+@pytest.mark.parametrize("gain", [6.0, 24.0])
+def test_peaked_softmax(gain):
+    """queries scaled up so that a handful of keys carry each row (logit spread of tens): the running-maximum
+    rescaling across key steps, key ranges and the merge has to hold where exp() spans its whole range"""
+    a = I.make_attn(8300 + int(gain), 60, 700, 16, 2, 128)
+    a.q = (a.q.astype(np.float32) * gain).astype(np.float16)
+    ref64, _ = R.tree_verify_attn(a.q, a.k, a.v, a.mask, a.scale)
+    for splits in (0, 1, 5):
+        B.w4a16_set_param("attn_splits", splits)
+        for row_tiles in (0, 2):
+            B.w4a16_set_param("attn_row_tiles", row_tiles)
+            check(run_attn(a), ref64, f"peaked softmax x{gain} splits={splits} row_tiles={row_tiles}")
+
+
+def test_constant_values_come_back_exactly():
+    """V = c for every key: any convex combination of it is c, whatever the weights"""
+    a = I.make_attn(8400, 33, 515, 8, 2, 128)
+    a.v[...] = np.float16(0.375)
+    for splits in (0, 4):
+        B.w4a16_set_param("attn_splits", splits)
+        got = run_attn(a).astype(np.float32)
+        assert np.abs(got - 0.375).max() <= 2.0 ** -11 * 0.375 * 2, np.abs(got - 0.375).max()
