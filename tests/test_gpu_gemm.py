@@ -275,3 +275,41 @@ def test_workspace_too_small_is_rejected():
     with pytest.raises(B.W4A16Error) as e:
         B.w4a16_gemm(x, packed, y, 1, 4096, 4096, 128, tiny)
     assert e.value.code == -5
+
+
+@pytest.mark.parametrize("M", [1, 4, 16, 32])
+def test_tiny_activations_stay_within_the_documented_absolute_error(M, big_ws):
+    """x ~ N(0, 1e-4^2): below 2^-10 the one-row-tile kernels round half of the x elements to multiples of 2^-20
+    (the header states it); the error stays absolute -- a few 1e-6 -- and the many-row kernels are unaffected"""
+    K, N = 4096, 1024
+    inp = I.make_linear(4321 + M, M, K, N)
+    inp.x = (np.random.default_rng(99).standard_normal((M, K)) * 1e-4).astype(np.float16)
+    packed = B.pack_from_numpy(inp)
+    got = run_gemm(inp, packed, big_ws).astype(np.float64)
+    y32, _, _ = R.matmul(inp.x, R.dequant(inp.qweight, inp.scales, inp.qzeros, 128), want64=False)
+    err = np.abs(got - y32).max()
+    rel = np.linalg.norm(got - y32) / np.linalg.norm(y32)
+    print(f"tiny x, M={M}: max abs err {err:.3g}, rel fro {rel:.3g}", flush=True)
+    # 2^-21 per element over half of K elements, times |q - z| s <= 15 * 1e-2, as a random walk: ~ 1e-6; bound with room
+    assert err <= 1e-5
+    assert rel <= (5e-3 if M <= 16 else 3e-4)
+
+
+@pytest.mark.parametrize("M", [1, 16, 32, 64])
+def test_large_activations(M, big_ws):
+    """x ~ N(0, 500^2), outputs in the thousands: the relative criterion applies (half an fp16 ulp of such a y is
+    already above 1e-2).  Element by element: half an ulp of the rounding plus the fp32 accumulation noise, which
+    scales with the row (in the one-row-tile kernels the cancelled code bias costs about ten bits of it)"""
+    K, N = 4096, 1024
+    inp = I.make_linear(4400 + M, M, K, N)
+    inp.x = (np.random.default_rng(7).standard_normal((M, K)) * 500.0).astype(np.float16)
+    packed = B.pack_from_numpy(inp)
+    got = run_gemm(inp, packed, big_ws).astype(np.float64)
+    y32, _, _ = R.matmul(inp.x, R.dequant(inp.qweight, inp.scales, inp.qzeros, 128), want64=False)
+    assert np.isfinite(got).all()
+    rel = np.linalg.norm(got - y32) / np.linalg.norm(y32)
+    ulp = np.spacing(np.abs(y32).astype(np.float16)).astype(np.float64)
+    rms = np.sqrt((y32.astype(np.float64) ** 2).mean(axis=1, keepdims=True))
+    excess = (np.abs(got - y32) - 0.5 * ulp) / rms
+    print(f"large x, M={M}: rel fro {rel:.3g}, error beyond half an ulp {excess.max():.3g} of the row rms", flush=True)
+    assert rel <= 3e-4 and excess.max() <= 5e-4
