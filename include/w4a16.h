@@ -89,12 +89,8 @@ int w4a16_dequant(const void *packed, float *W, int N, int K, int G, void *strea
  * analysis of section 3 for the values of M).  1 <= M <= 64; rows >= M of x and y are never
  * touched; y is overwritten.  `workspace` must hold w4a16_workspace_bytes(M, N, K, G) bytes and
  * have been initialised with w4a16_workspace_init.
- * Range of x: for M <= 16 half of the x elements reach the matrix instruction as x / 16 in fp16, which is
- * exact for |x| >= 2^-10 and otherwise rounds x to a multiple of 2^-20 -- an absolute error of at most
- * 2^-21 per element, far inside the tolerance for activations of ordinary size (about 2e-6 in y at K = 4096),
- * but rows whose entries are ALL tiny lose relative accuracy (relative Frobenius error 8e-4 for x ~ N(0, 3e-4^2),
- * 2e-3 for N(0, 1e-4^2); 2e-4, the rounding of y alone, from N(0, 1e-3^2) on).  The kernels for M > 16 have no
- * such step.  Large activations are no special case: products and sums are fp32 throughout. */
+ * No restriction on the size of the activations: every operand of the matrix instruction is exact in fp16
+ * and products and sums are fp32, so rows of tiny or of large entries keep the same relative accuracy. */
 int w4a16_gemm(const void *x, const void *packed, void *y, int M, int N, int K, int G,
                void *workspace, size_t workspace_bytes, void *stream);
 

@@ -46,12 +46,14 @@ struct DequantConsts {
     uint32_t magic;     // 0x6400 in both halves: fp16 1024
     uint32_t mask_lo;   // 0x000F000F
     uint32_t mask_hi;   // 0x00F000F0
+    uint32_t magic64;   // 0x5400 in both halves: fp16 64, whose mantissa bits 4..7 count in ones
 };
 
 __device__ __forceinline__ DequantConsts dequant_consts()
 {
-    DequantConsts k = {0x64006400u, 0x000F000Fu, 0x00F000F0u};
+    DequantConsts k = {0x64006400u, 0x000F000Fu, 0x00F000F0u, 0x54005400u};
     asm volatile("" : "+v"(k.magic));    // opaque to constant propagation: stays in a VGPR
+    asm volatile("" : "+v"(k.magic64));
     asm volatile("" : "+s"(k.mask_lo));  // stay in SGPRs
     asm volatile("" : "+s"(k.mask_hi));
     return k;
@@ -154,23 +156,23 @@ __device__ __forceinline__ void dequant_tile(half8v (&b)[4], const u32x4 &w, con
 // ---- offset-code arithmetic for one row tile (M <= 16) ------------------------------------------
 // With few rows the vector ALU, not the matrix pipe, is the scarce unit, and two thirds of its work
 // per weight is turning the biased code into (q - z).  Here the second operand keeps the bias:
-// 0x6400 | q is 1024 + q in the low-nibble positions and 0x6400 | (q << 4) is 1024 + 16 q in the
-// high-nibble ones, where the x fragment carries x / 16 instead of x (exact in fp16 but for the
-// lowest subnormal bits).  Writing a' for that fragment, one group and one column give
-//     T = sum_k a'_k b_k = sum_k x_k q_k + 1024 sum_k a'_k,
-// so with C = 1024 sum_k a'_k and X = sum_k x_k (two more products of the same fragment with
+// 0x6400 | q is 1024 + q in the low-nibble positions, and in the high-nibble ones, where the code
+// sits four bits up, 0x5400 | (q << 4) is 64 + q (one unit of those mantissa bits of 64 is 1).  With
+// the bias B_k (1024 or 64) of position k, one group and one column give
+//     T = sum_k x_k b_k = sum_k x_k q_k + sum_k B_k x_k,
+// so with C = sum_k B_k x_k and X = sum_k x_k (two more products of the same fragment with
 // constant operands, shared by all column tiles) the group's term is s (T - C - z X).  T - C is
-// formed inside the matrix pipe by starting the accumulation from -C.  All sums are fp32: inputs
-// whose products are exact stay exact; otherwise the cancellation of the 1024 bias costs about ten
-// bits of the fp32 significand in each group's term, which leaves it far more precise than the
-// fp16 result.
+// formed inside the matrix pipe by starting the accumulation from -C.  Every operand is exact in
+// fp16 and all sums are fp32: inputs whose products are exact stay exact; otherwise the
+// cancellation of the bias costs up to ten bits of the fp32 significand in each group's term, which
+// leaves it far more precise than the fp16 result.
 constexpr bool kOffsetCodes = true;   // one-row-tile kernels use the arithmetic above
 
 __device__ __forceinline__ half8v offset8(uint32_t w, const DequantConsts &k)
 {
     const uint32_t w2 = w >> 8;
-    const u32x4 v = {(w & k.mask_lo) | k.magic, (w & k.mask_hi) | k.magic, (w2 & k.mask_lo) | k.magic,
-                     (w2 & k.mask_hi) | k.magic};
+    const u32x4 v = {(w & k.mask_lo) | k.magic, (w & k.mask_hi) | k.magic64, (w2 & k.mask_lo) | k.magic,
+                     (w2 & k.mask_hi) | k.magic64};
     return __builtin_bit_cast(half8v, v);
 }
 
@@ -180,20 +182,12 @@ __device__ __forceinline__ void offset_tile(half8v (&b)[4], const u32x4 &w, cons
     for (int j = 0; j < 4; ++j) b[j] = offset8(w[j], magic);
 }
 
-// x fragment -> a': the four values that meet high-nibble codes (halves 2, 3, 6, 7) are divided by 16
-__device__ __forceinline__ void prescale_fragment(u32x4 &a)
-{
-    const half2v sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
-    a[1] = __builtin_bit_cast(uint32_t, as_h2(a[1]) * sixteenth);
-    a[3] = __builtin_bit_cast(uint32_t, as_h2(a[3]) * sixteenth);
-}
-
 // -C and X of one group for MT row tiles (every column of the result holds the same value)
 template <int MT>
 __device__ __forceinline__ void group_sums(const u32x4 (&a)[MT][4], float4v (&negc)[MT], float4v (&xs)[MT])
 {
-    const u32x4 bias = {0xE400E400u, 0xE400E400u, 0xE400E400u, 0xE400E400u};     // -1024 everywhere
-    const u32x4 ones = {0x3C003C00u, 0x4C004C00u, 0x3C003C00u, 0x4C004C00u};     // 1 or 16: undoes the / 16
+    const u32x4 bias = {0xE400E400u, 0xD400D400u, 0xE400E400u, 0xD400D400u};     // -1024 or -64: the position's bias
+    const u32x4 ones = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         negc[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
@@ -208,14 +202,14 @@ __device__ __forceinline__ void group_sums(const u32x4 (&a)[MT][4], float4v (&ne
     }
 }
 
-// Symmetric weights: z = 8 everywhere, so -C and -8 X are one sum over the same fragment, with -(1024 + 8) where
-// the fragment carries x and -(1024 + 128) where it carries x / 16 (both exact in fp16).  Started from it, the
+// Symmetric weights: z = 8 everywhere, so -C and -8 X are one sum over the same fragment, with -(1024 + 8) at the
+// low-nibble positions and -(64 + 8) at the high-nibble ones.  Started from it, the
 // matrix pipe leaves sum_k x_k (q_k - 8) and the fold is a plain multiply-add: four constant products per group
 // instead of eight, one fused multiply-add per live accumulator register instead of two.
 template <int MT>
 __device__ __forceinline__ void group_sums_symmetric(const u32x4 (&a)[MT][4], float4v (&negc)[MT])
 {
-    const u32x4 bias = {0xE408E408u, 0xE480E480u, 0xE408E408u, 0xE480E480u};     // -1032 or -1152
+    const u32x4 bias = {0xE408E408u, 0xD480D480u, 0xE408E408u, 0xD480D480u};     // -1032 or -72
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         negc[mt] = (float4v){0.f, 0.f, 0.f, 0.f};
@@ -266,10 +260,6 @@ __device__ __forceinline__ void compute_group(u32x4 (&a)[MT][4], const QuantWord
     const TileQuant<TW> qn = tile_quant<TW>(fn, t0);
     float4v negc[MT], xs[MT];
     if constexpr (OFF) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) prescale_fragment(a[mt][j]);
         if constexpr (SYM) group_sums_symmetric<MT>(a, negc);
         else group_sums<MT>(a, negc, xs);
     }
@@ -795,7 +785,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_flat_kernel(
     for (int l = 0; l < XL; ++l) {
         const int u = tid + kThreads * l, row = u / kRow16, col = u % kRow16;
         if (row < M) {
-            if constexpr (kOffsetCodes) prescale_fragment(xr[l]);
             xs[row * kRowStride16 + col] = xr[l];
         }
     }
