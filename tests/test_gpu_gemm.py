@@ -312,3 +312,25 @@ def test_large_activations(M, big_ws):
     excess = (np.abs(got - y32) - 0.5 * ulp) / rms
     print(f"large x, M={M}: rel fro {rel:.3g}, error beyond half an ulp {excess.max():.3g} of the row rms", flush=True)
     assert rel <= 3e-4 and excess.max() <= 5e-4
+
+
+@pytest.mark.parametrize("lo,hi", [(1e-7, 5e-5), (10.0, 200.0)])
+@pytest.mark.parametrize("M", [1, 16, 32, 64])
+def test_scale_extremes(M, lo, hi, big_ws):
+    """scales that are all subnormal in fp16, and scales in the hundreds: exact in the dequantisation export, and
+    the product as accurate as with the benchmark's scales (they enter as fp32 factors of fp32 group sums)"""
+    K, N = 4096, 1024
+    inp = I.make_linear(4500 + M, M, K, N)
+    inp.scales = np.random.default_rng(5).uniform(lo, hi, inp.scales.shape).astype(np.float16)
+    if hi > 1:
+        inp.x = (inp.x.astype(np.float32) * 0.01).astype(np.float16)   # keeps y inside the fp16 range
+    packed = B.pack_from_numpy(inp)
+    W = torch.empty((K, N), dtype=torch.float32, device=DEV)
+    B.w4a16_dequant(packed, W, N, K)
+    got = run_gemm(inp, packed, big_ws).astype(np.float64)
+    Wref = R.dequant(inp.qweight, inp.scales, inp.qzeros, 128)
+    assert np.array_equal(W.cpu().numpy().view(np.uint32), Wref.view(np.uint32))
+    y32, _, _ = R.matmul(inp.x, Wref, want64=False)
+    assert np.isfinite(got).all()
+    rel = np.linalg.norm(got - y32) / np.linalg.norm(y32)
+    assert rel <= 3e-4, rel
