@@ -59,6 +59,8 @@ CASES = [
     (3, 2, 12, 2, "chain"),          # fewer keys than one step
     (12, 300, 32, 4, "random"),      # groups of 8 heads, two heads per 24-row tile
     (7, 129, 12, 2, "chain"),        # groups of 6 heads: three per 21-row tile (42 rows would need the tall tile)
+    (8, 10001, 16, 2, "random"),     # long prefixes: many rounds per key range, a ragged last step
+    (3, 65536, 8, 8, "chain"),
 ]
 
 
