@@ -601,6 +601,16 @@ def main():
 
     extra = {}
     if not args.quick:
+        # cache-hot, labelled and never the headline: the same weight buffers every step.  One GEMM alone re-reads a
+        # buffer that fits the 256 MB last-level cache (all but gate_up: 244 MB); the layer's 445 MB do not fit
+        hot = {"note": "cache-hot: every step reads the SAME weight copy (the headline rotates copies); M = 1"}
+        for gi, (name, K, N) in enumerate(I.LLAMA3_70B):
+            ms = time_steps(lambda c, gi=gi: big.step(1, 0, only=gi), args.steps, args.warmup, use_graph, 1)
+            hot[name] = {"us": ms * 1e3, "GBps": weight_bytes(K, N) / ms / 1e6}
+        ms = time_steps(lambda c: big.step(1, 0), args.steps, args.warmup, use_graph, 1)
+        hot["layer"] = {"us": ms * 1e3, "GBps": big.bytes / ms / 1e6}
+        extra["llama3_70b_cache_hot_M1"] = hot
+        log("70B cache-hot M=1: " + ", ".join(f"{k} {v['us']:.1f} us" for k, v in hot.items() if k != "note"))
         # tree-verify step: attention at M = 60 over a 2048-token prefix, then the four linears at M = 60
         a = I.make_attn(I.seed_for(5, 0))
         q = torch.from_numpy(a.q).cuda()
