@@ -717,6 +717,8 @@ def main():
                                              "frac_of_hbm_peak": bytes70 / ms / 1e6 / HBM_PEAK_GBPS,
                                              "ratio_vs_M1": ms / ms1} for M, ms in sweep.items()}
         extra["llama3_70b_per_gemm"] = {str(M): d for M, d in per_gemm.items()}
+        extra["llama3_70b_per_gemm_ratio_M64_over_M1"] = {name: per_gemm[64][name]["us"] / per_gemm[1][name]["us"]
+                                                          for name in per_gemm[1]}
         extra["llama3_70b_plain_read"] = dict(plain, layer_us=sum(d["us"] for d in plain.values()),
                                               gemm_layer_over_plain_read=ms1 * 1e3 / sum(d["us"] for d in plain.values()))
         flops64 = sum(2.0 * 64 * K * N for (_, K, N) in I.LLAMA3_70B)
