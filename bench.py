@@ -330,6 +330,7 @@ def lm_head_leg(args, use_graph: bool) -> dict:
 
 
 REPEATS = 9   # timed regions per figure; the median is reported
+SETTLE_S = 0.06   # least duration of the untimed warm-up of a figure, whatever --warmup says
 MAX_GRAPH_STEPS = 512   # a timed region of up to this many steps is one HIP graph
 
 
@@ -390,6 +391,12 @@ def time_steps(fn, steps: int, warmup: int, use_graph: bool, copies: int, stats:
 
     run_warm()
     torch.cuda.synchronize()
+    # settle: for some 40 ms after set-up work (building weights, freeing and allocating buffers) and 15 ms after
+    # an idle gap the same graph runs up to 5 % slower; the untimed warm-up therefore lasts at least SETTLE_S
+    settle_until = time.perf_counter() + SETTLE_S
+    while time.perf_counter() < settle_until:
+        run_region()
+        torch.cuda.synchronize()
     times = []
     for _ in range(repeats):
         start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -737,7 +744,9 @@ def main():
                                "gate_up 8192->57344, down 28672->8192), W4A16 G=128, M=" + str(hm) + "; sweep M in {1,4,8,16,32,64}",
                    "weight_copies_rotated": args.copies, "hip_graph": use_graph, "device": dev},
         "frac_of_hbm_peak": value / HBM_PEAK_GBPS,
-        "timing": dict(sweep_stats[hm], note=f"median of {REPEATS} timed regions of exactly --steps steps each, HIP events on the launch stream"),
+        "timing": dict(sweep_stats[hm], note=f"median of {REPEATS} timed regions of exactly --steps steps each, HIP events on the launch stream; before them the same "
+                                               f"region runs untimed for --warmup steps and at least {SETTLE_S * 1e3:.0f} ms (the GPU is up to 5 % slower for "
+                                               f"some 40 ms after set-up work)"),
         "gpu_clocks": {"before": clocks_before, "after": gpu_clocks()},
         "roofline": roofline,
     }
